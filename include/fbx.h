@@ -1,0 +1,183 @@
+/*
+ * fbx.h — C ABI of the MI355X feature-extraction library (libfbx.so).
+ *
+ * The library evaluates a fixed collection of per-feature operators on every
+ * record of a batch of raw, tab-separated log records and returns, per emitted
+ * slot, the 64-bit feature signs in record order (CSR: values + offsets).  This
+ * is the "Extract features" stage of the paper (Section 3): operators are
+ * collected, their dependencies resolved and their order fixed before the run
+ * (Section 4, "Scheduling" and "Inner-GPU operator launching"), then executed
+ * layer by layer on the GPU with dynamic memory taken from a pre-allocated pool
+ * (Section 5).
+ *
+ * Conventions
+ *   - Every call returns an fbx_status; nothing throws across this boundary.
+ *   - "HOST" / "DEVICE" on a pointer says which memory it must point to.
+ *   - The library never allocates device memory: all device storage (tables,
+ *     scratch, results) lives in the workspace the caller hands over.
+ *   - A plan is not thread-safe; distinct plans are independent.
+ */
+#ifndef FBX_H
+#define FBX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fbx_plan fbx_plan; /* opaque, host-owned */
+
+typedef enum {
+  FBX_OK = 0,
+  FBX_E_ARG = -1,   /* NULL or inconsistent argument                         */
+  FBX_E_SPEC = -2,  /* operator-DAG spec rejected (see fbx_last_error)        */
+  FBX_E_NOMEM = -3, /* workspace too small; required size reported            */
+  FBX_E_INPUT = -4, /* record offsets decreasing / outside raw_len / too long */
+  FBX_E_HIP = -5    /* a HIP runtime call failed                              */
+} fbx_status;
+
+/* One emitted slot of a result.  HOST struct owned by the plan. */
+typedef struct {
+  uint32_t slot_id;        /* slot number given in the spec                                  */
+  uint32_t fixed_arity;    /* k > 0: exactly k signs per record and offsets == NULL (record r
+                              owns values[r*k, (r+1)*k)); 0: ragged, offsets given            */
+  uint64_t n_values;       /* signs in this slot for this call                               */
+  const uint64_t* values;  /* DEVICE, n_values entries, record order, token order inside     */
+  const uint64_t* offsets; /* DEVICE, n_records + 1 entries, offsets[0] = 0,
+                              offsets[n_records] = n_values; NULL for fixed-arity slots      */
+} fbx_slot_view;
+
+typedef struct {
+  uint64_t n_records;
+  uint64_t n_values_total;      /* sum of n_values over emitted slots                       */
+  uint64_t n_malformed_numeric; /* bucket tokens that were not clean decimal text           */
+  uint64_t arena_high_water;    /* workspace bytes this call needed (also set on NOMEM)     */
+  uint32_t n_slots;
+  uint32_t n_layers;
+  const fbx_slot_view* slots;   /* HOST, n_slots entries in spec order; valid until the next
+                                   fbx_extract or fbx_plan_destroy on this plan             */
+} fbx_result;
+
+/*
+ * fbx_plan_create — parse and type-check an operator-DAG spec, partition it
+ * into layers and precompute per-operator constants.  Host only; needs no GPU.
+ *
+ * Operators without dependencies form layer 1; every other operator sits one
+ * layer below its deepest input, so operators of one layer never depend on
+ * each other (Section 4, "Scheduling").  The order is fixed here, once, before
+ * any batch runs (Section 4, "Inner-GPU operator launching").
+ *
+ *   spec, spec_len : HOST, ASCII text, not retained:
+ *       fbx 1
+ *       fields <F>
+ *       op <id> hash   slot=<u32> seed=<u64> emit=<0|1> field=<k> multi=<0|1>
+ *       op <id> ngram  slot= seed= emit= field=<k> n=<1..8>
+ *       op <id> bucket slot= seed= emit= field=<k> multi=<0|1> bounds=<i64,...>  (non-decreasing)
+ *       op <id> filter slot= seed= emit= field=<k> multi=<0|1> prefix=<hex bytes>
+ *       op <id> cross  slot= seed= emit= a=<id> b=<id>
+ *       op <id> concat slot= emit= a=<id> b=<id>
+ *     '#' starts a comment line.  a/b must name operators defined on earlier lines.
+ *   out : receives the plan; untouched on error.
+ * Errors: FBX_E_ARG, FBX_E_SPEC (message via fbx_last_error(NULL)).
+ */
+fbx_status fbx_plan_create(const char* spec, size_t spec_len, fbx_plan** out);
+
+/* Release a plan (HOST memory only; the workspace stays the caller's).  NULL is fine. */
+void fbx_plan_destroy(fbx_plan* plan);
+
+/*
+ * fbx_plan_workspace_hint — a workspace size (bytes) that is enough for typical
+ * inputs of raw_len bytes and n_records records.  Ragged outputs cannot be
+ * bounded ahead of time, so fbx_extract may still answer FBX_E_NOMEM together
+ * with the exact requirement; the caller then enlarges the workspace and retries.
+ */
+fbx_status fbx_plan_workspace_hint(const fbx_plan* plan, uint64_t raw_len, uint64_t n_records,
+                                   uint64_t* bytes);
+
+/*
+ * fbx_plan_set_workspace — hand over the pre-allocated pool (Section 5: the
+ * pool "is pre-allocated in the GPU global memory").
+ *   d_workspace : DEVICE, 256-byte aligned, stays owned by the caller and must
+ *                 outlive every fbx_extract that uses it.
+ * Copies the plan's constant tables into its head (synchronous copy, once).
+ * Errors: FBX_E_ARG, FBX_E_NOMEM (smaller than the constant tables), FBX_E_HIP.
+ */
+fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t bytes);
+
+/*
+ * fbx_extract — run the whole path on one batch.
+ *   d_raw      : DEVICE, raw_len bytes.  Record i is d_raw[rec_off[i], rec_off[i+1]);
+ *                one trailing '\n' is not part of the record; fields are separated
+ *                by '\t', list items by ','.
+ *   d_rec_off  : DEVICE, n_records + 1 entries, non-decreasing, last <= raw_len.
+ *   hip_stream : a hipStream_t (0 = default stream); all work is enqueued there.
+ *   out        : HOST, filled on FBX_OK; on FBX_E_NOMEM only arena_high_water is set
+ *                (the workspace size that would have sufficed).
+ * Inputs are borrowed until the call returns.  Results point into the workspace
+ * and are overwritten by the next fbx_extract on this plan.  The call
+ * synchronises the stream exactly once, at its end, to read back sizes.
+ * Layer by layer: one tile kernel launch per layer with the stream order as the
+ * layer barrier (Section 4), or all layers in one launch when the plan option
+ * "fused" is set; the dynamic-memory pool is released in O(1) after each
+ * layer as far as live intermediates allow (Section 5, "Reset GPU memory pool").
+ * Errors: FBX_E_ARG, FBX_E_NOMEM, FBX_E_INPUT, FBX_E_HIP.
+ */
+fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len,
+                       const uint64_t* d_rec_off, uint64_t n_records, void* hip_stream,
+                       fbx_result* out);
+
+/* Last error text of a plan (or of the last failed fbx_plan_create when plan is NULL). */
+const char* fbx_last_error(const fbx_plan* plan);
+const char* fbx_status_str(fbx_status s);
+
+/*
+ * Plan introspection (HOST): operator count, layer count and, if the arrays
+ * are non-NULL (capacity n_ops each), the 1-based layer and the fixed arity
+ * (0 = ragged) of every operator in spec order.
+ */
+fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_layers,
+                         uint32_t* layer_of_op, uint32_t* arity_of_op);
+
+/*
+ * Tuning knobs, all optional.  Keys:
+ *   "tile_bytes"   target bytes of raw text staged per workgroup (default 24576)
+ *   "fused"        1: all layers in one launch, each workgroup running the layers
+ *                  in order on its own records; 0: one launch per layer (default 0)
+ *   "profile"      1: time every kernel of fbx_extract with HIP events
+ * Errors: FBX_E_ARG for an unknown key or an out-of-range value.
+ */
+fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value);
+
+/*
+ * Kernel timings of the last fbx_extract (needs option "profile" = 1).
+ * which: 0 validate, 1 count, 2 scan, 3 alloc, 4 all tile launches together,
+ *        100 + l : tile launch of layer l (1-based; 101 alone in fused mode).
+ * ms receives the HIP-event duration on the call's stream.
+ */
+fbx_status fbx_plan_kernel_ms(const fbx_plan* plan, uint32_t which, float* ms);
+
+/*
+ * In-kernel dynamic allocation as a primitive (Section 5, Algorithm 1 and
+ * "Reset GPU memory pool").  fbx_arena_alloc launches ceil(n / block_threads)
+ * workgroups; in each, thread i asks for d_sizes[i] bytes: the workgroup takes a
+ * prefix sum of its sizes, ONE thread adds the workgroup total (rounded up to
+ * 128 bytes) to *d_head with an atomic add, and thread i gets
+ * old_head + (sum of the sizes of the threads before it).  Workgroups land in
+ * arrival order, so offsets are only unique, not ordered, across workgroups.
+ *   d_head    : DEVICE, one u64 (the pool's idle-memory head, a byte offset)
+ *   d_sizes   : DEVICE, n u64
+ *   d_offsets : DEVICE, n u64 out (byte offsets from the pool base)
+ *   block_threads : 64..1024, multiple of 64
+ * fbx_arena_reset sets *d_head = value (constant time, frees everything above it).
+ * Both only enqueue on hip_stream.
+ */
+fbx_status fbx_arena_alloc(uint64_t* d_head, const uint64_t* d_sizes, uint64_t n, uint64_t* d_offsets,
+                           uint32_t block_threads, void* hip_stream);
+fbx_status fbx_arena_reset(uint64_t* d_head, uint64_t value, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FBX_H */

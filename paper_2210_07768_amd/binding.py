@@ -1,0 +1,218 @@
+"""Thin ctypes binding over the C ABI of ``libfbx.so`` (see ``include/fbx.h``).
+
+Argument marshalling only: every step of the extraction path runs in the
+library's HIP kernels.  PyTorch appears solely as the owner of device memory
+and streams.  If the library has not been built the import of this module
+fails loudly; there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfbx.so")
+
+OK, E_ARG, E_SPEC, E_NOMEM, E_INPUT, E_HIP = 0, -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "fbx_plan_create", "fbx_plan_destroy", "fbx_plan_workspace_hint", "fbx_plan_set_workspace",
+    "fbx_extract", "fbx_last_error", "fbx_status_str", "fbx_plan_info", "fbx_plan_set_option",
+    "fbx_plan_kernel_ms", "fbx_arena_alloc", "fbx_arena_reset",
+]
+
+
+class FbxError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"fbx status {status}: {msg}")
+        self.status = status
+        self.required_bytes = 0
+
+
+class SlotView(ctypes.Structure):
+    _fields_ = [("slot_id", ctypes.c_uint32), ("fixed_arity", ctypes.c_uint32),
+                ("n_values", ctypes.c_uint64), ("values", ctypes.c_void_p), ("offsets", ctypes.c_void_p)]
+
+
+class Result(ctypes.Structure):
+    _fields_ = [("n_records", ctypes.c_uint64), ("n_values_total", ctypes.c_uint64),
+                ("n_malformed_numeric", ctypes.c_uint64), ("arena_high_water", ctypes.c_uint64),
+                ("n_slots", ctypes.c_uint32), ("n_layers", ctypes.c_uint32),
+                ("slots", ctypes.POINTER(SlotView))]
+
+
+_lib = None
+
+
+def lib():
+    """Load libfbx.so (built beforehand by ``paper_2210_07768_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2210_07768_amd.build` first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u64, u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
+        L.fbx_plan_create.restype = ctypes.c_int
+        L.fbx_plan_create.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(vp)]
+        L.fbx_plan_destroy.restype = None
+        L.fbx_plan_destroy.argtypes = [vp]
+        L.fbx_plan_workspace_hint.restype = ctypes.c_int
+        L.fbx_plan_workspace_hint.argtypes = [vp, u64, u64, ctypes.POINTER(u64)]
+        L.fbx_plan_set_workspace.restype = ctypes.c_int
+        L.fbx_plan_set_workspace.argtypes = [vp, vp, u64]
+        L.fbx_extract.restype = ctypes.c_int
+        L.fbx_extract.argtypes = [vp, vp, u64, vp, u64, vp, ctypes.POINTER(Result)]
+        L.fbx_last_error.restype = ctypes.c_char_p
+        L.fbx_last_error.argtypes = [vp]
+        L.fbx_status_str.restype = ctypes.c_char_p
+        L.fbx_status_str.argtypes = [ctypes.c_int]
+        L.fbx_plan_info.restype = ctypes.c_int
+        L.fbx_plan_info.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(u32), vp, vp]
+        L.fbx_plan_set_option.restype = ctypes.c_int
+        L.fbx_plan_set_option.argtypes = [vp, ctypes.c_char_p, ctypes.c_int64]
+        L.fbx_plan_kernel_ms.restype = ctypes.c_int
+        L.fbx_plan_kernel_ms.argtypes = [vp, u32, ctypes.POINTER(ctypes.c_float)]
+        L.fbx_arena_alloc.restype = ctypes.c_int
+        L.fbx_arena_alloc.argtypes = [vp, vp, u64, vp, u32, vp]
+        L.fbx_arena_reset.restype = ctypes.c_int
+        L.fbx_arena_reset.argtypes = [vp, u64, vp]
+        _lib = L
+    return _lib
+
+
+class Slot:
+    """One emitted slot of a result; ``values`` / ``offsets`` are torch views of the workspace."""
+
+    def __init__(self, slot_id, fixed_arity, n_values, values, offsets):
+        self.slot_id, self.fixed_arity, self.n_values = slot_id, fixed_arity, n_values
+        self.values, self.offsets = values, offsets
+
+
+class ExtractResult:
+    def __init__(self):
+        self.n_records = 0
+        self.n_values_total = 0
+        self.n_malformed_numeric = 0
+        self.arena_high_water = 0
+        self.n_layers = 0
+        self.slots: Dict[int, Slot] = {}
+        self.slot_ids: List[int] = []
+
+
+class Plan:
+    """fbx_plan_create / fbx_plan_set_workspace / fbx_extract / fbx_plan_destroy."""
+
+    def __init__(self, spec: str):
+        self._h = ctypes.c_void_p()
+        s = spec.encode() if isinstance(spec, str) else spec
+        st = lib().fbx_plan_create(s, len(s), ctypes.byref(self._h))
+        if st != OK:
+            self._h = ctypes.c_void_p()
+            raise FbxError(st, lib().fbx_last_error(None).decode())
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            lib().fbx_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+        self._ws = None
+
+    __del__ = close
+
+    def _check(self, st: int):
+        if st != OK:
+            raise FbxError(st, lib().fbx_last_error(self._h).decode())
+
+    def info(self) -> Tuple[int, int, List[int], List[int]]:
+        n_ops, n_layers = ctypes.c_uint32(), ctypes.c_uint32()
+        self._check(lib().fbx_plan_info(self._h, ctypes.byref(n_ops), ctypes.byref(n_layers), None, None))
+        layers = (ctypes.c_uint32 * max(n_ops.value, 1))()
+        arity = (ctypes.c_uint32 * max(n_ops.value, 1))()
+        self._check(lib().fbx_plan_info(self._h, None, None, layers, arity))
+        return n_ops.value, n_layers.value, list(layers)[:n_ops.value], list(arity)[:n_ops.value]
+
+    def set_option(self, key: str, value: int):
+        self._check(lib().fbx_plan_set_option(self._h, key.encode(), int(value)))
+
+    def workspace_hint(self, raw_len: int, n_records: int) -> int:
+        out = ctypes.c_uint64()
+        self._check(lib().fbx_plan_workspace_hint(self._h, raw_len, n_records, ctypes.byref(out)))
+        return out.value
+
+    def set_workspace(self, ws):
+        """ws: a torch uint8 CUDA tensor; the caller keeps ownership (a reference is held here)."""
+        self._check(lib().fbx_plan_set_workspace(self._h, ws.data_ptr(), ws.numel()))
+        self._ws = ws
+
+    def kernel_ms(self, which: int) -> float:
+        ms = ctypes.c_float()
+        self._check(lib().fbx_plan_kernel_ms(self._h, which, ctypes.byref(ms)))
+        return ms.value
+
+    def extract_raw(self, raw_ptr: int, raw_len: int, off_ptr: int, n_records: int, stream: int = 0) -> Result:
+        res = Result()
+        st = lib().fbx_extract(self._h, raw_ptr, raw_len, off_ptr, n_records, stream, ctypes.byref(res))
+        if st != OK:
+            err = FbxError(st, lib().fbx_last_error(self._h).decode())
+            err.required_bytes = res.arena_high_water if st == E_NOMEM else 0
+            raise err
+        return res
+
+    def extract(self, d_raw, d_rec_off, stream: Optional[int] = None) -> ExtractResult:
+        """d_raw: uint8 CUDA tensor; d_rec_off: int64/uint64 CUDA tensor of n_records + 1 entries."""
+        import torch
+
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        n_records = d_rec_off.numel() - 1
+        res = self.extract_raw(d_raw.data_ptr() if d_raw.numel() else 0, d_raw.numel(), d_rec_off.data_ptr(),
+                               n_records, stream)
+        out = ExtractResult()
+        out.n_records, out.n_values_total = res.n_records, res.n_values_total
+        out.n_malformed_numeric, out.arena_high_water = res.n_malformed_numeric, res.arena_high_water
+        out.n_layers = res.n_layers
+        base = self._ws.data_ptr()
+        ws64 = self._ws[: self._ws.numel() // 8 * 8].view(torch.int64)
+        for i in range(res.n_slots):
+            sv = res.slots[i]
+            v0 = (sv.values - base) // 8
+            vals = ws64[v0:v0 + sv.n_values]
+            offs = None
+            if sv.offsets:
+                o0 = (sv.offsets - base) // 8
+                offs = ws64[o0:o0 + n_records + 1]
+            out.slots[sv.slot_id] = Slot(sv.slot_id, sv.fixed_arity, sv.n_values, vals, offs)
+            out.slot_ids.append(sv.slot_id)
+        return out
+
+
+def extract_with_retry(plan: Plan, d_raw, d_rec_off, device="cuda", slack: float = 1.0):
+    """Allocate a workspace from the hint, run, and grow once if the library asks for more."""
+    import torch
+
+    n_records = d_rec_off.numel() - 1
+    need = plan.workspace_hint(d_raw.numel(), n_records)
+    for _ in range(3):
+        ws = torch.empty(int(need * slack) + 256, dtype=torch.uint8, device=device)
+        plan.set_workspace(ws)
+        try:
+            return plan.extract(d_raw, d_rec_off), ws
+        except FbxError as e:
+            if e.status != E_NOMEM or not e.required_bytes:
+                raise
+            need = e.required_bytes
+    raise RuntimeError("workspace kept growing")
+
+
+def arena_alloc(d_head, d_sizes, d_offsets, block_threads: int = 256, stream: int = 0):
+    st = lib().fbx_arena_alloc(d_head.data_ptr(), d_sizes.data_ptr(), d_sizes.numel(), d_offsets.data_ptr(),
+                               block_threads, stream)
+    if st != OK:
+        raise FbxError(st, lib().fbx_status_str(st).decode())
+
+
+def arena_reset(d_head, value: int, stream: int = 0):
+    st = lib().fbx_arena_reset(d_head.data_ptr(), value, stream)
+    if st != OK:
+        raise FbxError(st, lib().fbx_status_str(st).decode())

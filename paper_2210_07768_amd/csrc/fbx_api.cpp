@@ -1,0 +1,421 @@
+// C ABI of libfbx: plan lifetime, workspace layout, and the launch sequence of
+// one extraction call.  See include/fbx.h for the contract of every entry point.
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "fbx_device.h"
+
+using namespace fbx;
+
+namespace {
+
+constexpr uint64_t kAlign = 256;
+uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
+
+thread_local std::string g_create_error;
+
+struct Timer {
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  bool used = false;
+};
+
+}  // namespace
+
+struct fbx_plan {
+  PlanHost host;
+  std::string error;
+
+  // workspace
+  uint8_t* ws = nullptr;
+  uint64_t ws_bytes = 0;
+  // constant-table placement inside the workspace (byte offsets)
+  uint64_t off_ctrl = 0, off_dyn = 0, off_ops = 0, off_layer_ops = 0, off_layer_begin = 0, off_nonroot = 0,
+           off_aux = 0, off_row_total = 0, off_static_end = 0;
+
+  // options
+  uint64_t tile_bytes = 20480;
+  int fused = 0;
+  int profile = 0;
+
+  // results of the last call
+  std::vector<uint8_t> readback;  // Ctrl + OpDyn[n_ops]
+  std::vector<fbx_slot_view> slots;
+  std::vector<uint32_t> emitted;  // operator index of every emitted slot, spec order
+
+  // profiling
+  std::vector<Timer> timers;  // 0 validate, 1 count, 2 scan, 3 alloc, 4.. tile launches
+  uint32_t n_tile_launches = 0;
+  std::vector<uint32_t> tile_launch_layer;
+
+  void layout() {
+    const uint64_t n = host.ops.size();
+    uint64_t o = 0;
+    off_ctrl = o; o += sizeof(Ctrl);
+    off_dyn = o; o = align_up(o + n * sizeof(OpDyn));
+    off_ops = o; o = align_up(o + n * sizeof(OpDesc));
+    off_layer_ops = o; o = align_up(o + n * 4);
+    off_layer_begin = o; o = align_up(o + (host.n_layers + 1) * 4);
+    off_nonroot = o; o = align_up(o + host.nonroot_ops.size() * 4);
+    off_aux = o; o = align_up(o + host.aux.size());
+    off_row_total = o; o = align_up(o + host.n_ragged * 8ull);
+    off_static_end = o;
+  }
+};
+
+namespace {
+
+struct CallGeometry {
+  uint32_t log2T = 0, n_tiles = 0;
+  uint32_t cap_bytes = 0, cap_tabs = 0;
+  uint32_t lds_cnt = 0, lds_tab = 0, lds_mask = 0, lds_bytes = 0, lds_total = 0;
+  uint64_t off_tile_cnt = 0, off_tile_base = 0, arena_base = 0;
+};
+
+CallGeometry geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records) {
+  CallGeometry g;
+  // records per tile: a power of two whose average byte size is near the target
+  const uint64_t avg = n_records ? std::max<uint64_t>(raw_len / n_records, 1) : 1;
+  uint32_t log2T = 0;
+  while (log2T < 6 && (avg << (log2T + 1)) <= p.tile_bytes) ++log2T;
+  // the per-record count table of the ragged operators has to fit beside the bytes
+  while (log2T > 0 && (uint64_t(p.host.n_ragged) << log2T) * 4 > 16384) --log2T;
+  g.log2T = log2T;
+  g.n_tiles = static_cast<uint32_t>((n_records + (1ull << log2T) - 1) >> log2T);
+  g.cap_bytes = static_cast<uint32_t>(std::min<uint64_t>(align_up(p.tile_bytes * 5 / 4, 16), 65024));
+  g.cap_tabs = g.cap_bytes / 4;
+  uint32_t o = 0;
+  g.lds_cnt = o; o += static_cast<uint32_t>(align_up((uint64_t(std::max(p.host.n_ragged, 1u)) << log2T) * 4, 16));
+  g.lds_tab = o; o += static_cast<uint32_t>(align_up(g.cap_tabs * 2ull, 16));
+  g.lds_mask = o; o += static_cast<uint32_t>(align_up((g.cap_bytes / 16 + 2) * 2ull, 16));
+  g.lds_bytes = o; o += g.cap_bytes + 32;
+  g.lds_total = o;
+  uint64_t w = p.off_static_end;
+  g.off_tile_cnt = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 4);
+  g.off_tile_base = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 8);
+  g.arena_base = w;
+  return g;
+}
+
+fbx_status hip_fail(fbx_plan* p, hipError_t e, const char* where) {
+  p->error = std::string(where) + ": " + hipGetErrorString(e);
+  (void)hipGetLastError();
+  return FBX_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fbx_status_str(fbx_status s) {
+  switch (s) {
+    case FBX_OK: return "ok";
+    case FBX_E_ARG: return "bad argument";
+    case FBX_E_SPEC: return "bad operator spec";
+    case FBX_E_NOMEM: return "workspace too small";
+    case FBX_E_INPUT: return "bad record offsets";
+    case FBX_E_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* fbx_last_error(const fbx_plan* plan) { return plan ? plan->error.c_str() : g_create_error.c_str(); }
+
+fbx_status fbx_plan_create(const char* spec, size_t spec_len, fbx_plan** out) {
+  if (!spec || !out) {
+    g_create_error = "spec and out must not be NULL";
+    return FBX_E_ARG;
+  }
+  std::unique_ptr<fbx_plan> p(new (std::nothrow) fbx_plan());
+  if (!p) return FBX_E_ARG;
+  std::string err;
+  fbx_status st = parse_plan(spec, spec_len, p->host, err);
+  if (st != FBX_OK) {
+    g_create_error = err;
+    return st;
+  }
+  for (uint32_t i = 0; i < p->host.ops.size(); ++i)
+    if (p->host.ops[i].d.flags & F_EMIT) p->emitted.push_back(i);
+  p->slots.resize(p->emitted.size());
+  p->layout();
+  p->readback.resize(p->off_dyn + p->host.ops.size() * sizeof(OpDyn));
+  *out = p.release();
+  return FBX_OK;
+}
+
+void fbx_plan_destroy(fbx_plan* plan) {
+  if (!plan) return;
+  for (Timer& t : plan->timers)
+    for (hipEvent_t e : t.ev)
+      if (e) (void)hipEventDestroy(e);
+  delete plan;
+}
+
+fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_layers, uint32_t* layer_of_op,
+                         uint32_t* arity_of_op) {
+  if (!plan) return FBX_E_ARG;
+  if (n_ops) *n_ops = static_cast<uint32_t>(plan->host.ops.size());
+  if (n_layers) *n_layers = plan->host.n_layers;
+  for (size_t i = 0; i < plan->host.ops.size(); ++i) {
+    if (layer_of_op) layer_of_op[i] = plan->host.ops[i].d.layer;
+    if (arity_of_op) arity_of_op[i] = plan->host.ops[i].d.arity;
+  }
+  return FBX_OK;
+}
+
+fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
+  if (!plan || !key) return FBX_E_ARG;
+  const std::string k(key);
+  if (k == "tile_bytes") {
+    if (value < 1024 || value > 49152) { plan->error = "tile_bytes must be in 1024..49152"; return FBX_E_ARG; }
+    plan->tile_bytes = static_cast<uint64_t>(value);
+  } else if (k == "fused") {
+    if (value != 0 && value != 1) { plan->error = "fused must be 0 or 1"; return FBX_E_ARG; }
+    plan->fused = static_cast<int>(value);
+  } else if (k == "profile") {
+    if (value != 0 && value != 1) { plan->error = "profile must be 0 or 1"; return FBX_E_ARG; }
+    plan->profile = static_cast<int>(value);
+  } else {
+    plan->error = "unknown option '" + k + "'";
+    return FBX_E_ARG;
+  }
+  return FBX_OK;
+}
+
+fbx_status fbx_plan_workspace_hint(const fbx_plan* plan, uint64_t raw_len, uint64_t n_records, uint64_t* bytes) {
+  if (!plan || !bytes) return FBX_E_ARG;
+  const CallGeometry g = geometry(*plan, raw_len, n_records);
+  // fixed-arity operators are exact; a ragged root operator cannot emit more
+  // signs than its field has bytes + 1, for which raw_len / #fields + records
+  // is a fair guess; a ragged cross or concat is guessed at four times that.
+  const uint64_t per_root = raw_len / std::max(plan->host.n_fields, 1u) + n_records;
+  uint64_t total = g.arena_base;
+  for (const HostOp& op : plan->host.ops) {
+    uint64_t n = op.d.arity ? n_records * op.d.arity : (op.d.layer == 1 ? per_root : 4 * per_root);
+    total += align_up(n * 8, 128);
+    if (!op.d.arity) total += align_up((n_records + 1) * 8, 128);
+  }
+  *bytes = align_up(total + 4096);
+  return FBX_OK;
+}
+
+fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t bytes) {
+  if (!plan || !d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255u)) {
+    if (plan) plan->error = "workspace must be a non-NULL, 256-byte aligned device pointer";
+    return FBX_E_ARG;
+  }
+  if (bytes < plan->off_static_end) {
+    plan->error = "workspace smaller than the plan's constant tables (" + std::to_string(plan->off_static_end) + " bytes)";
+    return FBX_E_NOMEM;
+  }
+  const PlanHost& h = plan->host;
+  std::vector<uint8_t> img(plan->off_static_end, 0);
+  std::vector<OpDesc> descs(h.ops.size());
+  for (size_t i = 0; i < h.ops.size(); ++i) descs[i] = h.ops[i].d;
+  if (!descs.empty()) std::memcpy(img.data() + plan->off_ops, descs.data(), descs.size() * sizeof(OpDesc));
+  if (!h.layer_ops.empty()) std::memcpy(img.data() + plan->off_layer_ops, h.layer_ops.data(), h.layer_ops.size() * 4);
+  std::memcpy(img.data() + plan->off_layer_begin, h.layer_begin.data(), h.layer_begin.size() * 4);
+  if (!h.nonroot_ops.empty()) std::memcpy(img.data() + plan->off_nonroot, h.nonroot_ops.data(), h.nonroot_ops.size() * 4);
+  if (!h.aux.empty()) std::memcpy(img.data() + plan->off_aux, h.aux.data(), h.aux.size());
+  hipError_t e = hipMemcpy(d_workspace, img.data(), img.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return hip_fail(plan, e, "copying plan tables");
+  plan->ws = static_cast<uint8_t*>(d_workspace);
+  plan->ws_bytes = bytes;
+  return FBX_OK;
+}
+
+fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, const uint64_t* d_rec_off,
+                       uint64_t n_records, void* hip_stream, fbx_result* out) {
+  if (!plan || !out || !d_rec_off || (!d_raw && raw_len)) {
+    if (plan) plan->error = "NULL argument";
+    return FBX_E_ARG;
+  }
+  if (!plan->ws) { plan->error = "no workspace set"; return FBX_E_ARG; }
+  if (n_records >= (1ull << 32)) { plan->error = "more than 2^32-1 records in one call"; return FBX_E_ARG; }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const PlanHost& h = plan->host;
+  const uint32_t n_ops = static_cast<uint32_t>(h.ops.size());
+  const CallGeometry g = geometry(*plan, raw_len, n_records);
+  if (g.arena_base > plan->ws_bytes) {
+    out->arena_high_water = g.arena_base;
+    plan->error = "workspace too small for the per-tile tables; need more than " + std::to_string(g.arena_base) + " bytes";
+    return FBX_E_NOMEM;
+  }
+  if (g.lds_total > 158 * 1024) { plan->error = "LDS budget exceeded"; return FBX_E_ARG; }
+
+  uint8_t* ws = plan->ws;
+  Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + plan->off_ctrl);
+  OpDyn* dyn = reinterpret_cast<OpDyn*>(ws + plan->off_dyn);
+  TileParams P{};
+  P.raw = d_raw; P.raw_len = raw_len; P.rec_off = d_rec_off; P.n_records = n_records;
+  P.ws = ws;
+  P.ops = reinterpret_cast<const OpDesc*>(ws + plan->off_ops);
+  P.layer_ops = reinterpret_cast<const uint32_t*>(ws + plan->off_layer_ops);
+  P.layer_begin = reinterpret_cast<const uint32_t*>(ws + plan->off_layer_begin);
+  P.nonroot = reinterpret_cast<const uint32_t*>(ws + plan->off_nonroot);
+  P.aux = ws + plan->off_aux;
+  P.dyn = dyn; P.ctrl = ctrl;
+  P.tile_cnt = reinterpret_cast<uint32_t*>(ws + g.off_tile_cnt);
+  P.tile_base = reinterpret_cast<uint64_t*>(ws + g.off_tile_base);
+  P.n_ops = n_ops; P.n_layers = h.n_layers; P.n_ragged = h.n_ragged;
+  P.n_nonroot = static_cast<uint32_t>(h.nonroot_ops.size());
+  P.n_tiles = g.n_tiles; P.log2T = g.log2T; P.n_fields = h.n_fields;
+  P.cap_bytes = g.cap_bytes; P.cap_tabs = g.cap_tabs;
+  P.lds_cnt = g.lds_cnt; P.lds_tab = g.lds_tab; P.lds_mask = g.lds_mask; P.lds_bytes = g.lds_bytes;
+  uint64_t* row_total = reinterpret_cast<uint64_t*>(ws + plan->off_row_total);
+
+  // profiling events
+  const uint32_t n_launch = h.n_layers == 0 ? 0 : (plan->fused ? 1 : h.n_layers);
+  plan->n_tile_launches = n_launch;
+  plan->tile_launch_layer.clear();
+  if (plan->profile) {
+    if (plan->timers.size() < 4 + n_launch) plan->timers.resize(4 + n_launch);
+    for (Timer& t : plan->timers) {
+      t.used = false;
+      for (hipEvent_t& e : t.ev)
+        if (!e) {
+          hipError_t he = hipEventCreate(&e);
+          if (he != hipSuccess) return hip_fail(plan, he, "hipEventCreate");
+        }
+    }
+  }
+  auto tick = [&](uint32_t which, int edge) {
+    if (plan->profile) {
+      (void)hipEventRecord(plan->timers[which].ev[edge], st);
+      plan->timers[which].used = true;
+    }
+  };
+#define FBX_LAUNCH(expr, what)                                 \
+  do {                                                         \
+    hipError_t e_ = (expr);                                    \
+    if (e_ != hipSuccess) return hip_fail(plan, e_, what);     \
+  } while (0)
+
+  FBX_LAUNCH(launch_reset(ctrl, g.arena_base, st), "reset");
+  tick(0, 0);
+  FBX_LAUNCH(launch_validate(d_rec_off, n_records, raw_len, g.log2T, ctrl, st), "validate");
+  tick(0, 1);
+  if (h.n_ragged) {
+    if (g.n_tiles) {
+      tick(1, 0);
+      P.layer_lo = 1; P.layer_hi = h.n_layers;
+      FBX_LAUNCH(launch_tile(P, true, g.lds_total, st), "count kernel");
+      tick(1, 1);
+    }
+    tick(2, 0);
+    FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
+    tick(2, 1);
+  }
+  tick(3, 0);
+  FBX_LAUNCH(launch_alloc(P.ops, dyn, n_ops, h.n_layers, row_total, n_records, plan->ws_bytes, ws,
+                          plan->fused ? 0 : 1, ctrl, st), "allocation kernel");
+  tick(3, 1);
+  if (g.n_tiles) {
+    if (plan->fused) {
+      P.layer_lo = 1; P.layer_hi = h.n_layers;
+      tick(4, 0);
+      FBX_LAUNCH(launch_tile(P, false, g.lds_total, st), "tile kernel");
+      tick(4, 1);
+      plan->tile_launch_layer.push_back(1);
+    } else {
+      for (uint32_t l = 1; l <= h.n_layers; ++l) {
+        P.layer_lo = P.layer_hi = l;
+        tick(3 + l, 0);
+        FBX_LAUNCH(launch_tile(P, false, g.lds_total, st), "tile kernel");
+        tick(3 + l, 1);
+        plan->tile_launch_layer.push_back(l);
+      }
+    }
+  }
+  FBX_LAUNCH(hipMemcpyAsync(plan->readback.data(), ws, plan->readback.size(), hipMemcpyDeviceToHost, st), "read-back");
+  FBX_LAUNCH(hipStreamSynchronize(st), "synchronise");
+#undef FBX_LAUNCH
+
+  const Ctrl* c = reinterpret_cast<const Ctrl*>(plan->readback.data() + plan->off_ctrl);
+  const OpDyn* y = reinterpret_cast<const OpDyn*>(plan->readback.data() + plan->off_dyn);
+  if (c->err & CE_OFFSETS) {
+    plan->error = "record offsets must be non-decreasing and end within raw_len";
+    return FBX_E_INPUT;
+  }
+  if (c->err & CE_TILE) {
+    plan->error = "a tile of records spans 2 GiB or more";
+    return FBX_E_INPUT;
+  }
+  if (c->err & CE_OVERFLOW) {
+    plan->error = "an operator produces 2^31 or more signs for one tile of records";
+    return FBX_E_INPUT;
+  }
+  if (c->err & CE_NOMEM) {
+    out->arena_high_water = c->required;
+    plan->error = "workspace too small: need " + std::to_string(c->required) + " bytes";
+    return FBX_E_NOMEM;
+  }
+  uint64_t total = 0;
+  for (size_t s = 0; s < plan->emitted.size(); ++s) {
+    const uint32_t i = plan->emitted[s];
+    const OpDesc& d = h.ops[i].d;
+    fbx_slot_view& v = plan->slots[s];
+    v.slot_id = h.ops[i].slot;
+    v.fixed_arity = d.arity;
+    v.n_values = y[i].n_values;
+    v.values = reinterpret_cast<const uint64_t*>(ws + y[i].values_off);
+    v.offsets = d.arity ? nullptr : reinterpret_cast<const uint64_t*>(ws + y[i].offsets_off);
+    total += v.n_values;
+  }
+  out->n_records = n_records;
+  out->n_values_total = total;
+  out->n_malformed_numeric = c->n_malformed;
+  out->arena_high_water = c->high_water;
+  out->n_slots = static_cast<uint32_t>(plan->slots.size());
+  out->n_layers = h.n_layers;
+  out->slots = plan->slots.data();
+  return FBX_OK;
+}
+
+fbx_status fbx_plan_kernel_ms(const fbx_plan* plan, uint32_t which, float* ms) {
+  if (!plan || !ms) return FBX_E_ARG;
+  auto one = [&](uint32_t idx, float& v) -> bool {
+    if (idx >= plan->timers.size() || !plan->timers[idx].used) return false;
+    return hipEventElapsedTime(&v, plan->timers[idx].ev[0], plan->timers[idx].ev[1]) == hipSuccess;
+  };
+  float v = 0.f;
+  if (which < 4) {
+    if (!one(which, v)) return FBX_E_ARG;
+    *ms = v;
+    return FBX_OK;
+  }
+  if (which == 4) {
+    float sum = 0.f;
+    for (uint32_t k = 0; k < plan->n_tile_launches; ++k) {
+      if (!one(4 + k, v)) return FBX_E_ARG;
+      sum += v;
+    }
+    *ms = sum;
+    return FBX_OK;
+  }
+  if (which > 100 && which - 101 < plan->n_tile_launches) {
+    if (!one(4 + (which - 101), v)) return FBX_E_ARG;
+    *ms = v;
+    return FBX_OK;
+  }
+  return FBX_E_ARG;
+}
+
+fbx_status fbx_arena_alloc(uint64_t* d_head, const uint64_t* d_sizes, uint64_t n, uint64_t* d_offsets,
+                           uint32_t block_threads, void* hip_stream) {
+  if (!d_head || (n && (!d_sizes || !d_offsets)) || block_threads < 64 || block_threads > 1024 || block_threads % 64 ||
+      (n + block_threads - 1) / block_threads > 0x7fffffffull)
+    return FBX_E_ARG;
+  hipError_t e = launch_arena_alloc(d_head, d_sizes, n, d_offsets, block_threads, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FBX_OK : FBX_E_HIP;
+}
+
+fbx_status fbx_arena_reset(uint64_t* d_head, uint64_t value, void* hip_stream) {
+  if (!d_head) return FBX_E_ARG;
+  hipError_t e = launch_arena_reset(d_head, value, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FBX_OK : FBX_E_HIP;
+}
+
+}  // extern "C"

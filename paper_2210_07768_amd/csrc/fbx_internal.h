@@ -1,0 +1,85 @@
+// Internal declarations shared by the host side and the HIP kernels of libfbx.
+// Nothing here is part of the C ABI.
+#pragma once
+
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "fbx.h"
+
+namespace fbx {
+
+enum OpKind : uint32_t { OP_HASH = 1, OP_NGRAM = 2, OP_BUCKET = 3, OP_FILTER = 4, OP_CROSS = 5, OP_CONCAT = 6 };
+
+enum OpFlags : uint32_t { F_MULTI = 1u, F_EMIT = 2u };
+
+// Device-visible operator descriptor (64 bytes).  Filled once at plan time.
+struct OpDesc {
+  uint32_t kind;
+  uint32_t flags;
+  uint32_t field;    // root operators: positional field index
+  uint32_t arity;    // signs per record when fixed, 0 when ragged
+  uint32_t a, b;     // cross / concat: input operator indices
+  uint32_t aux_off;  // byte offset into the aux table (bucket bounds, filter prefix)
+  uint32_t aux_len;  // #bounds, prefix length, or n-gram width
+  uint64_t key;      // hash/ngram/filter: FNV state after the 8 seed bytes;
+                     // cross/bucket: slot key mix64(seed)
+  uint32_t rag_row;  // row among ragged operators (count tables), 0xffffffff if fixed
+  uint32_t layer;    // 1-based
+  uint32_t birth;    // == layer
+  uint32_t death;    // last layer that reads this operator's output (>= layer)
+  uint32_t pad[2];
+};
+static_assert(sizeof(OpDesc) == 64, "OpDesc must stay 64 bytes");
+
+// Per-call, per-operator placement, written by the allocation kernel.
+struct OpDyn {
+  uint64_t values_off;   // byte offset of the values array from the workspace base
+  uint64_t offsets_off;  // byte offset of the offsets array (ragged only)
+  uint64_t n_values;
+  uint64_t pad;
+};
+
+// Device control block at the head of the workspace (read back once per call).
+struct Ctrl {
+  uint32_t err;            // bit 0 bad offsets, bit 1 out of memory, bit 2 count overflow, bit 3 tile too long
+  uint32_t pad0;
+  uint64_t required;       // workspace bytes needed (valid when the allocation kernel ran)
+  uint64_t head;           // idle-memory head of the arena (byte offset from workspace base)
+  uint64_t high_water;
+  uint64_t n_malformed;
+  uint64_t max_tile_bytes;
+  uint64_t slow_tiles;     // tiles that did not fit the staged fast path
+  uint64_t pad1;
+};
+static_assert(sizeof(Ctrl) == 64, "Ctrl must stay 64 bytes");
+
+enum CtrlErr : uint32_t { CE_OFFSETS = 1u, CE_NOMEM = 2u, CE_OVERFLOW = 4u, CE_TILE = 8u };
+
+struct HostOp {
+  std::string id;
+  OpDesc d{};
+  uint32_t slot = 0;
+  uint64_t seed = 0;
+  std::vector<int64_t> bounds;
+  std::vector<uint8_t> prefix;
+};
+
+// Parsed, layered plan (host).  Built by parse_plan(); no HIP calls involved.
+struct PlanHost {
+  uint32_t n_fields = 0;
+  uint32_t n_layers = 0;
+  uint32_t n_ragged = 0;
+  std::vector<HostOp> ops;             // spec order
+  std::vector<uint32_t> layer_ops;     // operator indices grouped by layer
+  std::vector<uint32_t> layer_begin;   // n_layers + 1 entries into layer_ops
+  std::vector<uint32_t> nonroot_ops;   // operators of layers >= 2, in spec order
+  std::vector<uint8_t> aux;            // bounds (8-byte aligned) and prefixes
+};
+
+// Returns FBX_OK or FBX_E_SPEC (message in err).
+fbx_status parse_plan(const char* spec, size_t len, PlanHost& out, std::string& err);
+
+}  // namespace fbx

@@ -1,0 +1,57 @@
+"""Spec texts and hand-built records shared by the CPU and GPU tests."""
+
+FRAMING_SPEC = ("fbx 1\nfields 4\n"
+                "# comment line\n"
+                "op a hash slot=0 seed=3 emit=1 field=0 multi=0\n"
+                "op b hash slot=1 seed=4 emit=1 field=1 multi=1\n"
+                "op c bucket slot=2 seed=5 emit=1 field=2 multi=1 bounds=0,1000000,2500000\n"
+                "op d ngram slot=3 seed=6 emit=1 field=3 n=3\n"
+                "op e filter slot=4 seed=7 emit=1 field=1 multi=1 prefix=78\n"
+                "op f filter slot=5 seed=8 emit=1 field=0 multi=0 prefix=\n"
+                "op g cross slot=6 seed=9 emit=1 a=b b=c\n"
+                "op h concat slot=7 emit=1 a=g b=a\n"
+                "op i cross slot=8 seed=10 emit=1 a=a b=a\n"
+                "op j hash slot=9 seed=0 emit=0 field=3 multi=0\n"
+                "op k concat slot=10 emit=1 a=j b=j\n")
+
+
+
+FRAMING_RECORDS = [
+    b"ab\tx,y,,z\t1.5,-2,abc\thello world\n",   # plain
+    b"ab\tx,y,,z\t1.5\thello world",             # no trailing newline
+    b"only\n",                                   # missing fields -> empty strings
+    b"\n",                                       # empty record (all fields empty)
+    b"",                                         # zero-length record
+    b"\t\t\t\n",                                 # all fields present and empty
+    b"a,b\txa,xb,x,,ax\t3\tab\textra\tfields\n", # extra fields ignored, n-gram shorter than n
+    b"q\t,\t,\tabc\n",                           # lone commas -> two empty items
+    b"w\tx\t2.5\tabcd\n\n",                      # only ONE trailing newline is dropped
+]
+
+BAD_SPECS = {
+    "no header": "fields 2\n",
+    "bad version": "fbx 2\nfields 2\n",
+    "no fields": "fbx 1\n",
+    "zero fields": "fbx 1\nfields 0\n",
+    "unknown kind": "fbx 1\nfields 2\nop a frob slot=0 seed=0 emit=1 field=0\n",
+    "unknown key": "fbx 1\nfields 2\nop a hash slot=0 seed=0 emit=1 field=0 multi=0 zz=1\n",
+    "missing key": "fbx 1\nfields 2\nop a hash slot=0 seed=0 emit=1 field=0\n",
+    "repeated key": "fbx 1\nfields 2\nop a hash slot=0 slot=1 seed=0 emit=1 field=0 multi=0\n",
+    "field out of range": "fbx 1\nfields 2\nop a hash slot=0 seed=0 emit=1 field=2 multi=0\n",
+    "duplicate id": "fbx 1\nfields 2\nop a hash slot=0 seed=0 emit=1 field=0 multi=0\n"
+                    "op a hash slot=1 seed=0 emit=1 field=0 multi=0\n",
+    "forward reference": "fbx 1\nfields 2\nop x cross slot=0 seed=0 emit=1 a=a b=a\n"
+                         "op a hash slot=1 seed=0 emit=1 field=0 multi=0\n",
+    "self reference": "fbx 1\nfields 2\nop x cross slot=0 seed=0 emit=1 a=x b=x\n",
+    "unsorted bounds": "fbx 1\nfields 2\nop a bucket slot=0 seed=0 emit=1 field=0 multi=0 bounds=3,2\n",
+    "bad bound": "fbx 1\nfields 2\nop a bucket slot=0 seed=0 emit=1 field=0 multi=0 bounds=3,,4\n",
+    "duplicate emitted slot": "fbx 1\nfields 2\nop a hash slot=0 seed=0 emit=1 field=0 multi=0\n"
+                              "op b hash slot=0 seed=1 emit=1 field=1 multi=0\n",
+    "odd hex prefix": "fbx 1\nfields 2\nop a filter slot=0 seed=0 emit=1 field=0 multi=0 prefix=abc\n",
+    "ngram width": "fbx 1\nfields 2\nop a ngram slot=0 seed=0 emit=1 field=0 n=9\n",
+    "seed on concat": "fbx 1\nfields 2\nop a hash slot=0 seed=0 emit=1 field=0 multi=0\n"
+                      "op c concat slot=1 seed=3 emit=1 a=a b=a\n",
+    "seed too large": "fbx 1\nfields 2\nop a hash slot=0 seed=18446744073709551616 emit=1 field=0 multi=0\n",
+}
+
+

@@ -1,0 +1,218 @@
+"""GPU parity: libfbx (through the C ABI) against the CPU oracle, bit-exact.
+All arithmetic on the path is integer, so the tolerance is zero."""
+import random
+
+import numpy as np
+import pytest
+
+from oracle import fbx_oracle as O
+from paper_2210_07768_amd import binding as B
+from paper_2210_07768_amd import workloads as W
+from helpers import FRAMING_RECORDS, FRAMING_SPEC
+from gpu_harness import assert_same, check, run_gpu, to_device
+
+pytestmark = pytest.mark.gpu
+
+MODES = [{"fused": 0}, {"fused": 1}]
+
+
+def _cat(records):
+    raw = b"".join(records)
+    off = np.cumsum([0] + [len(r) for r in records]).astype(np.uint64)
+    return raw, off
+
+
+@pytest.mark.parametrize("mode", MODES, ids=["per_layer", "fused"])
+@pytest.mark.parametrize("tile_bytes", [1024, 20480])
+def test_hand_built_records(mode, tile_bytes):
+    raw, off = _cat(FRAMING_RECORDS * 7)
+    check(FRAMING_SPEC, raw, off, dict(mode, tile_bytes=tile_bytes))
+
+
+@pytest.mark.parametrize("mode", MODES, ids=["per_layer", "fused"])
+@pytest.mark.parametrize("cfg,n", [(1, 4096), (2, 700), (3, 3001), (4, 1500), (5, 2050)])
+def test_configs_small(cfg, n, mode):
+    w = W.get(cfg, n)
+    raw, off = w.generate()
+    res, want = check(w.spec, raw, off, mode, label=w.name)
+    assert res.n_layers == w.n_layers
+
+
+@pytest.mark.parametrize("tile_bytes", [1024, 4096, 49152])
+def test_tile_sizes(tile_bytes):
+    w = W.get(5, 777)
+    raw, off = w.generate()
+    check(w.spec, raw, off, {"tile_bytes": tile_bytes})
+    w = W.get(2, 130)
+    raw, off = w.generate()
+    check(w.spec, raw, off, {"tile_bytes": tile_bytes})
+
+
+@pytest.mark.parametrize("misalign", [1, 7, 15])
+def test_unaligned_raw_pointer_and_slack(misalign):
+    w = W.get(1, 300)
+    raw, off = w.generate()
+    # a gap before the first record and unused bytes after the last one
+    raw2 = np.concatenate([np.frombuffer(b"junk\tjunk\n", np.uint8), raw, np.frombuffer(b"\ttail", np.uint8)])
+    check(w.spec, raw2, off + np.uint64(10), misalign=misalign)
+
+
+def test_empty_batch_and_single_record():
+    out, res, plan = run_gpu(FRAMING_SPEC, np.zeros(0, np.uint8), np.zeros(1, np.uint64))
+    assert res.n_values_total == 0
+    for s, (v, o) in out.items():
+        assert v.size == 0 and o.tolist() == [0]
+    plan.close()
+    check(FRAMING_SPEC, *_cat([FRAMING_RECORDS[0]]))
+    check(FRAMING_SPEC, *_cat([b""]))
+
+
+def test_slow_path_long_records_and_dense_tabs():
+    rng = random.Random(5)
+    long_field = bytes(rng.choice(b"abcxyz,0123") for _ in range(70000))
+    recs = [b"k\t" + long_field + b"\t1.25,7\tquery text here\n",
+            b"a\tb\tc\td\n",
+            b"\t" * 5000 + b"\n",            # more tabs than the staged tab list holds
+            b"m\tx1,x2\t-3.5\tabcdef\n"] * 3
+    raw, off = _cat(recs)
+    res, _ = check(FRAMING_SPEC, raw, off, {"tile_bytes": 2048})
+    # dense tabs inside an otherwise small tile
+    recs = [b"\t\t\t" * 300 + b"\n"] * 40 + [b"a\tb,c\t1\tdddd\n"] * 40
+    check(FRAMING_SPEC, *_cat(recs), options={"tile_bytes": 4096})
+
+
+def test_malformed_numerics_are_counted():
+    spec = ("fbx 1\nfields 2\n"
+            "op a bucket slot=0 seed=1 emit=1 field=0 multi=1 bounds=-1000000,0,1000000\n"
+            "op b bucket slot=1 seed=2 emit=0 field=1 multi=0 bounds=\n")
+    recs = [b"1,x,-,.,-.5,1.2.3,99999999999999999999999\t12x\n", b"\t\n", b"-0.0000009,5\t7\n"] * 50
+    res, want = check(spec, *_cat(recs))
+    assert res.n_malformed_numeric == want.n_malformed_numeric > 0
+
+
+def test_bad_offsets_are_rejected():
+    w = W.get(1, 64)
+    raw, off = w.generate()
+    for mutate in ("decreasing", "beyond"):
+        bad = off.copy()
+        if mutate == "decreasing":
+            bad[10] = bad[12]
+        else:
+            bad[-1] = raw.size + 5
+        with pytest.raises(B.FbxError) as e:
+            run_gpu(w.spec, raw, bad)
+        assert e.value.status == B.E_INPUT
+
+
+def test_small_workspace_reports_requirement_then_succeeds():
+    import torch
+    w = W.get(2, 200)
+    raw, off = w.generate()
+    want = O.extract(w.spec, raw, off)
+    plan = B.Plan(w.spec)
+    d_raw, d_off = to_device(raw, off)
+    hint = plan.workspace_hint(raw.size, 200)
+    ws = torch.empty(hint // 8, dtype=torch.uint8, device="cuda")
+    plan.set_workspace(ws)
+    with pytest.raises(B.FbxError) as e:
+        plan.extract(d_raw, d_off)
+    assert e.value.status == B.E_NOMEM and e.value.required_bytes > ws.numel()
+    need = e.value.required_bytes
+    for size, ok in ((need - 128, False), (need, True)):
+        ws = torch.empty(size, dtype=torch.uint8, device="cuda")
+        plan.set_workspace(ws)
+        if ok:
+            res = plan.extract(d_raw, d_off)
+            assert res.arena_high_water == need
+            from gpu_harness import expand
+            assert_same({s: expand(res.slots[s], 200) for s in res.slot_ids}, res, want)
+        else:
+            with pytest.raises(B.FbxError) as e2:
+                plan.extract(d_raw, d_off)
+            assert e2.value.status == B.E_NOMEM
+    plan.close()
+
+
+def test_repeated_calls_are_bit_identical_and_plan_is_reusable():
+    w = W.get(4, 600)
+    raw, off = w.generate()
+    want = O.extract(w.spec, raw, off)
+    plan = B.Plan(w.spec)
+    d_raw, d_off = to_device(raw, off)
+    res, ws = B.extract_with_retry(plan, d_raw, d_off)
+    from gpu_harness import expand
+    first = {s: expand(res.slots[s], 600) for s in res.slot_ids}
+    assert_same(first, res, want)
+    for _ in range(10):
+        res = plan.extract(d_raw, d_off)
+        again = {s: expand(res.slots[s], 600) for s in res.slot_ids}
+        for s in first:
+            assert np.array_equal(first[s][0], again[s][0]) and np.array_equal(first[s][1], again[s][1])
+    # a different, smaller batch on the same plan and workspace
+    w2 = W.get(4, 100)
+    raw2, off2 = w2.generate(rec_begin=5000, n_records=100)
+    d_raw2, d_off2 = to_device(raw2, off2)
+    res2 = plan.extract(d_raw2, d_off2)
+    assert_same({s: expand(res2.slots[s], 100) for s in res2.slot_ids}, res2, O.extract(w.spec, raw2, off2))
+    plan.close()
+
+
+def test_results_do_not_depend_on_op_order_or_launch_mode():
+    w = W.get(4, 300)
+    raw, off = w.generate()
+    lines = w.spec.strip().split("\n")
+    head, ops = lines[:2], lines[2:]
+    roots = [l for l in ops if " cross " not in l and " concat " not in l]
+    rest = [l for l in ops if l not in roots]
+    random.Random(3).shuffle(roots)                # any order of the roots is topologically valid
+    spec2 = "\n".join(head + roots + rest) + "\n"
+    a, ra, pa = run_gpu(w.spec, raw, off, {"fused": 0})
+    b, rb, pb = run_gpu(spec2, raw, off, {"fused": 1})
+    assert sorted(a) == sorted(b)
+    for s in a:
+        assert np.array_equal(a[s][0], b[s][0]) and np.array_equal(a[s][1], b[s][1])
+    pa.close(); pb.close()
+
+
+def test_arena_reuse_lowers_the_high_water_mark():
+    # non-emitted intermediates of early layers are released for later layers
+    w = W.get(4, 2000)
+    raw, off = w.generate()
+    _, r_layered, p1 = run_gpu(w.spec, raw, off, {"fused": 0})
+    _, r_fused, p2 = run_gpu(w.spec, raw, off, {"fused": 1})
+    assert r_layered.arena_high_water <= r_fused.arena_high_water
+    p1.close(); p2.close()
+
+
+def test_algorithm1_arena_primitive():
+    # Section 5, Algorithm 1: per-thread regions are disjoint, contiguous inside a
+    # workgroup, sum to the bump of the head; workgroup bases are 128-byte aligned;
+    # a reset makes the next allocation start from the pool base again.
+    import torch
+    rng = np.random.default_rng(9)
+    for threads, n in ((64, 1000), (256, 5000), (1024, 3000)):
+        sizes = rng.integers(0, 300, size=n).astype(np.int64)
+        d_sizes = torch.from_numpy(sizes).cuda()
+        d_off = torch.zeros(n, dtype=torch.int64, device="cuda")
+        d_head = torch.tensor([4096], dtype=torch.int64, device="cuda")
+        B.arena_alloc(d_head, d_sizes, d_off, threads)
+        torch.cuda.synchronize()
+        offs = d_off.cpu().numpy()
+        head = int(d_head.cpu()[0])
+        total = 0
+        bases = []
+        for b0 in range(0, n, threads):
+            s, o = sizes[b0:b0 + threads], offs[b0:b0 + threads]
+            assert o[0] % 128 == 0
+            assert np.array_equal(o - o[0], np.cumsum(s) - s)      # exclusive prefix inside the workgroup
+            bases.append((o[0], (int(s.sum()) + 127) // 128 * 128))
+            total += bases[-1][1]
+        assert head == 4096 + total
+        bases.sort()
+        assert bases[0][0] == 4096
+        for (b, sz), (nb, _) in zip(bases, bases[1:]):
+            assert b + sz == nb                                     # workgroup regions tile the bumped range
+        B.arena_reset(d_head, 4096)
+        B.arena_alloc(d_head, d_sizes[:threads], d_off[:threads], threads)
+        torch.cuda.synchronize()
+        assert int(d_off[0].cpu()) == 4096
