@@ -51,6 +51,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2210_07768_amd.build` first")
+        # PyTorch ships its own HIP runtime; load it first so that libfbx binds to the
+        # same runtime instance that owns the device memory and streams it is handed.
+        import torch  # noqa: F401
+
         L = ctypes.CDLL(LIB_PATH)
         vp, u64, u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
         L.fbx_plan_create.restype = ctypes.c_int

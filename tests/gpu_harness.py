@@ -12,7 +12,7 @@ def to_device(raw: np.ndarray, off: np.ndarray, misalign: int = 0):
     buf = torch.empty(raw.size + misalign + 64, dtype=torch.uint8, device="cuda")
     d_raw = buf[misalign:misalign + raw.size]
     if raw.size:
-        d_raw.copy_(torch.from_numpy(np.ascontiguousarray(raw)))
+        d_raw.copy_(torch.from_numpy(np.array(raw, dtype=np.uint8)))
     d_off = torch.from_numpy(np.ascontiguousarray(off).astype(np.int64)).cuda()
     return d_raw, d_off
 

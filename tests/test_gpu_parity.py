@@ -112,7 +112,7 @@ def test_small_workspace_reports_requirement_then_succeeds():
     plan = B.Plan(w.spec)
     d_raw, d_off = to_device(raw, off)
     hint = plan.workspace_hint(raw.size, 200)
-    ws = torch.empty(hint // 8, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(262144, dtype=torch.uint8, device="cuda")
     plan.set_workspace(ws)
     with pytest.raises(B.FbxError) as e:
         plan.extract(d_raw, d_off)
