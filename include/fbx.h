@@ -118,9 +118,10 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
  * Inputs are borrowed until the call returns.  Results point into the workspace
  * and are overwritten by the next fbx_extract on this plan.  The call
  * synchronises the stream exactly once, at its end, to read back sizes.
- * Layer by layer: one tile kernel launch per layer with the stream order as the
- * layer barrier (Section 4), or all layers in one launch when the plan option
- * "fused" is set; the dynamic-memory pool is released in O(1) after each
+ * Layer by layer: with the plan option "fused" = 0 one kernel launch per layer,
+ * the stream order being the layer barrier (Section 4); by default all layers in
+ * one launch, each wavefront taking its records through the layers in order;
+ * the dynamic-memory pool is released in O(1) after each
  * layer as far as live intermediates allow (Section 5, "Reset GPU memory pool").
  * Errors: FBX_E_ARG, FBX_E_NOMEM, FBX_E_INPUT, FBX_E_HIP.
  */
@@ -142,9 +143,8 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
 
 /*
  * Tuning knobs, all optional.  Keys:
- *   "tile_bytes"   target bytes of raw text staged per workgroup (default 24576)
- *   "fused"        1: all layers in one launch, each workgroup running the layers
- *                  in order on its own records; 0: one launch per layer (default 0)
+ *   "fused"        1: all layers in one launch, each wavefront running the layers in
+ *                  order on its own 64 records (default); 0: one launch per layer
  *   "profile"      1: time every kernel of fbx_extract with HIP events
  * Errors: FBX_E_ARG for an unknown key or an out-of-range value.
  */

@@ -33,11 +33,10 @@ struct fbx_plan {
   uint64_t ws_bytes = 0;
   // constant-table placement inside the workspace (byte offsets)
   uint64_t off_ctrl = 0, off_dyn = 0, off_ops = 0, off_layer_ops = 0, off_layer_begin = 0, off_nonroot = 0,
-           off_aux = 0, off_row_total = 0, off_static_end = 0;
+           off_aux = 0, off_fields = 0, off_field_ops = 0, off_row_total = 0, off_static_end = 0;
 
   // options
-  uint64_t tile_bytes = 20480;
-  int fused = 0;
+  int fused = 1;
   int profile = 0;
 
   // results of the last call
@@ -60,6 +59,8 @@ struct fbx_plan {
     off_layer_begin = o; o = align_up(o + (host.n_layers + 1) * 4);
     off_nonroot = o; o = align_up(o + host.nonroot_ops.size() * 4);
     off_aux = o; o = align_up(o + host.aux.size());
+    off_fields = o; o = align_up(o + host.fields.size() * sizeof(FieldDesc));
+    off_field_ops = o; o = align_up(o + host.field_ops.size() * 4);
     off_row_total = o; o = align_up(o + host.n_ragged * 8ull);
     off_static_end = o;
   }
@@ -68,30 +69,17 @@ struct fbx_plan {
 namespace {
 
 struct CallGeometry {
-  uint32_t log2T = 0, n_tiles = 0;
-  uint32_t cap_bytes = 0, cap_tabs = 0;
-  uint32_t lds_cnt = 0, lds_tab = 0, lds_mask = 0, lds_bytes = 0, lds_total = 0;
+  uint32_t n_tiles = 0, count_waves = 1;
   uint64_t off_tile_cnt = 0, off_tile_base = 0, arena_base = 0;
 };
 
-CallGeometry geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records) {
+CallGeometry geometry(const fbx_plan& p, uint64_t n_records) {
   CallGeometry g;
-  // records per tile: a power of two whose average byte size is near the target
-  const uint64_t avg = n_records ? std::max<uint64_t>(raw_len / n_records, 1) : 1;
-  uint32_t log2T = 0;
-  while (log2T < 6 && (avg << (log2T + 1)) <= p.tile_bytes) ++log2T;
-  // the per-record count table of the ragged operators has to fit beside the bytes
-  while (log2T > 0 && (uint64_t(p.host.n_ragged) << log2T) * 4 > 16384) --log2T;
-  g.log2T = log2T;
-  g.n_tiles = static_cast<uint32_t>((n_records + (1ull << log2T) - 1) >> log2T);
-  g.cap_bytes = static_cast<uint32_t>(std::min<uint64_t>(align_up(p.tile_bytes * 5 / 4, 16), 65024));
-  g.cap_tabs = g.cap_bytes / 4;
-  uint32_t o = 0;
-  g.lds_cnt = o; o += static_cast<uint32_t>(align_up((uint64_t(std::max(p.host.n_ragged, 1u)) << log2T) * 4, 16));
-  g.lds_tab = o; o += static_cast<uint32_t>(align_up(g.cap_tabs * 2ull, 16));
-  g.lds_mask = o; o += static_cast<uint32_t>(align_up((g.cap_bytes / 16 + 2) * 2ull, 16));
-  g.lds_bytes = o; o += g.cap_bytes + 32;
-  g.lds_total = o;
+  g.n_tiles = static_cast<uint32_t>((n_records + kTile - 1) >> kTileLog2);
+  // counting pass: one 256-byte LDS row per ragged operator and wavefront; as many
+  // wavefronts per workgroup (at most 4) as fit into 48 KB
+  const uint32_t per_wave = std::max(p.host.n_ragged, 1u) * 256u;
+  g.count_waves = std::min(4u, std::max(1u, 49152u / per_wave));
   uint64_t w = p.off_static_end;
   g.off_tile_cnt = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 4);
   g.off_tile_base = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 8);
@@ -168,10 +156,7 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
 fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   if (!plan || !key) return FBX_E_ARG;
   const std::string k(key);
-  if (k == "tile_bytes") {
-    if (value < 1024 || value > 49152) { plan->error = "tile_bytes must be in 1024..49152"; return FBX_E_ARG; }
-    plan->tile_bytes = static_cast<uint64_t>(value);
-  } else if (k == "fused") {
+  if (k == "fused") {
     if (value != 0 && value != 1) { plan->error = "fused must be 0 or 1"; return FBX_E_ARG; }
     plan->fused = static_cast<int>(value);
   } else if (k == "profile") {
@@ -186,7 +171,7 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
 
 fbx_status fbx_plan_workspace_hint(const fbx_plan* plan, uint64_t raw_len, uint64_t n_records, uint64_t* bytes) {
   if (!plan || !bytes) return FBX_E_ARG;
-  const CallGeometry g = geometry(*plan, raw_len, n_records);
+  const CallGeometry g = geometry(*plan, n_records);
   // fixed-arity operators are exact; a ragged root operator cannot emit more
   // signs than its field has bytes + 1, for which raw_len / #fields + records
   // is a fair guess; a ragged cross or concat is guessed at four times that.
@@ -219,6 +204,8 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
   std::memcpy(img.data() + plan->off_layer_begin, h.layer_begin.data(), h.layer_begin.size() * 4);
   if (!h.nonroot_ops.empty()) std::memcpy(img.data() + plan->off_nonroot, h.nonroot_ops.data(), h.nonroot_ops.size() * 4);
   if (!h.aux.empty()) std::memcpy(img.data() + plan->off_aux, h.aux.data(), h.aux.size());
+  if (!h.fields.empty()) std::memcpy(img.data() + plan->off_fields, h.fields.data(), h.fields.size() * sizeof(FieldDesc));
+  if (!h.field_ops.empty()) std::memcpy(img.data() + plan->off_field_ops, h.field_ops.data(), h.field_ops.size() * 4);
   hipError_t e = hipMemcpy(d_workspace, img.data(), img.size(), hipMemcpyHostToDevice);
   if (e != hipSuccess) return hip_fail(plan, e, "copying plan tables");
   plan->ws = static_cast<uint8_t*>(d_workspace);
@@ -237,21 +224,22 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const PlanHost& h = plan->host;
   const uint32_t n_ops = static_cast<uint32_t>(h.ops.size());
-  const CallGeometry g = geometry(*plan, raw_len, n_records);
+  const CallGeometry g = geometry(*plan, n_records);
   if (g.arena_base > plan->ws_bytes) {
     out->arena_high_water = g.arena_base;
     plan->error = "workspace too small for the per-tile tables; need more than " + std::to_string(g.arena_base) + " bytes";
     return FBX_E_NOMEM;
   }
-  if (g.lds_total > 158 * 1024) { plan->error = "LDS budget exceeded"; return FBX_E_ARG; }
 
   uint8_t* ws = plan->ws;
   Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + plan->off_ctrl);
   OpDyn* dyn = reinterpret_cast<OpDyn*>(ws + plan->off_dyn);
-  TileParams P{};
+  WalkParams P{};
   P.raw = d_raw; P.raw_len = raw_len; P.rec_off = d_rec_off; P.n_records = n_records;
   P.ws = ws;
   P.ops = reinterpret_cast<const OpDesc*>(ws + plan->off_ops);
+  P.fields = reinterpret_cast<const FieldDesc*>(ws + plan->off_fields);
+  P.field_ops = reinterpret_cast<const uint32_t*>(ws + plan->off_field_ops);
   P.layer_ops = reinterpret_cast<const uint32_t*>(ws + plan->off_layer_ops);
   P.layer_begin = reinterpret_cast<const uint32_t*>(ws + plan->off_layer_begin);
   P.nonroot = reinterpret_cast<const uint32_t*>(ws + plan->off_nonroot);
@@ -261,9 +249,8 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   P.tile_base = reinterpret_cast<uint64_t*>(ws + g.off_tile_base);
   P.n_ops = n_ops; P.n_layers = h.n_layers; P.n_ragged = h.n_ragged;
   P.n_nonroot = static_cast<uint32_t>(h.nonroot_ops.size());
-  P.n_tiles = g.n_tiles; P.log2T = g.log2T; P.n_fields = h.n_fields;
-  P.cap_bytes = g.cap_bytes; P.cap_tabs = g.cap_tabs;
-  P.lds_cnt = g.lds_cnt; P.lds_tab = g.lds_tab; P.lds_mask = g.lds_mask; P.lds_bytes = g.lds_bytes;
+  P.n_tiles = g.n_tiles; P.n_fields = h.n_fields; P.count_fields = h.count_fields;
+  P.waves_per_block = g.count_waves;
   uint64_t* row_total = reinterpret_cast<uint64_t*>(ws + plan->off_row_total);
 
   // profiling events
@@ -295,13 +282,13 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
 
   FBX_LAUNCH(launch_reset(ctrl, g.arena_base, st), "reset");
   tick(0, 0);
-  FBX_LAUNCH(launch_validate(d_rec_off, n_records, raw_len, g.log2T, ctrl, st), "validate");
+  FBX_LAUNCH(launch_validate(d_rec_off, n_records, raw_len, kTileLog2, ctrl, st), "validate");
   tick(0, 1);
   if (h.n_ragged) {
     if (g.n_tiles) {
       tick(1, 0);
       P.layer_lo = 1; P.layer_hi = h.n_layers;
-      FBX_LAUNCH(launch_tile(P, true, g.lds_total, st), "count kernel");
+      FBX_LAUNCH(launch_count(P, st), "count kernel");
       tick(1, 1);
     }
     tick(2, 0);
@@ -316,14 +303,14 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     if (plan->fused) {
       P.layer_lo = 1; P.layer_hi = h.n_layers;
       tick(4, 0);
-      FBX_LAUNCH(launch_tile(P, false, g.lds_total, st), "tile kernel");
+      FBX_LAUNCH(launch_walk(P, st), "walk kernel");
       tick(4, 1);
       plan->tile_launch_layer.push_back(1);
     } else {
       for (uint32_t l = 1; l <= h.n_layers; ++l) {
         P.layer_lo = P.layer_hi = l;
         tick(3 + l, 0);
-        FBX_LAUNCH(launch_tile(P, false, g.lds_total, st), "tile kernel");
+        FBX_LAUNCH(launch_walk(P, st), "walk kernel");
         tick(3 + l, 1);
         plan->tile_launch_layer.push_back(l);
       }

@@ -34,6 +34,20 @@ struct OpDesc {
 };
 static_assert(sizeof(OpDesc) == 64, "OpDesc must stay 64 bytes");
 
+// Per-field program: which root operators read field k.
+enum FieldClass : uint32_t {
+  FC_SKIP = 0,    // no operator reads the field: only its end is looked for
+  FC_HASH1 = 1,   // exactly one operator, a single-valued hash: hashed while its tab is looked for
+  FC_GENERIC = 2  // anything else: find the end, then run every operator on the span
+};
+struct FieldDesc {
+  uint32_t op_begin;   // into the field_ops table
+  uint32_t op_count;
+  uint32_t cls;        // FieldClass
+  uint32_t need;       // bit 0: some operator needs the comma count of the field
+};
+static_assert(sizeof(FieldDesc) == 16, "FieldDesc must stay 16 bytes");
+
 // Per-call, per-operator placement, written by the allocation kernel.
 struct OpDyn {
   uint64_t values_off;   // byte offset of the values array from the workspace base
@@ -77,6 +91,9 @@ struct PlanHost {
   std::vector<uint32_t> layer_begin;   // n_layers + 1 entries into layer_ops
   std::vector<uint32_t> nonroot_ops;   // operators of layers >= 2, in spec order
   std::vector<uint8_t> aux;            // bounds (8-byte aligned) and prefixes
+  std::vector<FieldDesc> fields;       // n_fields entries
+  std::vector<uint32_t> field_ops;     // root operator indices grouped by field, spec order inside a field
+  uint32_t count_fields = 0;           // the counting pass may stop after this many fields
 };
 
 // Returns FBX_OK or FBX_E_SPEC (message in err).

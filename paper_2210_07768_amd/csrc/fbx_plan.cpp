@@ -296,8 +296,26 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
     }
   }
   while (plan.aux.size() % 16) plan.aux.push_back(0);
-  if (plan.n_ragged > 2048) {
-    err = "more than 2048 ragged operators";
+  // field programs: the root operators of every field, and how the field is walked
+  plan.fields.assign(plan.n_fields, FieldDesc{0, 0, FC_SKIP, 0});
+  for (uint32_t k = 0; k < plan.n_fields; ++k) {
+    FieldDesc& f = plan.fields[k];
+    f.op_begin = static_cast<uint32_t>(plan.field_ops.size());
+    for (uint32_t i = 0; i < plan.ops.size(); ++i) {
+      const OpDesc& d = plan.ops[i].d;
+      if (d.layer != 1 || d.field != k) continue;
+      plan.field_ops.push_back(i);
+      ++f.op_count;
+      if ((d.kind == OP_HASH || d.kind == OP_BUCKET) && (d.flags & F_MULTI)) f.need |= 1u;
+      if (d.arity == 0) plan.count_fields = k + 1;
+    }
+    if (f.op_count == 0) f.cls = FC_SKIP;
+    else if (f.op_count == 1 && plan.ops[plan.field_ops[f.op_begin]].d.kind == OP_HASH &&
+             !(plan.ops[plan.field_ops[f.op_begin]].d.flags & F_MULTI)) f.cls = FC_HASH1;
+    else f.cls = FC_GENERIC;
+  }
+  if (plan.n_ragged > 512) {
+    err = "more than 512 ragged operators";
     return FBX_E_SPEC;
   }
   return FBX_OK;

@@ -1,0 +1,223 @@
+// Support kernels of libfbx: per-call reset and input validation, the scan that
+// turns per-tile counts into per-tile bases, and the arena (Algorithm 1 of the
+// paper and the per-call carving of operator arrays).
+#include <hip/hip_runtime.h>
+
+#include "fbx_device.h"
+
+namespace fbx {
+
+// --------------------------------------------------------------- validation
+__global__ void k_reset(Ctrl* ctrl, uint64_t arena_base) {
+  if (threadIdx.x == 0) {
+    ctrl->err = 0; ctrl->pad0 = 0; ctrl->required = 0; ctrl->head = arena_base; ctrl->high_water = arena_base;
+    ctrl->n_malformed = 0; ctrl->max_tile_bytes = 0; ctrl->slow_tiles = 0; ctrl->pad1 = 0;
+  }
+}
+
+__global__ void k_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t raw_len, uint32_t log2T, Ctrl* ctrl) {
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_records) return;
+  const uint64_t a = rec_off[i], b = rec_off[i + 1];
+  uint32_t err = 0;
+  if (a > b || b > raw_len) err |= CE_OFFSETS;
+  if ((i & ((1ull << log2T) - 1)) == 0) {
+    const uint64_t j = i + (1ull << log2T) < n_records ? i + (1ull << log2T) : n_records;
+    const uint64_t hi = rec_off[j];
+    if (hi >= a) {
+      if (hi - a >= (1ull << 31)) err |= CE_TILE;
+      atomicMax(reinterpret_cast<unsigned long long*>(&ctrl->max_tile_bytes), (unsigned long long)(hi - a));
+    }
+  }
+  if (err) atomicOr(&ctrl->err, err);
+}
+
+// --------------------------------------------------------------------- scan
+// Exclusive scan over tiles of one ragged operator's per-tile counts.
+__global__ __launch_bounds__(kBlock) void k_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total,
+                                                 uint32_t n_tiles, const Ctrl* ctrl) {
+  __shared__ uint64_t s[kBlock];
+  if (ctrl->err) return;
+  const uint32_t row = blockIdx.x, tid = threadIdx.x;
+  const uint32_t* src = tile_cnt + (uint64_t)row * n_tiles;
+  uint64_t* dst = tile_base + (uint64_t)row * n_tiles;
+  const uint32_t chunk = (n_tiles + kBlock - 1) / kBlock;
+  const uint32_t lo = min(tid * chunk, n_tiles), hi = min(lo + chunk, n_tiles);
+  uint64_t sum = 0;
+  for (uint32_t i = lo; i < hi; ++i) sum += src[i];
+  s[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < kBlock; d <<= 1) {
+    uint64_t t = tid >= (uint32_t)d ? s[tid - d] : 0;
+    __syncthreads();
+    s[tid] += t;
+    __syncthreads();
+  }
+  uint64_t run = s[tid] - sum;
+  for (uint32_t i = lo; i < hi; ++i) { dst[i] = run; run += src[i]; }
+  if (tid == kBlock - 1) row_total[row] = s[tid];
+}
+
+// ------------------------------------------------------------------- arena
+__device__ __forceinline__ uint64_t round128(uint64_t x) { return (x + 127ull) & ~127ull; }
+
+// Algorithm 1 of the paper (Section 5): every thread of the block brings a
+// size; the block takes a prefix sum, ONE thread adds the block's total to the
+// idle-memory head with an atomic add, and every thread's offset is the old
+// head plus the sizes of the threads before it.  (The listing subtracts the
+// first thread's prefix, which is only right for equal sizes; the prose and
+// the figure call for the exclusive prefix, which is what is computed here.)
+// The block total is rounded up to 128 bytes so that every block starts on a
+// 128-byte line, as the paper asks.  s_scan must hold blockDim.x entries.
+__device__ uint64_t arena_alloc_block(uint64_t* head, uint64_t size, uint64_t* s_scan, uint64_t* s_addr) {
+  const uint32_t tid = threadIdx.x, n = blockDim.x;
+  s_scan[tid] = size;
+  __syncthreads();
+  for (uint32_t d = 1; d < n; d <<= 1) {
+    uint64_t t = tid >= d ? s_scan[tid - d] : 0;
+    __syncthreads();
+    s_scan[tid] += t;
+    __syncthreads();
+  }
+  const uint64_t incl = s_scan[tid];
+  if (tid == 0) {
+    const uint64_t total = round128(s_scan[n - 1]);
+    *s_addr = total ? atomicAdd(reinterpret_cast<unsigned long long*>(head), (unsigned long long)total)
+                    : *reinterpret_cast<volatile uint64_t*>(head);
+  }
+  __syncthreads();
+  const uint64_t out = *s_addr + incl - size;
+  __syncthreads();
+  return out;
+}
+
+__global__ void k_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets) {
+  extern __shared__ __align__(16) uint8_t dyn_smem[];
+  uint64_t* s_scan = reinterpret_cast<uint64_t*>(dyn_smem);
+  __shared__ uint64_t s_addr;
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t size = i < n ? sizes[i] : 0;
+  const uint64_t off = arena_alloc_block(head, size, s_scan, &s_addr);
+  if (i < n) offsets[i] = off;
+}
+
+__global__ void k_arena_reset(uint64_t* head, uint64_t value) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *head = value;
+}
+
+// Carve the operators' value / offset arrays out of the pool, once sizes are
+// known.  Emitted operators first (they live until the next call); then layer
+// by layer the intermediates born in that layer, and after each layer the head
+// drops back as far as still-live intermediates allow: the constant-time reset
+// of Section 5 ("Reset GPU memory pool"), generalised to outputs that a later
+// layer still reads.  With reuse off (all layers in one launch) nothing is
+// released.  One block of kBlock threads.
+__global__ __launch_bounds__(kBlock) void k_alloc(const OpDesc* ops, OpDyn* dyn, uint32_t n_ops, uint32_t n_layers,
+                                                  const uint64_t* row_total, uint64_t n_records, uint64_t ws_bytes,
+                                                  uint8_t* ws, int reuse, Ctrl* ctrl) {
+  __shared__ uint64_t s_scan[kBlock];
+  __shared__ uint64_t s_addr;
+  __shared__ unsigned long long s_max;
+  if (ctrl->err) return;
+  const uint32_t tid = threadIdx.x;
+  uint64_t high = ctrl->head;
+  uint64_t persist_end = high;  // end of the emitted operators' storage
+  for (uint32_t pass = 0; pass <= n_layers; ++pass) {  // pass 0: emitted; pass l: intermediates of layer l
+    for (uint32_t c0 = 0; c0 < n_ops; c0 += kBlock) {
+      const uint32_t i = c0 + tid;
+      uint64_t sv = 0, so = 0, nv = 0;
+      bool mine = false;
+      if (i < n_ops) {
+        const OpDesc& d = ops[i];
+        const bool emit = d.flags & F_EMIT;
+        mine = pass == 0 ? emit : (!emit && d.layer == pass);
+        if (mine) {
+          nv = d.arity ? n_records * d.arity : row_total[d.rag_row];
+          sv = round128(nv * 8ull);
+          so = d.arity ? 0 : round128((n_records + 1) * 8ull);
+        }
+      }
+      const uint64_t off = arena_alloc_block(&ctrl->head, sv + so, s_scan, &s_addr);
+      if (mine) {
+        dyn[i].values_off = off;
+        dyn[i].offsets_off = so ? off + sv : 0;
+        dyn[i].n_values = nv;
+        dyn[i].pad = off + sv + so;  // end of this operator's storage
+      }
+    }
+    __threadfence();
+    __syncthreads();
+    const uint64_t head_now = *reinterpret_cast<volatile uint64_t*>(&ctrl->head);
+    if (head_now > high) high = head_now;
+    if (pass == 0) persist_end = head_now;
+    if (pass >= 1 && reuse) {
+      // release: the head drops to the end of the highest still-live intermediate
+      if (tid == 0) s_max = persist_end;
+      __syncthreads();
+      unsigned long long m = 0;
+      for (uint32_t i = tid; i < n_ops; i += kBlock) {
+        const OpDesc& d = ops[i];
+        if (!(d.flags & F_EMIT) && d.layer <= pass && d.death > pass) m = max(m, (unsigned long long)dyn[i].pad);
+      }
+      atomicMax(&s_max, m);
+      __syncthreads();
+      if (tid == 0) *reinterpret_cast<volatile uint64_t*>(&ctrl->head) = s_max;
+      __threadfence();
+      __syncthreads();
+    }
+  }
+  if (tid == 0) {
+    ctrl->high_water = high;
+    ctrl->required = high;
+    if (high > ws_bytes) atomicOr(&ctrl->err, (uint32_t)CE_NOMEM);
+  }
+  // an empty batch still owes every ragged slot its single offset entry
+  if (n_records == 0 && high <= ws_bytes) {
+    for (uint32_t i = tid; i < n_ops; i += kBlock)
+      if (!ops[i].arity) *reinterpret_cast<uint64_t*>(ws + dyn[i].offsets_off) = 0;
+  }
+}
+
+// ----------------------------------------------------------- launch wrappers
+hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st) {
+  hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctrl, arena_base);
+  return hipGetLastError();
+}
+
+hipError_t launch_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t raw_len, uint32_t log2T, Ctrl* ctrl,
+                           hipStream_t st) {
+  if (n_records == 0) return hipSuccess;
+  const uint64_t blocks = (n_records + 255) / 256;
+  hipLaunchKernelGGL(k_validate, dim3((uint32_t)blocks), dim3(256), 0, st, rec_off, n_records, raw_len, log2T, ctrl);
+  return hipGetLastError();
+}
+
+hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total, uint32_t n_ragged,
+                       uint32_t n_tiles, const Ctrl* ctrl, hipStream_t st) {
+  if (n_ragged == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_scan, dim3(n_ragged), dim3(kBlock), 0, st, tile_cnt, tile_base, row_total, n_tiles, ctrl);
+  return hipGetLastError();
+}
+
+hipError_t launch_alloc(const OpDesc* ops, OpDyn* dyn, uint32_t n_ops, uint32_t n_layers, const uint64_t* row_total,
+                        uint64_t n_records, uint64_t ws_bytes, uint8_t* ws, int reuse, Ctrl* ctrl, hipStream_t st) {
+  hipLaunchKernelGGL(k_alloc, dim3(1), dim3(kBlock), 0, st, ops, dyn, n_ops, n_layers, row_total, n_records, ws_bytes,
+                     ws, reuse, ctrl);
+  return hipGetLastError();
+}
+
+hipError_t launch_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets, uint32_t threads,
+                              hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const uint64_t blocks = (n + threads - 1) / threads;
+  hipLaunchKernelGGL(k_arena_alloc, dim3((uint32_t)blocks), dim3(threads), threads * sizeof(uint64_t), st, head, sizes,
+                     n, offsets);
+  return hipGetLastError();
+}
+
+hipError_t launch_arena_reset(uint64_t* head, uint64_t value, hipStream_t st) {
+  hipLaunchKernelGGL(k_arena_reset, dim3(1), dim3(64), 0, st, head, value);
+  return hipGetLastError();
+}
+
+}  // namespace fbx

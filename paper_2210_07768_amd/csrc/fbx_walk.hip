@@ -1,0 +1,556 @@
+// The walk kernels of libfbx for gfx950 (MI355X): counting pass and writing pass.
+//
+// Work decomposition.  Records are independent (every operator computes on one
+// row of the table; Section 3, "Extract features"), so one wavefront owns a tile
+// of 64 consecutive records, one record per lane, and walks the fields of its
+// records in lock step: field 0 of all 64 records, then field 1, and so on.
+// Which operators read field k is the same for every record, so all control
+// flow that depends on the plan is wave-uniform and runs on the scalar unit; a
+// lane only diverges from its neighbours by the length of its own field.
+//
+//  * Raw bytes are read in place: a lane loads a 16-byte window at its current
+//    position (4-byte aligned, funnel-shifted into place) and takes its bytes
+//    out of registers.  The 64 windows of a wavefront lie in 64 different
+//    records; they are served by L2, and every raw byte comes from HBM once.
+//  * Splitting at the delimiter (Section 5, first paragraph) needs no array
+//    here: the end of a field is found by the same loop that hashes it.
+//  * A fixed-arity slot is written by 64 lanes to 64 consecutive u64: one
+//    512-byte store per wavefront and operator.
+//  * A ragged slot needs the tile's base inside the slot (from the counting
+//    pass and the scan over tiles) plus a prefix sum over the 64 lanes.
+//  * Later layers run in the same lane on the signs that lane wrote itself, so
+//    executing all layers in one launch needs no synchronisation between
+//    wavefronts at all; the per-layer launch of the paper (Section 4) is the
+//    same kernel restricted to one layer.
+#include <hip/hip_runtime.h>
+
+#include "fbx_device.h"
+
+namespace fbx {
+
+constexpr uint32_t kNoRow = 0xffffffffu;
+constexpr uint64_t kPrime = 0x100000001b3ull;
+constexpr uint32_t kWin = 12;  // bytes of a window that are always valid after alignment
+
+// ------------------------------------------------------------ small helpers
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  x = (x ^ (x >> 30)) * 0xbf58476d1ce4e5b9ull;
+  x = (x ^ (x >> 27)) * 0x94d049bb133111ebull;
+  return x ^ (x >> 31);
+}
+
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  const uint32_t lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t t = __shfl_up(v, d, 64);
+    if (lane >= (uint32_t)d) v += t;
+  }
+  return v;
+}
+
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// ------------------------------------------------------------ byte windows
+// Per-wavefront view of the raw buffer.  Positions are 32-bit offsets from the
+// first byte of the tile (a tile spans less than 2 GiB; checked beforehand).
+struct Ctx {
+  const uint8_t* base4;  // 4-byte aligned address at or just before tile byte 0
+  uint32_t delta;        // tile byte 0 is base4[delta], delta in 0..3
+  uint32_t lo_valid;     // base4[o] lies inside the raw buffer iff lo_valid <= o < hi_valid
+  uint32_t hi_valid;
+};
+
+struct Win { uint32_t a, b, c; };  // 12 bytes starting at the requested position
+
+__device__ __forceinline__ Win load_win(const Ctx& c, uint32_t p) {
+  const uint32_t o = p + c.delta, qa = o & ~3u, sh = (o & 3u) * 8u;
+  uint32_t w0, w1, w2, w3;
+  if (qa >= c.lo_valid && qa + 16u <= c.hi_valid) {
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(__builtin_assume_aligned(c.base4 + qa, 4));
+    w0 = src[0]; w1 = src[1]; w2 = src[2]; w3 = src[3];
+  } else {
+    // window straddles an end of the buffer: fetch what exists byte by byte
+    uint32_t w[4] = {0, 0, 0, 0};
+    for (uint32_t i = 0; i < 16; ++i) {
+      const uint32_t oi = qa + i;
+      if (oi >= c.lo_valid && oi < c.hi_valid) w[i >> 2] |= (uint32_t)c.base4[oi] << (8u * (i & 3u));
+    }
+    w0 = w[0]; w1 = w[1]; w2 = w[2]; w3 = w[3];
+  }
+  Win r;
+  r.a = __builtin_amdgcn_alignbit(w1, w0, sh);
+  r.b = __builtin_amdgcn_alignbit(w2, w1, sh);
+  r.c = __builtin_amdgcn_alignbit(w3, w2, sh);
+  return r;
+}
+
+__device__ __forceinline__ uint32_t load_byte(const Ctx& c, uint32_t p) { return c.base4[p + c.delta]; }
+
+template <int J>
+__device__ __forceinline__ uint32_t win_byte(const Win& w) {
+  const uint32_t d = J < 4 ? w.a : (J < 8 ? w.b : w.c);
+  return (d >> (8 * (J & 3))) & 0xffu;
+}
+
+// 0x80 in (at least) the lowest zero byte of x; bytes above a zero byte may be flagged too.
+__device__ __forceinline__ uint32_t zero_low(uint32_t x) { return (x - 0x01010101u) & ~x & 0x80808080u; }
+// 0x80 in exactly the zero bytes of x.
+__device__ __forceinline__ uint32_t zero_exact(uint32_t x) {
+  return ~(((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x | 0x7f7f7f7fu);
+}
+
+// Index of the first tab among the first n (<= 12) bytes of the window, or n.
+__device__ __forceinline__ uint32_t first_tab(const Win& w, uint32_t n) {
+  const uint32_t t0 = zero_low(w.a ^ 0x09090909u), t1 = zero_low(w.b ^ 0x09090909u), t2 = zero_low(w.c ^ 0x09090909u);
+  uint32_t idx = 12;
+  if (t2) idx = 8 + ((__ffs(t2) - 1) >> 3);
+  if (t1) idx = 4 + ((__ffs(t1) - 1) >> 3);
+  if (t0) idx = (__ffs(t0) - 1) >> 3;
+  return idx < n ? idx : n;
+}
+
+// Number of commas among the first m (<= 12) bytes of the window.
+__device__ __forceinline__ uint32_t count_commas(const Win& w, uint32_t m) {
+  const uint32_t f[3] = {zero_exact(w.a ^ 0x2c2c2c2cu), zero_exact(w.b ^ 0x2c2c2c2cu), zero_exact(w.c ^ 0x2c2c2c2cu)};
+  uint32_t c = 0;
+#pragma unroll
+  for (int d = 0; d < 3; ++d) {
+    const uint32_t v = m > 4u * d ? (m - 4u * d < 4u ? m - 4u * d : 4u) : 0u;  // valid bytes of this dword
+    const uint32_t mask = v >= 4u ? 0xffffffffu : ((1u << (8u * v)) - 1u);
+    c += __popc(f[d] & mask);
+  }
+  return c;
+}
+
+// End of the field that starts at pos: position of its tab, or the end of the
+// record.  With COMMAS the commas of the field are counted on the way.
+template <bool COMMAS>
+__device__ __forceinline__ uint32_t find_end(const Ctx& c, uint32_t pos, uint32_t end, uint32_t& commas) {
+  uint32_t p = pos;
+  commas = 0;
+  while (p < end) {
+    const uint32_t n = end - p < kWin ? end - p : kWin;
+    const Win w = load_win(c, p);
+    const uint32_t i = first_tab(w, n);
+    if (COMMAS) commas += count_commas(w, i);
+    p += i;
+    if (i < n) break;
+  }
+  return p;
+}
+
+// Calls f(byte) for every byte of [s, e), in order.
+template <class F>
+__device__ __forceinline__ void for_each_byte(const Ctx& c, uint32_t s, uint32_t e, F&& f) {
+  for (uint32_t p = s; p < e; p += kWin) {
+    const uint32_t n = e - p < kWin ? e - p : kWin;
+    const Win w = load_win(c, p);
+#define FBX_STEP(J) if ((uint32_t)J >= n) continue; f(win_byte<J>(w));
+    FBX_STEP(0) FBX_STEP(1) FBX_STEP(2) FBX_STEP(3) FBX_STEP(4) FBX_STEP(5)
+    FBX_STEP(6) FBX_STEP(7) FBX_STEP(8) FBX_STEP(9) FBX_STEP(10) FBX_STEP(11)
+#undef FBX_STEP
+  }
+}
+
+// Single-valued hash of the field at pos, fused with the search for its tab.
+// Returns the position of the field's end (its tab, or the end of the record).
+__device__ __forceinline__ uint32_t hash_to_tab(const Ctx& c, uint32_t pos, uint32_t end, uint64_t& h) {
+  uint32_t p = pos;
+  while (p < end) {
+    const uint32_t n = end - p < kWin ? end - p : kWin;
+    const Win w = load_win(c, p);
+    uint32_t j = 0;
+    bool tab = false;
+#define FBX_STEP(J)                                  \
+    if (!tab && (uint32_t)J < n) {                   \
+      const uint32_t b = win_byte<J>(w);             \
+      if (b == '\t') tab = true;                     \
+      else { h = (h ^ b) * kPrime; j = J + 1; }      \
+    }
+    FBX_STEP(0) FBX_STEP(1) FBX_STEP(2) FBX_STEP(3) FBX_STEP(4) FBX_STEP(5)
+    FBX_STEP(6) FBX_STEP(7) FBX_STEP(8) FBX_STEP(9) FBX_STEP(10) FBX_STEP(11)
+#undef FBX_STEP
+    p += j;
+    if (tab) break;
+  }
+  return p;
+}
+
+// ------------------------------------------------------------ token operators
+struct NumState {
+  uint64_t ip = 0, fp = 0;
+  uint32_t digits = 0, nfrac = 0, st = 0;  // st: 0 start, 1 integer part, 2 fraction, 3 stopped early
+  bool neg = false;
+  __device__ __forceinline__ void step(uint32_t b) {
+    if (st == 3) return;
+    if (st == 0) {
+      st = 1;
+      if (b == '-') { neg = true; return; }
+    }
+    const uint32_t d = b - '0';
+    if (st == 1) {
+      if (d <= 9) { ip = ip * 10u + d; ++digits; }
+      else if (b == '.') st = 2;
+      else st = 3;
+    } else {
+      if (d <= 9) {
+        if (nfrac < 6) { fp = fp * 10u + d; ++nfrac; }
+        ++digits;
+      } else st = 3;
+    }
+  }
+  // signed micro-units; bad when the text was not wholly -?digits*(.digits*)? with a digit
+  __device__ __forceinline__ int64_t finish(bool& bad) {
+    for (; nfrac < 6; ++nfrac) fp *= 10u;
+    uint64_t v = ip * 1000000ull + fp;
+    if (neg) v = 0ull - v;
+    bad = st == 3 || digits == 0;
+    return (int64_t)v;
+  }
+};
+
+__device__ __forceinline__ uint64_t bucket_sign(const OpDesc& d, const uint8_t* aux, NumState& ns, uint32_t& malformed) {
+  bool bad;
+  const int64_t v = ns.finish(bad);
+  malformed += bad ? 1u : 0u;
+  const int64_t* b = reinterpret_cast<const int64_t*>(aux + d.aux_off);
+  uint32_t lo = 0, hi = d.aux_len;  // index = number of boundaries <= v
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (b[mid] <= v) lo = mid + 1; else hi = mid;
+  }
+  return mix64(d.key + lo);
+}
+
+// Number of signs a ragged root operator (not n-gram) produces on [s, e); commas = #',' in the span.
+__device__ __forceinline__ uint32_t ragged_root_count(const Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s,
+                                                      uint32_t e, uint32_t commas) {
+  if (d.kind != OP_FILTER) return commas + 1;  // multi-valued hash / bucket
+  const uint8_t* pre = aux + d.aux_off;
+  const uint32_t plen = d.aux_len;
+  const bool multi = d.flags & F_MULTI;
+  uint32_t cnt = 0, k = 0;
+  bool match = true;
+  for_each_byte(c, s, e, [&](uint32_t b) {
+    if (multi && b == ',') {
+      cnt += (match && k >= plen) ? 1u : 0u;
+      k = 0; match = true;
+    } else {
+      if (k < plen && b != pre[k]) match = false;
+      ++k;
+    }
+  });
+  cnt += (match && k >= plen) ? 1u : 0u;
+  return cnt;
+}
+
+// Writes the signs of a root operator (not n-gram) on [s, e) to dst[0 .. count).
+__device__ __forceinline__ void root_emit(const Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s, uint32_t e,
+                                          uint64_t* dst, uint32_t& malformed) {
+  const bool multi = d.flags & F_MULTI;
+  if (d.kind == OP_HASH) {
+    uint64_t h = d.key;
+    for_each_byte(c, s, e, [&](uint32_t b) {
+      if (multi && b == ',') { *dst++ = h; h = d.key; }
+      else h = (h ^ b) * kPrime;
+    });
+    *dst = h;
+  } else if (d.kind == OP_FILTER) {
+    const uint8_t* pre = aux + d.aux_off;
+    const uint32_t plen = d.aux_len;
+    uint64_t h = d.key;
+    uint32_t k = 0;
+    bool match = true;
+    for_each_byte(c, s, e, [&](uint32_t b) {
+      if (multi && b == ',') {
+        if (match && k >= plen) *dst++ = h;
+        h = d.key; k = 0; match = true;
+      } else {
+        if (k < plen && b != pre[k]) match = false;
+        h = (h ^ b) * kPrime;
+        ++k;
+      }
+    });
+    if (match && k >= plen) *dst = h;
+  } else {  // OP_BUCKET
+    NumState ns;
+    for_each_byte(c, s, e, [&](uint32_t b) {
+      if (multi && b == ',') {
+        *dst++ = bucket_sign(d, aux, ns, malformed);
+        ns = NumState();
+      } else ns.step(b);
+    });
+    *dst = bucket_sign(d, aux, ns, malformed);
+  }
+}
+
+// ------------------------------------------------------------ tile set-up
+struct Tile {
+  Ctx ctx;
+  uint32_t tile;
+  uint64_t g;      // this lane's record
+  bool live;       // false in the lanes past the last record
+  uint32_t pos, end;
+};
+
+// Which tile this wavefront owns.  Consecutive workgroup ids are dealt
+// round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so that
+// neighbouring tiles, whose outputs share cache lines, share an L2.
+__device__ __forceinline__ bool tile_of_wave(uint32_t n_tiles, uint32_t waves_per_block, uint32_t& tile) {
+  const uint32_t chunk = gridDim.x >> 3;
+  const uint32_t blk = (blockIdx.x & 7u) * chunk + (blockIdx.x >> 3);
+  tile = blk * waves_per_block + (threadIdx.x >> 6);
+  return tile < n_tiles;
+}
+
+__device__ __forceinline__ void open_tile(const WalkParams& P, Tile& t, bool need_raw) {
+  const uint64_t g0 = (uint64_t)t.tile << kTileLog2;
+  t.g = g0 + lane_id();
+  t.live = t.g < P.n_records;
+  t.pos = t.end = 0;
+  if (!need_raw) return;
+  uint64_t a = 0, b = 0;
+  if (t.live) { a = P.rec_off[t.g]; b = P.rec_off[t.g + 1]; }
+  const uint64_t tile_lo = uniform64(a);  // lane 0 is always live
+  const uintptr_t t0 = reinterpret_cast<uintptr_t>(P.raw) + tile_lo;
+  const uintptr_t base4 = t0 & ~uintptr_t(3);
+  const uintptr_t raw0 = reinterpret_cast<uintptr_t>(P.raw);
+  t.ctx.base4 = reinterpret_cast<const uint8_t*>(base4);
+  t.ctx.delta = (uint32_t)(t0 & 3u);
+  t.ctx.lo_valid = raw0 > base4 ? (uint32_t)(raw0 - base4) : 0u;
+  const uint64_t hi = raw0 + P.raw_len - base4;
+  t.ctx.hi_valid = hi > 0xffffffffull ? 0xffffffffu : (uint32_t)hi;
+  if (t.live) {
+    t.pos = (uint32_t)(a - tile_lo);
+    t.end = (uint32_t)(b - tile_lo);
+    // one trailing newline is not part of the record
+    if (t.end > t.pos && load_byte(t.ctx, t.end - 1) == '\n') --t.end;
+  }
+}
+
+// Base of this tile inside a ragged operator's value array plus the lane's
+// exclusive prefix: where the lane's signs start.  Also writes the lane's two
+// offsets entries (each lane writes its own end too, so that a lane can later
+// read back both of its entries without relying on a neighbour).
+__device__ __forceinline__ uint64_t place_ragged(const WalkParams& P, const Tile& t, uint32_t op, uint32_t row,
+                                                 uint32_t cnt) {
+  const uint32_t incl = wave_incl_scan(cnt);
+  const uint64_t start = P.tile_base[(uint64_t)row * P.n_tiles + t.tile] + (incl - cnt);
+  if (t.live) {
+    uint64_t* off = reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].offsets_off);
+    off[t.g] = start;
+    off[t.g + 1] = start + cnt;
+  }
+  return start;
+}
+
+// This lane's list of an earlier operator.
+__device__ __forceinline__ void input_list(const WalkParams& P, uint32_t op, uint64_t g, const uint64_t*& ptr,
+                                           uint32_t& n) {
+  const OpDesc& d = P.ops[op];
+  const OpDyn& y = P.dyn[op];
+  const uint64_t* vals = reinterpret_cast<const uint64_t*>(P.ws + y.values_off);
+  if (d.arity) {
+    n = d.arity;
+    ptr = vals + g * d.arity;
+  } else {
+    const uint64_t* off = reinterpret_cast<const uint64_t*>(P.ws + y.offsets_off);
+    const uint64_t o0 = off[g], o1 = off[g + 1];
+    n = (uint32_t)(o1 - o0);
+    ptr = vals + o0;
+  }
+}
+
+// ------------------------------------------------------------ counting pass
+// Per tile and ragged operator: how many signs the tile's 64 records produce.
+// Dynamic LDS: one row of 64 u32 per ragged operator and wavefront.
+__global__ __launch_bounds__(kBlock) void k_count(WalkParams P) {
+  extern __shared__ __align__(16) uint32_t s_cnt[];
+  if (P.ctrl->err) return;  // an earlier kernel of this call found a problem
+  Tile t;
+  if (!tile_of_wave(P.n_tiles, P.waves_per_block, t.tile)) return;
+  open_tile(P, t, true);
+  const uint32_t lane = lane_id();
+  uint32_t* cnt = s_cnt + (size_t)(threadIdx.x >> 6) * P.n_ragged * 64u;  // [row][lane], this wavefront's rows
+  for (uint32_t k = 0; k < P.count_fields; ++k) {
+    const FieldDesc fd = P.fields[k];
+    uint32_t commas, e;
+    if (fd.need & 1u) e = find_end<true>(t.ctx, t.pos, t.end, commas);
+    else e = find_end<false>(t.ctx, t.pos, t.end, commas);
+    for (uint32_t q = 0; q < fd.op_count; ++q) {
+      const OpDesc& d = P.ops[P.field_ops[fd.op_begin + q]];
+      if (d.rag_row == kNoRow) continue;
+      uint32_t c;
+      if (d.kind == OP_NGRAM) {
+        const uint32_t L = e > t.pos ? e - t.pos : 0u;
+        c = L >= d.aux_len ? L - d.aux_len + 1 : 0u;
+      } else {
+        c = ragged_root_count(t.ctx, d, P.aux, t.pos, e, commas);
+      }
+      cnt[d.rag_row * 64u + lane] = t.live ? c : 0u;
+    }
+    t.pos = e + 1;
+  }
+  // counts of the later layers follow from the inputs' counts, record by record
+  bool overflow = false;
+  for (uint32_t k = 0; k < P.n_nonroot; ++k) {
+    const OpDesc& d = P.ops[P.nonroot[k]];
+    if (d.rag_row == kNoRow) continue;
+    const OpDesc& da = P.ops[d.a];
+    const OpDesc& db = P.ops[d.b];
+    const uint64_t ca = da.arity ? da.arity : cnt[da.rag_row * 64u + lane];
+    const uint64_t cb = db.arity ? db.arity : cnt[db.rag_row * 64u + lane];
+    const uint64_t c = d.kind == OP_CROSS ? ca * cb : ca + cb;
+    if (c > 0x3ffffffull) overflow = true;  // keeps a tile's total below 2^32
+    cnt[d.rag_row * 64u + lane] = t.live ? (uint32_t)c : 0u;
+  }
+  for (uint32_t row = 0; row < P.n_ragged; ++row) {
+    const uint32_t c = cnt[row * 64u + lane];
+    if (c > 0x3ffffffu) overflow = true;
+    const uint64_t sum = wave_sum64(c);
+    if (lane == 0) P.tile_cnt[(uint64_t)row * P.n_tiles + t.tile] = (uint32_t)sum;
+  }
+  if (overflow) atomicOr(&P.ctrl->err, (uint32_t)CE_OVERFLOW);
+}
+
+// ------------------------------------------------------------- writing pass
+__device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_t& malformed) {
+  const uint32_t lane = lane_id();
+  for (uint32_t k = 0; k < P.n_fields; ++k) {
+    const FieldDesc fd = P.fields[k];
+    if (fd.cls == FC_HASH1) {
+      const uint32_t op = P.field_ops[fd.op_begin];
+      uint64_t h = P.ops[op].key;
+      const uint32_t e = hash_to_tab(t.ctx, t.pos, t.end, h);
+      if (t.live) reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].values_off)[t.g] = h;
+      t.pos = e + 1;
+      continue;
+    }
+    uint32_t commas, e;
+    if (fd.need & 1u) e = find_end<true>(t.ctx, t.pos, t.end, commas);
+    else e = find_end<false>(t.ctx, t.pos, t.end, commas);
+    for (uint32_t q = 0; q < fd.op_count; ++q) {
+      const uint32_t op = P.field_ops[fd.op_begin + q];
+      const OpDesc& d = P.ops[op];
+      uint64_t* vals = reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].values_off);
+      if (d.kind == OP_NGRAM) {
+        // lanes over the grams of one record at a time: balanced and coalesced
+        const uint32_t L = e > t.pos ? e - t.pos : 0u;
+        const uint32_t n = d.aux_len;
+        const uint32_t ng = (t.live && L >= n) ? L - n + 1 : 0u;
+        const uint64_t start = place_ragged(P, t, op, d.rag_row, ng);
+        for (int r = 0; r < kTile; ++r) {
+          const uint32_t ng_r = __shfl(ng, r, 64);
+          if (ng_r == 0) continue;
+          const uint32_t s_r = __shfl(t.pos, r, 64);
+          const uint64_t start_r = __shfl(start, r, 64);
+          for (uint32_t g = lane; g < ng_r; g += 64) {
+            const Win w = load_win(t.ctx, s_r + g);
+            uint64_t h = d.key;
+#define FBX_STEP(J) if ((uint32_t)J < n) h = (h ^ win_byte<J>(w)) * kPrime;
+            FBX_STEP(0) FBX_STEP(1) FBX_STEP(2) FBX_STEP(3) FBX_STEP(4) FBX_STEP(5) FBX_STEP(6) FBX_STEP(7)
+#undef FBX_STEP
+            vals[start_r + g] = h;
+          }
+        }
+        continue;
+      }
+      uint64_t* dst;
+      if (d.arity) {
+        dst = vals + t.g;  // single-valued hash or bucket: arity 1
+      } else {
+        const uint32_t c = t.live ? ragged_root_count(t.ctx, d, P.aux, t.pos, e, commas) : 0u;
+        dst = vals + place_ragged(P, t, op, d.rag_row, c);
+      }
+      if (t.live) root_emit(t.ctx, d, P.aux, t.pos, e, dst, malformed);  // a filter that keeps nothing writes nothing
+    }
+    t.pos = e + 1;
+  }
+}
+
+__device__ __forceinline__ void run_layer(const WalkParams& P, const Tile& t, uint32_t layer) {
+  const uint32_t l0 = P.layer_begin[layer - 1], l1 = P.layer_begin[layer];
+  for (uint32_t q = l0; q < l1; ++q) {
+    const uint32_t op = P.layer_ops[q];
+    const OpDesc& d = P.ops[op];
+    uint64_t* vals = reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].values_off);
+    const uint64_t* pa = nullptr; const uint64_t* pb = nullptr;
+    uint32_t na = 0, nb = 0;
+    if (t.live) {
+      input_list(P, d.a, t.g, pa, na);
+      input_list(P, d.b, t.g, pb, nb);
+    }
+    uint64_t* dst;
+    if (d.arity) {
+      dst = vals + t.g * d.arity;
+    } else {
+      const uint32_t c = d.kind == OP_CROSS ? na * nb : na + nb;
+      dst = vals + place_ragged(P, t, op, d.rag_row, c);
+    }
+    if (!t.live) continue;
+    if (d.kind == OP_CROSS) {
+      for (uint32_t i = 0; i < na; ++i) {
+        const uint64_t ma = mix64(pa[i] + d.key);
+        for (uint32_t j = 0; j < nb; ++j) *dst++ = mix64(ma + pb[j]);
+      }
+    } else {
+      for (uint32_t i = 0; i < na; ++i) *dst++ = pa[i];
+      for (uint32_t j = 0; j < nb; ++j) *dst++ = pb[j];
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_walk(WalkParams P) {
+  if (P.ctrl->err) return;  // an earlier kernel of this call found a problem
+  Tile t;
+  if (!tile_of_wave(P.n_tiles, kBlock / 64, t.tile)) return;
+  open_tile(P, t, P.layer_lo == 1);
+  uint32_t malformed = 0;
+  for (uint32_t layer = P.layer_lo; layer <= P.layer_hi; ++layer) {
+    if (layer == 1) walk_roots(P, t, malformed);
+    else run_layer(P, t, layer);
+    // a lane reads back only what this wavefront stored; make those stores land first
+    if (layer < P.layer_hi) __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  }
+  const uint64_t wm = wave_sum64(malformed);
+  if (lane_id() == 0 && wm) atomicAdd(reinterpret_cast<unsigned long long*>(&P.ctrl->n_malformed), (unsigned long long)wm);
+}
+
+// ----------------------------------------------------------- launch wrappers
+static dim3 tile_grid(uint32_t n_tiles, uint32_t waves_per_block) {
+  const uint32_t blocks = (n_tiles + waves_per_block - 1) / waves_per_block;
+  return dim3(((blocks + 7u) / 8u) * 8u);
+}
+
+hipError_t launch_count(const WalkParams& P, hipStream_t st) {
+  if (P.n_tiles == 0) return hipSuccess;
+  const uint32_t lds = P.waves_per_block * P.n_ragged * 64u * sizeof(uint32_t);
+  if (lds > 64u * 1024u) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_count),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_count, tile_grid(P.n_tiles, P.waves_per_block), dim3(P.waves_per_block * 64u), lds, st, P);
+  return hipGetLastError();
+}
+
+hipError_t launch_walk(const WalkParams& P, hipStream_t st) {
+  if (P.n_tiles == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_walk, tile_grid(P.n_tiles, kBlock / 64), dim3(kBlock), 0, st, P);
+  return hipGetLastError();
+}
+
+}  // namespace fbx

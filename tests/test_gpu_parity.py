@@ -23,10 +23,11 @@ def _cat(records):
 
 
 @pytest.mark.parametrize("mode", MODES, ids=["per_layer", "fused"])
-@pytest.mark.parametrize("tile_bytes", [1024, 20480])
-def test_hand_built_records(mode, tile_bytes):
-    raw, off = _cat(FRAMING_RECORDS * 7)
-    check(FRAMING_SPEC, raw, off, dict(mode, tile_bytes=tile_bytes))
+@pytest.mark.parametrize("copies", [1, 7, 29])
+def test_hand_built_records(mode, copies):
+    # 9, 63 and 261 records: less than a tile, one short of a tile, several tiles and a ragged tail
+    raw, off = _cat(FRAMING_RECORDS * copies)
+    check(FRAMING_SPEC, raw, off, mode)
 
 
 @pytest.mark.parametrize("mode", MODES, ids=["per_layer", "fused"])
@@ -38,14 +39,12 @@ def test_configs_small(cfg, n, mode):
     assert res.n_layers == w.n_layers
 
 
-@pytest.mark.parametrize("tile_bytes", [1024, 4096, 49152])
-def test_tile_sizes(tile_bytes):
-    w = W.get(5, 777)
-    raw, off = w.generate()
-    check(w.spec, raw, off, {"tile_bytes": tile_bytes})
-    w = W.get(2, 130)
-    raw, off = w.generate()
-    check(w.spec, raw, off, {"tile_bytes": tile_bytes})
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 777])
+def test_tile_boundaries(n):
+    for cfg in (5, 2):
+        w = W.get(cfg, n)
+        raw, off = w.generate()
+        check(w.spec, raw, off, label=f"{w.name} n={n}")
 
 
 @pytest.mark.parametrize("misalign", [1, 7, 15])
@@ -67,18 +66,18 @@ def test_empty_batch_and_single_record():
     check(FRAMING_SPEC, *_cat([b""]))
 
 
-def test_slow_path_long_records_and_dense_tabs():
+def test_long_records_and_dense_tabs():
     rng = random.Random(5)
     long_field = bytes(rng.choice(b"abcxyz,0123") for _ in range(70000))
     recs = [b"k\t" + long_field + b"\t1.25,7\tquery text here\n",
             b"a\tb\tc\td\n",
-            b"\t" * 5000 + b"\n",            # more tabs than the staged tab list holds
+            b"\t" * 5000 + b"\n",            # far more tabs than fields
             b"m\tx1,x2\t-3.5\tabcdef\n"] * 3
     raw, off = _cat(recs)
-    res, _ = check(FRAMING_SPEC, raw, off, {"tile_bytes": 2048})
-    # dense tabs inside an otherwise small tile
+    res, _ = check(FRAMING_SPEC, raw, off)
+    # dense tabs
     recs = [b"\t\t\t" * 300 + b"\n"] * 40 + [b"a\tb,c\t1\tdddd\n"] * 40
-    check(FRAMING_SPEC, *_cat(recs), options={"tile_bytes": 4096})
+    check(FRAMING_SPEC, *_cat(recs))
 
 
 def test_malformed_numerics_are_counted():

@@ -104,9 +104,9 @@ def test_layer_rule_properties_on_random_dags():
 
 def test_options_and_calls_without_workspace():
     p = B.Plan(FRAMING_SPEC)
-    p.set_option("tile_bytes", 8192)
     p.set_option("fused", 1)
-    for key, val in (("tile_bytes", 10), ("fused", 2), ("nonsense", 1)):
+    p.set_option("profile", 0)
+    for key, val in (("profile", 7), ("fused", 2), ("nonsense", 1)):
         with pytest.raises(B.FbxError) as e:
             p.set_option(key, val)
         assert e.value.status == B.E_ARG
