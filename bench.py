@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the largest)")
     ap.add_argument("--records", type=int, default=None, help="override the record count (debugging)")
     ap.add_argument("--fused", type=int, default=1)
+    ap.add_argument("--lds-pad", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -103,6 +104,8 @@ def main():
     plan = B.Plan(w.spec)
     plan.set_option("profile", 1)
     plan.set_option("fused", args.fused)
+    if args.lds_pad:
+        plan.set_option("lds_pad", args.lds_pad)
     res, ws = B.extract_with_retry(plan, d_raw, d_off)
     log(f"[bench] workspace {ws.numel() / 1e9:.2f} GB, {res.n_values_total} signs, "
         f"{len(res.slot_ids)} slots, malformed {res.n_malformed_numeric}")

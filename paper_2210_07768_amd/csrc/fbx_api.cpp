@@ -37,6 +37,7 @@ struct fbx_plan {
 
   // options
   int fused = 1;
+  uint32_t lds_pad = 0;
   int profile = 0;
 
   // results of the last call
@@ -78,8 +79,8 @@ CallGeometry geometry(const fbx_plan& p, uint64_t n_records) {
   g.n_tiles = static_cast<uint32_t>((n_records + kTile - 1) >> kTileLog2);
   // counting pass: one 256-byte LDS row per ragged operator and wavefront; as many
   // wavefronts per workgroup (at most 4) as fit into 48 KB
-  const uint32_t per_wave = std::max(p.host.n_ragged, 1u) * 256u;
-  g.count_waves = std::min(4u, std::max(1u, 49152u / per_wave));
+  const uint32_t per_wave = 8960u + p.host.n_ragged * 256u;  // byte ring + count rows
+  g.count_waves = std::min(4u, std::max(1u, 65536u / per_wave));
   uint64_t w = p.off_static_end;
   g.off_tile_cnt = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 4);
   g.off_tile_base = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 8);
@@ -159,6 +160,9 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   if (k == "fused") {
     if (value != 0 && value != 1) { plan->error = "fused must be 0 or 1"; return FBX_E_ARG; }
     plan->fused = static_cast<int>(value);
+  } else if (k == "lds_pad") {
+    if (value < 0 || value > 65536) { plan->error = "lds_pad must be in 0..65536"; return FBX_E_ARG; }
+    plan->lds_pad = static_cast<uint32_t>(value);
   } else if (k == "profile") {
     if (value != 0 && value != 1) { plan->error = "profile must be 0 or 1"; return FBX_E_ARG; }
     plan->profile = static_cast<int>(value);
@@ -251,6 +255,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   P.n_nonroot = static_cast<uint32_t>(h.nonroot_ops.size());
   P.n_tiles = g.n_tiles; P.n_fields = h.n_fields; P.count_fields = h.count_fields;
   P.waves_per_block = g.count_waves;
+  P.lds_pad = plan->lds_pad;
   uint64_t* row_total = reinterpret_cast<uint64_t*>(ws + plan->off_row_total);
 
   // profiling events

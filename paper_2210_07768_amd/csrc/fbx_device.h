@@ -32,6 +32,7 @@ struct WalkParams {
   uint32_t n_tiles, n_fields, count_fields;
   uint32_t layer_lo, layer_hi;  // 1-based, inclusive
   uint32_t waves_per_block;     // counting pass only
+  uint32_t lds_pad;             // extra dynamic LDS per workgroup: lowers occupancy (tuning)
 };
 
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st);

@@ -24,6 +24,8 @@
 //    same kernel restricted to one layer.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "fbx_device.h"
 
 namespace fbx {
@@ -66,27 +68,97 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
 // ------------------------------------------------------------ byte windows
 // Per-wavefront view of the raw buffer.  Positions are 32-bit offsets from the
 // first byte of the tile (a tile spans less than 2 GiB; checked beforehand).
+//
+// A lane walks its record front to back a few bytes at a time, and the 64
+// records of a wavefront lie far apart, so fetching every 16-byte window from
+// memory would pull the same 64-byte sector out of HBM once per window.  Each
+// lane therefore keeps the two sectors it is working in inside LDS (a two-entry
+// direct-mapped cache, sector s in slot s & 1): a sector is fetched from memory
+// once, with four adjacent 16-byte loads, and windows are then cut out of LDS.
+// Dword d of a lane's 128 ring bytes sits at ring[d * 64 + lane], so all lanes
+// hit different banks whatever their positions; the first three dwords of slot
+// 0 are mirrored behind slot 1 so that a window never wraps.
+constexpr uint32_t kRingDwords = 35;                 // 2 sectors of 16 dwords + 3 mirrored
+constexpr uint32_t kRingWave = kRingDwords * 64u;    // dwords of LDS per wavefront
+
+extern __shared__ __align__(16) uint32_t smem32[];
+
 struct Ctx {
-  const uint8_t* base4;  // 4-byte aligned address at or just before tile byte 0
-  uint32_t delta;        // tile byte 0 is base4[delta], delta in 0..3
-  uint32_t lo_valid;     // base4[o] lies inside the raw buffer iff lo_valid <= o < hi_valid
+  const uint8_t* base64;  // 64-byte aligned address at or just before tile byte 0   (uniform)
+  uint32_t delta;         // tile byte 0 is base64[delta], delta in 0..63            (uniform)
+  uint32_t lo_valid;      // base64[o] lies inside the raw buffer iff lo_valid <= o < hi_valid
   uint32_t hi_valid;
+  uint32_t ring;          // index in smem32 of dword 0 of this lane's ring          (per lane)
+  uint32_t tag0, tag1;    // sector held in slot 0 / slot 1, 0xffffffff = none       (per lane)
 };
 
 struct Win { uint32_t a, b, c; };  // 12 bytes starting at the requested position
 
-__device__ __forceinline__ Win load_win(const Ctx& c, uint32_t p) {
+// Fetch 64-byte sector s of this lane's stream into its ring slot.
+__device__ __forceinline__ void ring_fill(Ctx& c, uint32_t s) {
+  const uint32_t so = s << 6;
+  uint32_t v[16];
+  if (so >= c.lo_valid && so + 64u <= c.hi_valid) {
+    const uint4* src = reinterpret_cast<const uint4*>(c.base64 + so);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 q = src[i];
+      v[4 * i] = q.x; v[4 * i + 1] = q.y; v[4 * i + 2] = q.z; v[4 * i + 3] = q.w;
+    }
+  } else {
+    // sector straddles an end of the buffer: fetch what exists byte by byte
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = 0;
+    for (uint32_t i = 0; i < 64; ++i) {
+      const uint32_t oi = so + i;
+      if (oi >= c.lo_valid && oi < c.hi_valid) {
+        const uint32_t byte = (uint32_t)c.base64[oi] << (8u * (i & 3u));
+#pragma unroll
+        for (int k = 0; k < 16; ++k) if ((i >> 2) == (uint32_t)k) v[k] |= byte;
+      }
+    }
+  }
+  const uint32_t slot = s & 1u;
+  const uint32_t dst = c.ring + slot * 16u * 64u;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) smem32[dst + i * 64] = v[i];
+  if (slot == 0) {
+    smem32[c.ring + 32 * 64] = v[0];
+    smem32[c.ring + 33 * 64] = v[1];
+    smem32[c.ring + 34 * 64] = v[2];
+    c.tag0 = s;
+  } else {
+    c.tag1 = s;
+  }
+}
+
+__device__ __forceinline__ Win load_win(Ctx& c, uint32_t p) {
+  const uint32_t o = p + c.delta, qa = o & ~3u, sh = (o & 3u) * 8u;
+  const uint32_t s0 = qa >> 6, s1 = (qa + 15u) >> 6;
+  if (((s0 & 1u) ? c.tag1 : c.tag0) != s0) ring_fill(c, s0);
+  if (((s1 & 1u) ? c.tag1 : c.tag0) != s1) ring_fill(c, s1);
+  const uint32_t idx = c.ring + ((qa >> 2) & 31u) * 64u;
+  const uint32_t w0 = smem32[idx], w1 = smem32[idx + 64], w2 = smem32[idx + 128], w3 = smem32[idx + 192];
+  Win r;
+  r.a = __builtin_amdgcn_alignbit(w1, w0, sh);
+  r.b = __builtin_amdgcn_alignbit(w2, w1, sh);
+  r.c = __builtin_amdgcn_alignbit(w3, w2, sh);
+  return r;
+}
+
+// The same window straight from memory, for accesses that do not follow the
+// lane's own record (lanes reading neighbouring bytes of one record coalesce).
+__device__ __forceinline__ Win load_win_direct(const Ctx& c, uint32_t p) {
   const uint32_t o = p + c.delta, qa = o & ~3u, sh = (o & 3u) * 8u;
   uint32_t w0, w1, w2, w3;
   if (qa >= c.lo_valid && qa + 16u <= c.hi_valid) {
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(__builtin_assume_aligned(c.base4 + qa, 4));
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(__builtin_assume_aligned(c.base64 + qa, 4));
     w0 = src[0]; w1 = src[1]; w2 = src[2]; w3 = src[3];
   } else {
-    // window straddles an end of the buffer: fetch what exists byte by byte
     uint32_t w[4] = {0, 0, 0, 0};
     for (uint32_t i = 0; i < 16; ++i) {
       const uint32_t oi = qa + i;
-      if (oi >= c.lo_valid && oi < c.hi_valid) w[i >> 2] |= (uint32_t)c.base4[oi] << (8u * (i & 3u));
+      if (oi >= c.lo_valid && oi < c.hi_valid) w[i >> 2] |= (uint32_t)c.base64[oi] << (8u * (i & 3u));
     }
     w0 = w[0]; w1 = w[1]; w2 = w[2]; w3 = w[3];
   }
@@ -97,7 +169,7 @@ __device__ __forceinline__ Win load_win(const Ctx& c, uint32_t p) {
   return r;
 }
 
-__device__ __forceinline__ uint32_t load_byte(const Ctx& c, uint32_t p) { return c.base4[p + c.delta]; }
+__device__ __forceinline__ uint32_t load_byte(const Ctx& c, uint32_t p) { return c.base64[p + c.delta]; }
 
 template <int J>
 __device__ __forceinline__ uint32_t win_byte(const Win& w) {
@@ -138,7 +210,7 @@ __device__ __forceinline__ uint32_t count_commas(const Win& w, uint32_t m) {
 // End of the field that starts at pos: position of its tab, or the end of the
 // record.  With COMMAS the commas of the field are counted on the way.
 template <bool COMMAS>
-__device__ __forceinline__ uint32_t find_end(const Ctx& c, uint32_t pos, uint32_t end, uint32_t& commas) {
+__device__ __forceinline__ uint32_t find_end(Ctx& c, uint32_t pos, uint32_t end, uint32_t& commas) {
   uint32_t p = pos;
   commas = 0;
   while (p < end) {
@@ -154,7 +226,7 @@ __device__ __forceinline__ uint32_t find_end(const Ctx& c, uint32_t pos, uint32_
 
 // Calls f(byte) for every byte of [s, e), in order.
 template <class F>
-__device__ __forceinline__ void for_each_byte(const Ctx& c, uint32_t s, uint32_t e, F&& f) {
+__device__ __forceinline__ void for_each_byte(Ctx& c, uint32_t s, uint32_t e, F&& f) {
   for (uint32_t p = s; p < e; p += kWin) {
     const uint32_t n = e - p < kWin ? e - p : kWin;
     const Win w = load_win(c, p);
@@ -167,7 +239,7 @@ __device__ __forceinline__ void for_each_byte(const Ctx& c, uint32_t s, uint32_t
 
 // Single-valued hash of the field at pos, fused with the search for its tab.
 // Returns the position of the field's end (its tab, or the end of the record).
-__device__ __forceinline__ uint32_t hash_to_tab(const Ctx& c, uint32_t pos, uint32_t end, uint64_t& h) {
+__device__ __forceinline__ uint32_t hash_to_tab(Ctx& c, uint32_t pos, uint32_t end, uint64_t& h) {
   uint32_t p = pos;
   while (p < end) {
     const uint32_t n = end - p < kWin ? end - p : kWin;
@@ -236,7 +308,7 @@ __device__ __forceinline__ uint64_t bucket_sign(const OpDesc& d, const uint8_t* 
 }
 
 // Number of signs a ragged root operator (not n-gram) produces on [s, e); commas = #',' in the span.
-__device__ __forceinline__ uint32_t ragged_root_count(const Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s,
+__device__ __forceinline__ uint32_t ragged_root_count(Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s,
                                                       uint32_t e, uint32_t commas) {
   if (d.kind != OP_FILTER) return commas + 1;  // multi-valued hash / bucket
   const uint8_t* pre = aux + d.aux_off;
@@ -258,7 +330,7 @@ __device__ __forceinline__ uint32_t ragged_root_count(const Ctx& c, const OpDesc
 }
 
 // Writes the signs of a root operator (not n-gram) on [s, e) to dst[0 .. count).
-__device__ __forceinline__ void root_emit(const Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s, uint32_t e,
+__device__ __forceinline__ void root_emit(Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s, uint32_t e,
                                           uint64_t* dst, uint32_t& malformed) {
   const bool multi = d.flags & F_MULTI;
   if (d.kind == OP_HASH) {
@@ -316,7 +388,7 @@ __device__ __forceinline__ bool tile_of_wave(uint32_t n_tiles, uint32_t waves_pe
   return tile < n_tiles;
 }
 
-__device__ __forceinline__ void open_tile(const WalkParams& P, Tile& t, bool need_raw) {
+__device__ __forceinline__ void open_tile(const WalkParams& P, Tile& t, bool need_raw, uint32_t ring_base) {
   const uint64_t g0 = (uint64_t)t.tile << kTileLog2;
   t.g = g0 + lane_id();
   t.live = t.g < P.n_records;
@@ -326,13 +398,15 @@ __device__ __forceinline__ void open_tile(const WalkParams& P, Tile& t, bool nee
   if (t.live) { a = P.rec_off[t.g]; b = P.rec_off[t.g + 1]; }
   const uint64_t tile_lo = uniform64(a);  // lane 0 is always live
   const uintptr_t t0 = reinterpret_cast<uintptr_t>(P.raw) + tile_lo;
-  const uintptr_t base4 = t0 & ~uintptr_t(3);
+  const uintptr_t base64 = t0 & ~uintptr_t(63);
   const uintptr_t raw0 = reinterpret_cast<uintptr_t>(P.raw);
-  t.ctx.base4 = reinterpret_cast<const uint8_t*>(base4);
-  t.ctx.delta = (uint32_t)(t0 & 3u);
-  t.ctx.lo_valid = raw0 > base4 ? (uint32_t)(raw0 - base4) : 0u;
-  const uint64_t hi = raw0 + P.raw_len - base4;
+  t.ctx.base64 = reinterpret_cast<const uint8_t*>(base64);
+  t.ctx.delta = (uint32_t)(t0 & 63u);
+  t.ctx.lo_valid = raw0 > base64 ? (uint32_t)(raw0 - base64) : 0u;
+  const uint64_t hi = raw0 + P.raw_len - base64;
   t.ctx.hi_valid = hi > 0xffffffffull ? 0xffffffffu : (uint32_t)hi;
+  t.ctx.ring = ring_base + lane_id();
+  t.ctx.tag0 = t.ctx.tag1 = 0xffffffffu;
   if (t.live) {
     t.pos = (uint32_t)(a - tile_lo);
     t.end = (uint32_t)(b - tile_lo);
@@ -376,15 +450,16 @@ __device__ __forceinline__ void input_list(const WalkParams& P, uint32_t op, uin
 
 // ------------------------------------------------------------ counting pass
 // Per tile and ragged operator: how many signs the tile's 64 records produce.
-// Dynamic LDS: one row of 64 u32 per ragged operator and wavefront.
+// Dynamic LDS: the byte rings of the wavefronts, then one row of 64 u32 per ragged operator and wavefront.
 __global__ __launch_bounds__(kBlock) void k_count(WalkParams P) {
-  extern __shared__ __align__(16) uint32_t s_cnt[];
   if (P.ctrl->err) return;  // an earlier kernel of this call found a problem
   Tile t;
   if (!tile_of_wave(P.n_tiles, P.waves_per_block, t.tile)) return;
-  open_tile(P, t, true);
+  const uint32_t wave = threadIdx.x >> 6;
+  open_tile(P, t, true, wave * kRingWave);
   const uint32_t lane = lane_id();
-  uint32_t* cnt = s_cnt + (size_t)(threadIdx.x >> 6) * P.n_ragged * 64u;  // [row][lane], this wavefront's rows
+  // after the rings: one row of 64 counts per ragged operator, [row][lane], per wavefront
+  uint32_t* cnt = smem32 + P.waves_per_block * kRingWave + (size_t)wave * P.n_ragged * 64u;
   for (uint32_t k = 0; k < P.count_fields; ++k) {
     const FieldDesc fd = P.fields[k];
     uint32_t commas, e;
@@ -458,7 +533,7 @@ __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_
           const uint32_t s_r = __shfl(t.pos, r, 64);
           const uint64_t start_r = __shfl(start, r, 64);
           for (uint32_t g = lane; g < ng_r; g += 64) {
-            const Win w = load_win(t.ctx, s_r + g);
+            const Win w = load_win_direct(t.ctx, s_r + g);
             uint64_t h = d.key;
 #define FBX_STEP(J) if ((uint32_t)J < n) h = (h ^ win_byte<J>(w)) * kPrime;
             FBX_STEP(0) FBX_STEP(1) FBX_STEP(2) FBX_STEP(3) FBX_STEP(4) FBX_STEP(5) FBX_STEP(6) FBX_STEP(7)
@@ -517,7 +592,7 @@ __global__ __launch_bounds__(kBlock) void k_walk(WalkParams P) {
   if (P.ctrl->err) return;  // an earlier kernel of this call found a problem
   Tile t;
   if (!tile_of_wave(P.n_tiles, kBlock / 64, t.tile)) return;
-  open_tile(P, t, P.layer_lo == 1);
+  open_tile(P, t, P.layer_lo == 1, (threadIdx.x >> 6) * kRingWave);
   uint32_t malformed = 0;
   for (uint32_t layer = P.layer_lo; layer <= P.layer_hi; ++layer) {
     if (layer == 1) walk_roots(P, t, malformed);
@@ -537,7 +612,7 @@ static dim3 tile_grid(uint32_t n_tiles, uint32_t waves_per_block) {
 
 hipError_t launch_count(const WalkParams& P, hipStream_t st) {
   if (P.n_tiles == 0) return hipSuccess;
-  const uint32_t lds = P.waves_per_block * P.n_ragged * 64u * sizeof(uint32_t);
+  const uint32_t lds = std::max(P.waves_per_block * (kRingWave + P.n_ragged * 64u) * (uint32_t)sizeof(uint32_t), P.lds_pad);
   if (lds > 64u * 1024u) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_count),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -549,7 +624,8 @@ hipError_t launch_count(const WalkParams& P, hipStream_t st) {
 
 hipError_t launch_walk(const WalkParams& P, hipStream_t st) {
   if (P.n_tiles == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_walk, tile_grid(P.n_tiles, kBlock / 64), dim3(kBlock), 0, st, P);
+  hipLaunchKernelGGL(k_walk, tile_grid(P.n_tiles, kBlock / 64), dim3(kBlock),
+                     std::max((uint32_t)((kBlock / 64) * kRingWave * sizeof(uint32_t)), P.lds_pad), st, P);
   return hipGetLastError();
 }
 
