@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--fused", type=int, default=1)
     ap.add_argument("--lds-pad", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run a device-to-device copy of this many MiB (3 times) and exit: the known "
+                         "traffic against which FETCH_SIZE / WRITE_SIZE readings of rocprofv3 are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (records shard trivially, see DESIGN.md); use --gpus 1")
@@ -95,6 +98,14 @@ def main():
     from paper_2210_07768_amd import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel(), "copy_bytes_written": src.numel(), "copies": 3}))
+        return
     B.lib()  # fails loudly when libfbx.so is missing
     w = W.get(args.config, args.records)
     log(f"[bench] workload {w.name}: {w.n_records} records x {w.n_fields} fields, {w.n_ops} ops, {w.n_layers} layers")

@@ -26,7 +26,9 @@ __global__ void k_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t
     const uint64_t hi = rec_off[j];
     if (hi >= a) {
       if (hi - a >= (1ull << 31)) err |= CE_TILE;
-      atomicMax(reinterpret_cast<unsigned long long*>(&ctrl->max_tile_bytes), (unsigned long long)(hi - a));
+      // the maximum only ever grows: skip the atomic unless this tile can raise it
+      if (hi - a > *reinterpret_cast<volatile uint64_t*>(&ctrl->max_tile_bytes))
+        atomicMax(reinterpret_cast<unsigned long long*>(&ctrl->max_tile_bytes), (unsigned long long)(hi - a));
     }
   }
   if (err) atomicOr(&ctrl->err, err);
