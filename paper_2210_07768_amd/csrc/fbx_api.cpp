@@ -33,7 +33,8 @@ struct fbx_plan {
   uint64_t ws_bytes = 0;
   // constant-table placement inside the workspace (byte offsets)
   uint64_t off_ctrl = 0, off_dyn = 0, off_ops = 0, off_layer_ops = 0, off_layer_begin = 0, off_nonroot = 0,
-           off_aux = 0, off_fields = 0, off_field_ops = 0, off_row_total = 0, off_static_end = 0;
+           off_aux = 0, off_fields = 0, off_field_ops = 0, off_prog_ops = 0, off_prog_fields = 0, off_row_total = 0,
+           off_static_end = 0;
 
   // options
   int fused = 1;
@@ -62,6 +63,8 @@ struct fbx_plan {
     off_aux = o; o = align_up(o + host.aux.size());
     off_fields = o; o = align_up(o + host.fields.size() * sizeof(FieldDesc));
     off_field_ops = o; o = align_up(o + host.field_ops.size() * 4);
+    off_prog_ops = o; o = align_up(o + n * sizeof(OpProg));
+    off_prog_fields = o; o = align_up(o + host.fields.size() * sizeof(FieldProg));
     off_row_total = o; o = align_up(o + host.n_ragged * 8ull);
     off_static_end = o;
   }
@@ -249,6 +252,8 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   P.nonroot = reinterpret_cast<const uint32_t*>(ws + plan->off_nonroot);
   P.aux = ws + plan->off_aux;
   P.dyn = dyn; P.ctrl = ctrl;
+  P.prog_ops = reinterpret_cast<OpProg*>(ws + plan->off_prog_ops);
+  P.prog_fields = reinterpret_cast<FieldProg*>(ws + plan->off_prog_fields);
   P.tile_cnt = reinterpret_cast<uint32_t*>(ws + g.off_tile_cnt);
   P.tile_base = reinterpret_cast<uint64_t*>(ws + g.off_tile_base);
   P.n_ops = n_ops; P.n_layers = h.n_layers; P.n_ragged = h.n_ragged;
@@ -301,8 +306,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     tick(2, 1);
   }
   tick(3, 0);
-  FBX_LAUNCH(launch_alloc(P.ops, dyn, n_ops, h.n_layers, row_total, n_records, plan->ws_bytes, ws,
-                          plan->fused ? 0 : 1, ctrl, st), "allocation kernel");
+  FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, plan->fused ? 0 : 1, st), "allocation kernel");
   tick(3, 1);
   if (g.n_tiles) {
     if (plan->fused) {

@@ -25,6 +25,8 @@ struct WalkParams {
   const uint32_t* nonroot;
   const uint8_t* aux;
   OpDyn* dyn;
+  OpProg* prog_ops;        // [n_ops], per call
+  FieldProg* prog_fields;  // [n_fields], per call
   Ctrl* ctrl;
   uint32_t* tile_cnt;   // [n_ragged][n_tiles]
   uint64_t* tile_base;  // [n_ragged][n_tiles]
@@ -42,8 +44,7 @@ hipError_t launch_count(const WalkParams& P, hipStream_t st);
 hipError_t launch_walk(const WalkParams& P, hipStream_t st);
 hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total, uint32_t n_ragged,
                        uint32_t n_tiles, const Ctrl* ctrl, hipStream_t st);
-hipError_t launch_alloc(const OpDesc* ops, OpDyn* dyn, uint32_t n_ops, uint32_t n_layers, const uint64_t* row_total,
-                        uint64_t n_records, uint64_t ws_bytes, uint8_t* ws, int reuse, Ctrl* ctrl, hipStream_t st);
+hipError_t launch_alloc(const WalkParams& P, const uint64_t* row_total, uint64_t ws_bytes, int reuse, hipStream_t st);
 hipError_t launch_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets, uint32_t threads,
                               hipStream_t st);
 hipError_t launch_arena_reset(uint64_t* head, uint64_t value, hipStream_t st);

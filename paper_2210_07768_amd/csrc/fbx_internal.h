@@ -48,6 +48,26 @@ struct FieldDesc {
 };
 static_assert(sizeof(FieldDesc) == 16, "FieldDesc must stay 16 bytes");
 
+// Per-call flattened programs, written by the allocation kernel once the
+// operators' arrays are placed: everything the walk needs about an operator (or
+// about a single-valued hash field) in one aligned record, so that one scalar
+// load per step replaces a chain of dependent table lookups.
+struct OpProg {
+  uint32_t kind, flags, arity, rag_row;
+  uint32_t aux_off, aux_len, a, b;
+  uint64_t key;
+  uint64_t values;   // absolute device address of the values array
+  uint64_t offsets;  // absolute device address of the offsets array (ragged only)
+  uint64_t pad;
+};
+static_assert(sizeof(OpProg) == 64, "OpProg must stay 64 bytes");
+struct FieldProg {
+  uint32_t cls, need, op_begin, op_count;
+  uint64_t key;      // FC_HASH1: FNV state after the seed bytes
+  uint64_t dst;      // FC_HASH1: absolute device address of the values array
+};
+static_assert(sizeof(FieldProg) == 32, "FieldProg must stay 32 bytes");
+
 // Per-call, per-operator placement, written by the allocation kernel.
 struct OpDyn {
   uint64_t values_off;   // byte offset of the values array from the workspace base

@@ -114,9 +114,13 @@ __global__ void k_arena_reset(uint64_t* head, uint64_t value) {
 // of Section 5 ("Reset GPU memory pool"), generalised to outputs that a later
 // layer still reads.  With reuse off (all layers in one launch) nothing is
 // released.  One block of kBlock threads.
-__global__ __launch_bounds__(kBlock) void k_alloc(const OpDesc* ops, OpDyn* dyn, uint32_t n_ops, uint32_t n_layers,
-                                                  const uint64_t* row_total, uint64_t n_records, uint64_t ws_bytes,
-                                                  uint8_t* ws, int reuse, Ctrl* ctrl) {
+__global__ __launch_bounds__(kBlock) void k_alloc(WalkParams P, const uint64_t* row_total, uint64_t ws_bytes, int reuse) {
+  const OpDesc* ops = P.ops;
+  OpDyn* dyn = P.dyn;
+  Ctrl* ctrl = P.ctrl;
+  uint8_t* ws = P.ws;
+  const uint32_t n_ops = P.n_ops, n_layers = P.n_layers;
+  const uint64_t n_records = P.n_records;
   __shared__ uint64_t s_scan[kBlock];
   __shared__ uint64_t s_addr;
   __shared__ unsigned long long s_max;
@@ -178,6 +182,31 @@ __global__ __launch_bounds__(kBlock) void k_alloc(const OpDesc* ops, OpDyn* dyn,
     for (uint32_t i = tid; i < n_ops; i += kBlock)
       if (!ops[i].arity) *reinterpret_cast<uint64_t*>(ws + dyn[i].offsets_off) = 0;
   }
+  // flattened programs for the walk
+  __syncthreads();
+  for (uint32_t i = tid; i < n_ops; i += kBlock) {
+    const OpDesc& d = ops[i];
+    OpProg g;
+    g.kind = d.kind; g.flags = d.flags; g.arity = d.arity; g.rag_row = d.rag_row;
+    g.aux_off = d.aux_off; g.aux_len = d.aux_len; g.a = d.a; g.b = d.b;
+    g.key = d.key;
+    g.values = reinterpret_cast<uint64_t>(ws + dyn[i].values_off);
+    g.offsets = d.arity ? 0 : reinterpret_cast<uint64_t>(ws + dyn[i].offsets_off);
+    g.pad = 0;
+    P.prog_ops[i] = g;
+  }
+  for (uint32_t k = tid; k < P.n_fields; k += kBlock) {
+    const FieldDesc& f = P.fields[k];
+    FieldProg g;
+    g.cls = f.cls; g.need = f.need; g.op_begin = f.op_begin; g.op_count = f.op_count;
+    g.key = 0; g.dst = 0;
+    if (f.cls == FC_HASH1) {
+      const uint32_t op = P.field_ops[f.op_begin];
+      g.key = ops[op].key;
+      g.dst = reinterpret_cast<uint64_t>(ws + dyn[op].values_off);
+    }
+    P.prog_fields[k] = g;
+  }
 }
 
 // ----------------------------------------------------------- launch wrappers
@@ -201,10 +230,8 @@ hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* 
   return hipGetLastError();
 }
 
-hipError_t launch_alloc(const OpDesc* ops, OpDyn* dyn, uint32_t n_ops, uint32_t n_layers, const uint64_t* row_total,
-                        uint64_t n_records, uint64_t ws_bytes, uint8_t* ws, int reuse, Ctrl* ctrl, hipStream_t st) {
-  hipLaunchKernelGGL(k_alloc, dim3(1), dim3(kBlock), 0, st, ops, dyn, n_ops, n_layers, row_total, n_records, ws_bytes,
-                     ws, reuse, ctrl);
+hipError_t launch_alloc(const WalkParams& P, const uint64_t* row_total, uint64_t ws_bytes, int reuse, hipStream_t st) {
+  hipLaunchKernelGGL(k_alloc, dim3(1), dim3(kBlock), 0, st, P, row_total, ws_bytes, reuse);
   return hipGetLastError();
 }
 

@@ -65,6 +65,23 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
   return ((uint64_t)hi << 32) | lo;
 }
 
+// Load of a table record that every lane of the wavefront reads alike and that
+// no kernel writes while this one runs (plan tables, and per-call tables written
+// by earlier kernels of the same stream).  Going through the constant address
+// space lets the compiler use scalar loads, which do not wait on the vector
+// memory counter and land in SGPRs.
+#define FBX_CONST __attribute__((address_space(4)))
+template <class T>
+__device__ __forceinline__ T cload(const T* p) {
+  static_assert(sizeof(T) % 4 == 0, "dword multiples only");
+  constexpr int N = sizeof(T) / 4;
+  const FBX_CONST uint32_t* q = reinterpret_cast<const FBX_CONST uint32_t*>(reinterpret_cast<uintptr_t>(p));
+  union { T t; uint32_t w[N]; } u;
+#pragma unroll
+  for (int i = 0; i < N; ++i) u.w[i] = q[i];
+  return u.t;
+}
+
 // ------------------------------------------------------------ byte windows
 // Per-wavefront view of the raw buffer.  Positions are 32-bit offsets from the
 // first byte of the tile (a tile spans less than 2 GiB; checked beforehand).
@@ -294,7 +311,8 @@ struct NumState {
   }
 };
 
-__device__ __forceinline__ uint64_t bucket_sign(const OpDesc& d, const uint8_t* aux, NumState& ns, uint32_t& malformed) {
+template <class D>
+__device__ __forceinline__ uint64_t bucket_sign(const D& d, const uint8_t* aux, NumState& ns, uint32_t& malformed) {
   bool bad;
   const int64_t v = ns.finish(bad);
   malformed += bad ? 1u : 0u;
@@ -308,7 +326,8 @@ __device__ __forceinline__ uint64_t bucket_sign(const OpDesc& d, const uint8_t* 
 }
 
 // Number of signs a ragged root operator (not n-gram) produces on [s, e); commas = #',' in the span.
-__device__ __forceinline__ uint32_t ragged_root_count(Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s,
+template <class D>
+__device__ __forceinline__ uint32_t ragged_root_count(Ctx& c, const D& d, const uint8_t* aux, uint32_t s,
                                                       uint32_t e, uint32_t commas) {
   if (d.kind != OP_FILTER) return commas + 1;  // multi-valued hash / bucket
   const uint8_t* pre = aux + d.aux_off;
@@ -330,7 +349,8 @@ __device__ __forceinline__ uint32_t ragged_root_count(Ctx& c, const OpDesc& d, c
 }
 
 // Writes the signs of a root operator (not n-gram) on [s, e) to dst[0 .. count).
-__device__ __forceinline__ void root_emit(Ctx& c, const OpDesc& d, const uint8_t* aux, uint32_t s, uint32_t e,
+template <class D>
+__device__ __forceinline__ void root_emit(Ctx& c, const D& d, const uint8_t* aux, uint32_t s, uint32_t e,
                                           uint64_t* dst, uint32_t& malformed) {
   const bool multi = d.flags & F_MULTI;
   if (d.kind == OP_HASH) {
@@ -419,12 +439,11 @@ __device__ __forceinline__ void open_tile(const WalkParams& P, Tile& t, bool nee
 // exclusive prefix: where the lane's signs start.  Also writes the lane's two
 // offsets entries (each lane writes its own end too, so that a lane can later
 // read back both of its entries without relying on a neighbour).
-__device__ __forceinline__ uint64_t place_ragged(const WalkParams& P, const Tile& t, uint32_t op, uint32_t row,
-                                                 uint32_t cnt) {
+__device__ __forceinline__ uint64_t place_ragged(const WalkParams& P, const Tile& t, const OpProg& d, uint32_t cnt) {
   const uint32_t incl = wave_incl_scan(cnt);
-  const uint64_t start = P.tile_base[(uint64_t)row * P.n_tiles + t.tile] + (incl - cnt);
+  const uint64_t start = cload(&P.tile_base[(uint64_t)d.rag_row * P.n_tiles + t.tile]) + (incl - cnt);
   if (t.live) {
-    uint64_t* off = reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].offsets_off);
+    uint64_t* off = reinterpret_cast<uint64_t*>(d.offsets);
     off[t.g] = start;
     off[t.g + 1] = start + cnt;
   }
@@ -432,16 +451,13 @@ __device__ __forceinline__ uint64_t place_ragged(const WalkParams& P, const Tile
 }
 
 // This lane's list of an earlier operator.
-__device__ __forceinline__ void input_list(const WalkParams& P, uint32_t op, uint64_t g, const uint64_t*& ptr,
-                                           uint32_t& n) {
-  const OpDesc& d = P.ops[op];
-  const OpDyn& y = P.dyn[op];
-  const uint64_t* vals = reinterpret_cast<const uint64_t*>(P.ws + y.values_off);
+__device__ __forceinline__ void input_list(const OpProg& d, uint64_t g, const uint64_t*& ptr, uint32_t& n) {
+  const uint64_t* vals = reinterpret_cast<const uint64_t*>(d.values);
   if (d.arity) {
     n = d.arity;
     ptr = vals + g * d.arity;
   } else {
-    const uint64_t* off = reinterpret_cast<const uint64_t*>(P.ws + y.offsets_off);
+    const uint64_t* off = reinterpret_cast<const uint64_t*>(d.offsets);
     const uint64_t o0 = off[g], o1 = off[g + 1];
     n = (uint32_t)(o1 - o0);
     ptr = vals + o0;
@@ -461,12 +477,12 @@ __global__ __launch_bounds__(kBlock) void k_count(WalkParams P) {
   // after the rings: one row of 64 counts per ragged operator, [row][lane], per wavefront
   uint32_t* cnt = smem32 + P.waves_per_block * kRingWave + (size_t)wave * P.n_ragged * 64u;
   for (uint32_t k = 0; k < P.count_fields; ++k) {
-    const FieldDesc fd = P.fields[k];
+    const FieldDesc fd = cload(&P.fields[k]);
     uint32_t commas, e;
     if (fd.need & 1u) e = find_end<true>(t.ctx, t.pos, t.end, commas);
     else e = find_end<false>(t.ctx, t.pos, t.end, commas);
     for (uint32_t q = 0; q < fd.op_count; ++q) {
-      const OpDesc& d = P.ops[P.field_ops[fd.op_begin + q]];
+      const OpDesc d = cload(&P.ops[cload(&P.field_ops[fd.op_begin + q])]);
       if (d.rag_row == kNoRow) continue;
       uint32_t c;
       if (d.kind == OP_NGRAM) {
@@ -482,10 +498,10 @@ __global__ __launch_bounds__(kBlock) void k_count(WalkParams P) {
   // counts of the later layers follow from the inputs' counts, record by record
   bool overflow = false;
   for (uint32_t k = 0; k < P.n_nonroot; ++k) {
-    const OpDesc& d = P.ops[P.nonroot[k]];
+    const OpDesc d = cload(&P.ops[cload(&P.nonroot[k])]);
     if (d.rag_row == kNoRow) continue;
-    const OpDesc& da = P.ops[d.a];
-    const OpDesc& db = P.ops[d.b];
+    const OpDesc da = cload(&P.ops[d.a]);
+    const OpDesc db = cload(&P.ops[d.b]);
     const uint64_t ca = da.arity ? da.arity : cnt[da.rag_row * 64u + lane];
     const uint64_t cb = db.arity ? db.arity : cnt[db.rag_row * 64u + lane];
     const uint64_t c = d.kind == OP_CROSS ? ca * cb : ca + cb;
@@ -504,13 +520,14 @@ __global__ __launch_bounds__(kBlock) void k_count(WalkParams P) {
 // ------------------------------------------------------------- writing pass
 __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_t& malformed) {
   const uint32_t lane = lane_id();
+  FieldProg next = cload(&P.prog_fields[0]);
   for (uint32_t k = 0; k < P.n_fields; ++k) {
-    const FieldDesc fd = P.fields[k];
+    const FieldProg fd = next;
+    if (k + 1 < P.n_fields) next = cload(&P.prog_fields[k + 1]);  // in flight while this field is worked on
     if (fd.cls == FC_HASH1) {
-      const uint32_t op = P.field_ops[fd.op_begin];
-      uint64_t h = P.ops[op].key;
+      uint64_t h = fd.key;
       const uint32_t e = hash_to_tab(t.ctx, t.pos, t.end, h);
-      if (t.live) reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].values_off)[t.g] = h;
+      if (t.live) reinterpret_cast<uint64_t*>(fd.dst)[t.g] = h;
       t.pos = e + 1;
       continue;
     }
@@ -518,15 +535,14 @@ __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_
     if (fd.need & 1u) e = find_end<true>(t.ctx, t.pos, t.end, commas);
     else e = find_end<false>(t.ctx, t.pos, t.end, commas);
     for (uint32_t q = 0; q < fd.op_count; ++q) {
-      const uint32_t op = P.field_ops[fd.op_begin + q];
-      const OpDesc& d = P.ops[op];
-      uint64_t* vals = reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].values_off);
+      const OpProg d = cload(&P.prog_ops[cload(&P.field_ops[fd.op_begin + q])]);
+      uint64_t* vals = reinterpret_cast<uint64_t*>(d.values);
       if (d.kind == OP_NGRAM) {
         // lanes over the grams of one record at a time: balanced and coalesced
         const uint32_t L = e > t.pos ? e - t.pos : 0u;
         const uint32_t n = d.aux_len;
         const uint32_t ng = (t.live && L >= n) ? L - n + 1 : 0u;
-        const uint64_t start = place_ragged(P, t, op, d.rag_row, ng);
+        const uint64_t start = place_ragged(P, t, d, ng);
         for (int r = 0; r < kTile; ++r) {
           const uint32_t ng_r = __shfl(ng, r, 64);
           if (ng_r == 0) continue;
@@ -548,7 +564,7 @@ __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_
         dst = vals + t.g;  // single-valued hash or bucket: arity 1
       } else {
         const uint32_t c = t.live ? ragged_root_count(t.ctx, d, P.aux, t.pos, e, commas) : 0u;
-        dst = vals + place_ragged(P, t, op, d.rag_row, c);
+        dst = vals + place_ragged(P, t, d, c);
       }
       if (t.live) root_emit(t.ctx, d, P.aux, t.pos, e, dst, malformed);  // a filter that keeps nothing writes nothing
     }
@@ -557,23 +573,33 @@ __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_
 }
 
 __device__ __forceinline__ void run_layer(const WalkParams& P, const Tile& t, uint32_t layer) {
-  const uint32_t l0 = P.layer_begin[layer - 1], l1 = P.layer_begin[layer];
+  const uint32_t l0 = cload(&P.layer_begin[layer - 1]), l1 = cload(&P.layer_begin[layer]);
   for (uint32_t q = l0; q < l1; ++q) {
-    const uint32_t op = P.layer_ops[q];
-    const OpDesc& d = P.ops[op];
-    uint64_t* vals = reinterpret_cast<uint64_t*>(P.ws + P.dyn[op].values_off);
+    const OpProg d = cload(&P.prog_ops[cload(&P.layer_ops[q])]);
+    const OpProg da = cload(&P.prog_ops[d.a]);
+    const OpProg db = cload(&P.prog_ops[d.b]);
+    uint64_t* vals = reinterpret_cast<uint64_t*>(d.values);
+    if (d.kind == OP_CROSS && da.arity == 1 && db.arity == 1) {
+      // the common case: two single-valued inputs, one sign out, all three accesses coalesced
+      if (t.live) {
+        const uint64_t a = reinterpret_cast<const uint64_t*>(da.values)[t.g];
+        const uint64_t b = reinterpret_cast<const uint64_t*>(db.values)[t.g];
+        vals[t.g] = mix64(mix64(a + d.key) + b);
+      }
+      continue;
+    }
     const uint64_t* pa = nullptr; const uint64_t* pb = nullptr;
     uint32_t na = 0, nb = 0;
     if (t.live) {
-      input_list(P, d.a, t.g, pa, na);
-      input_list(P, d.b, t.g, pb, nb);
+      input_list(da, t.g, pa, na);
+      input_list(db, t.g, pb, nb);
     }
     uint64_t* dst;
     if (d.arity) {
       dst = vals + t.g * d.arity;
     } else {
       const uint32_t c = d.kind == OP_CROSS ? na * nb : na + nb;
-      dst = vals + place_ragged(P, t, op, d.rag_row, c);
+      dst = vals + place_ragged(P, t, d, c);
     }
     if (!t.live) continue;
     if (d.kind == OP_CROSS) {
