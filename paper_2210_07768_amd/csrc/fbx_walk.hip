@@ -71,6 +71,13 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
 // space lets the compiler use scalar loads, which do not wait on the vector
 // memory counter and land in SGPRs.
 #define FBX_CONST __attribute__((address_space(4)))
+#define FBX_GLOBAL __attribute__((address_space(1)))
+// An address kept as an integer, turned back into a pointer the compiler knows to be global memory.
+template <class T>
+__device__ __forceinline__ FBX_GLOBAL T* gptr(uint64_t addr) { return reinterpret_cast<FBX_GLOBAL T*>(addr); }
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using G64 = FBX_GLOBAL uint64_t*;         // signs and offsets being written
+using CG64 = const FBX_GLOBAL uint64_t*;  // signs and offsets being read
 template <class T>
 __device__ __forceinline__ T cload(const T* p) {
   static_assert(sizeof(T) % 4 == 0, "dword multiples only");
@@ -101,7 +108,7 @@ constexpr uint32_t kRingWave = kRingDwords * 64u;    // dwords of LDS per wavefr
 extern __shared__ __align__(16) uint32_t smem32[];
 
 struct Ctx {
-  const uint8_t* base64;  // 64-byte aligned address at or just before tile byte 0   (uniform)
+  const FBX_GLOBAL uint8_t* base64;  // 64-byte aligned address at or just before tile byte 0   (uniform)
   uint32_t delta;         // tile byte 0 is base64[delta], delta in 0..63            (uniform)
   uint32_t lo_valid;      // base64[o] lies inside the raw buffer iff lo_valid <= o < hi_valid
   uint32_t hi_valid;
@@ -116,10 +123,10 @@ __device__ __forceinline__ void ring_fill(Ctx& c, uint32_t s) {
   const uint32_t so = s << 6;
   uint32_t v[16];
   if (so >= c.lo_valid && so + 64u <= c.hi_valid) {
-    const uint4* src = reinterpret_cast<const uint4*>(c.base64 + so);
+    const FBX_GLOBAL u32x4* src = reinterpret_cast<const FBX_GLOBAL u32x4*>(c.base64 + so);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint4 q = src[i];
+      const u32x4 q = src[i];
       v[4 * i] = q.x; v[4 * i + 1] = q.y; v[4 * i + 2] = q.z; v[4 * i + 3] = q.w;
     }
   } else {
@@ -169,7 +176,7 @@ __device__ __forceinline__ Win load_win_direct(const Ctx& c, uint32_t p) {
   const uint32_t o = p + c.delta, qa = o & ~3u, sh = (o & 3u) * 8u;
   uint32_t w0, w1, w2, w3;
   if (qa >= c.lo_valid && qa + 16u <= c.hi_valid) {
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(__builtin_assume_aligned(c.base64 + qa, 4));
+    const FBX_GLOBAL uint32_t* src = reinterpret_cast<const FBX_GLOBAL uint32_t*>(c.base64 + qa);
     w0 = src[0]; w1 = src[1]; w2 = src[2]; w3 = src[3];
   } else {
     uint32_t w[4] = {0, 0, 0, 0};
@@ -242,38 +249,42 @@ __device__ __forceinline__ uint32_t find_end(Ctx& c, uint32_t pos, uint32_t end,
 }
 
 // Calls f(byte) for every byte of [s, e), in order.
+// Calls f(byte) for the first n (<= 12) bytes of a window, in order.  The steps
+// nest (step J+1 sits inside the test of step J), so a lane that is done leaves
+// the execution mask once and the wavefront skips ahead when every lane is done.
+template <class F>
+__device__ __forceinline__ void for_win_bytes(const Win& w, uint32_t n, F&& f) {
+#define FBX_OPEN(J) if (n > (uint32_t)J) { f(win_byte<J>(w));
+  FBX_OPEN(0) FBX_OPEN(1) FBX_OPEN(2) FBX_OPEN(3) FBX_OPEN(4) FBX_OPEN(5)
+  FBX_OPEN(6) FBX_OPEN(7) FBX_OPEN(8) FBX_OPEN(9) FBX_OPEN(10) FBX_OPEN(11)
+  }}}}}}}}}}}}
+#undef FBX_OPEN
+}
+
+// Calls f(byte) for every byte of [s, e), in order.
 template <class F>
 __device__ __forceinline__ void for_each_byte(Ctx& c, uint32_t s, uint32_t e, F&& f) {
   for (uint32_t p = s; p < e; p += kWin) {
     const uint32_t n = e - p < kWin ? e - p : kWin;
     const Win w = load_win(c, p);
-#define FBX_STEP(J) if ((uint32_t)J >= n) continue; f(win_byte<J>(w));
-    FBX_STEP(0) FBX_STEP(1) FBX_STEP(2) FBX_STEP(3) FBX_STEP(4) FBX_STEP(5)
-    FBX_STEP(6) FBX_STEP(7) FBX_STEP(8) FBX_STEP(9) FBX_STEP(10) FBX_STEP(11)
-#undef FBX_STEP
+    for_win_bytes(w, n, f);
   }
 }
 
-// Single-valued hash of the field at pos, fused with the search for its tab.
+// Single-valued hash of the field at pos, fused with the search for its tab:
+// the bytes of a window up to its first tab are folded into h, window by window.
 // Returns the position of the field's end (its tab, or the end of the record).
 __device__ __forceinline__ uint32_t hash_to_tab(Ctx& c, uint32_t pos, uint32_t end, uint64_t& h) {
   uint32_t p = pos;
   while (p < end) {
     const uint32_t n = end - p < kWin ? end - p : kWin;
     const Win w = load_win(c, p);
-    uint32_t j = 0;
-    bool tab = false;
-#define FBX_STEP(J)                                  \
-    if (!tab && (uint32_t)J < n) {                   \
-      const uint32_t b = win_byte<J>(w);             \
-      if (b == '\t') tab = true;                     \
-      else { h = (h ^ b) * kPrime; j = J + 1; }      \
-    }
-    FBX_STEP(0) FBX_STEP(1) FBX_STEP(2) FBX_STEP(3) FBX_STEP(4) FBX_STEP(5)
-    FBX_STEP(6) FBX_STEP(7) FBX_STEP(8) FBX_STEP(9) FBX_STEP(10) FBX_STEP(11)
-#undef FBX_STEP
-    p += j;
-    if (tab) break;
+    const uint32_t i = first_tab(w, n);
+    uint64_t hh = h;
+    for_win_bytes(w, i, [&](uint32_t b) { hh = (hh ^ b) * kPrime; });
+    h = hh;
+    p += i;
+    if (i < n) break;
   }
   return p;
 }
@@ -351,7 +362,7 @@ __device__ __forceinline__ uint32_t ragged_root_count(Ctx& c, const D& d, const 
 // Writes the signs of a root operator (not n-gram) on [s, e) to dst[0 .. count).
 template <class D>
 __device__ __forceinline__ void root_emit(Ctx& c, const D& d, const uint8_t* aux, uint32_t s, uint32_t e,
-                                          uint64_t* dst, uint32_t& malformed) {
+                                          G64 dst, uint32_t& malformed) {
   const bool multi = d.flags & F_MULTI;
   if (d.kind == OP_HASH) {
     uint64_t h = d.key;
@@ -420,7 +431,7 @@ __device__ __forceinline__ void open_tile(const WalkParams& P, Tile& t, bool nee
   const uintptr_t t0 = reinterpret_cast<uintptr_t>(P.raw) + tile_lo;
   const uintptr_t base64 = t0 & ~uintptr_t(63);
   const uintptr_t raw0 = reinterpret_cast<uintptr_t>(P.raw);
-  t.ctx.base64 = reinterpret_cast<const uint8_t*>(base64);
+  t.ctx.base64 = gptr<const uint8_t>(base64);
   t.ctx.delta = (uint32_t)(t0 & 63u);
   t.ctx.lo_valid = raw0 > base64 ? (uint32_t)(raw0 - base64) : 0u;
   const uint64_t hi = raw0 + P.raw_len - base64;
@@ -443,7 +454,7 @@ __device__ __forceinline__ uint64_t place_ragged(const WalkParams& P, const Tile
   const uint32_t incl = wave_incl_scan(cnt);
   const uint64_t start = cload(&P.tile_base[(uint64_t)d.rag_row * P.n_tiles + t.tile]) + (incl - cnt);
   if (t.live) {
-    uint64_t* off = reinterpret_cast<uint64_t*>(d.offsets);
+    G64 off = gptr<uint64_t>(d.offsets);
     off[t.g] = start;
     off[t.g + 1] = start + cnt;
   }
@@ -451,13 +462,13 @@ __device__ __forceinline__ uint64_t place_ragged(const WalkParams& P, const Tile
 }
 
 // This lane's list of an earlier operator.
-__device__ __forceinline__ void input_list(const OpProg& d, uint64_t g, const uint64_t*& ptr, uint32_t& n) {
-  const uint64_t* vals = reinterpret_cast<const uint64_t*>(d.values);
+__device__ __forceinline__ void input_list(const OpProg& d, uint64_t g, CG64& ptr, uint32_t& n) {
+  CG64 vals = gptr<const uint64_t>(d.values);
   if (d.arity) {
     n = d.arity;
     ptr = vals + g * d.arity;
   } else {
-    const uint64_t* off = reinterpret_cast<const uint64_t*>(d.offsets);
+    CG64 off = gptr<const uint64_t>(d.offsets);
     const uint64_t o0 = off[g], o1 = off[g + 1];
     n = (uint32_t)(o1 - o0);
     ptr = vals + o0;
@@ -527,7 +538,7 @@ __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_
     if (fd.cls == FC_HASH1) {
       uint64_t h = fd.key;
       const uint32_t e = hash_to_tab(t.ctx, t.pos, t.end, h);
-      if (t.live) reinterpret_cast<uint64_t*>(fd.dst)[t.g] = h;
+      if (t.live) gptr<uint64_t>(fd.dst)[t.g] = h;
       t.pos = e + 1;
       continue;
     }
@@ -536,7 +547,7 @@ __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_
     else e = find_end<false>(t.ctx, t.pos, t.end, commas);
     for (uint32_t q = 0; q < fd.op_count; ++q) {
       const OpProg d = cload(&P.prog_ops[cload(&P.field_ops[fd.op_begin + q])]);
-      uint64_t* vals = reinterpret_cast<uint64_t*>(d.values);
+      G64 vals = gptr<uint64_t>(d.values);
       if (d.kind == OP_NGRAM) {
         // lanes over the grams of one record at a time: balanced and coalesced
         const uint32_t L = e > t.pos ? e - t.pos : 0u;
@@ -559,7 +570,7 @@ __device__ __forceinline__ void walk_roots(const WalkParams& P, Tile& t, uint32_
         }
         continue;
       }
-      uint64_t* dst;
+      G64 dst;
       if (d.arity) {
         dst = vals + t.g;  // single-valued hash or bucket: arity 1
       } else {
@@ -578,23 +589,23 @@ __device__ __forceinline__ void run_layer(const WalkParams& P, const Tile& t, ui
     const OpProg d = cload(&P.prog_ops[cload(&P.layer_ops[q])]);
     const OpProg da = cload(&P.prog_ops[d.a]);
     const OpProg db = cload(&P.prog_ops[d.b]);
-    uint64_t* vals = reinterpret_cast<uint64_t*>(d.values);
+    G64 vals = gptr<uint64_t>(d.values);
     if (d.kind == OP_CROSS && da.arity == 1 && db.arity == 1) {
       // the common case: two single-valued inputs, one sign out, all three accesses coalesced
       if (t.live) {
-        const uint64_t a = reinterpret_cast<const uint64_t*>(da.values)[t.g];
-        const uint64_t b = reinterpret_cast<const uint64_t*>(db.values)[t.g];
+        const uint64_t a = gptr<const uint64_t>(da.values)[t.g];
+        const uint64_t b = gptr<const uint64_t>(db.values)[t.g];
         vals[t.g] = mix64(mix64(a + d.key) + b);
       }
       continue;
     }
-    const uint64_t* pa = nullptr; const uint64_t* pb = nullptr;
+    CG64 pa = nullptr; CG64 pb = nullptr;
     uint32_t na = 0, nb = 0;
     if (t.live) {
       input_list(da, t.g, pa, na);
       input_list(db, t.g, pb, nb);
     }
-    uint64_t* dst;
+    G64 dst;
     if (d.arity) {
       dst = vals + t.g * d.arity;
     } else {
