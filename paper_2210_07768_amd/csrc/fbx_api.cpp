@@ -34,12 +34,15 @@ struct fbx_plan {
   // constant-table placement inside the workspace (byte offsets)
   uint64_t off_ctrl = 0, off_dyn = 0, off_ops = 0, off_layer_ops = 0, off_layer_begin = 0, off_nonroot = 0,
            off_aux = 0, off_fields = 0, off_field_ops = 0, off_prog_ops = 0, off_prog_fields = 0, off_row_total = 0,
-           off_static_end = 0;
+           off_tile_lists = 0, off_tile_list_begin = 0, off_static_end = 0;
 
   // options
   int fused = 1;
   uint32_t lds_pad = 0;
   int profile = 0;
+  int tile_log2 = -1;             // -1: chosen per call
+  uint32_t raw_cap = 0;           // 0: chosen per call
+  uint32_t lds_budget = 64u * 1024u;
 
   // results of the last call
   std::vector<uint8_t> readback;  // Ctrl + OpDyn[n_ops]
@@ -66,6 +69,8 @@ struct fbx_plan {
     off_prog_ops = o; o = align_up(o + n * sizeof(OpProg));
     off_prog_fields = o; o = align_up(o + host.fields.size() * sizeof(FieldProg));
     off_row_total = o; o = align_up(o + host.n_ragged * 8ull);
+    off_tile_lists = o; o = align_up(o + host.tile_lists.size() * 4);
+    off_tile_list_begin = o; o = align_up(o + host.tile_list_begin.size() * 4);
     off_static_end = o;
   }
 };
@@ -73,17 +78,66 @@ struct fbx_plan {
 namespace {
 
 struct CallGeometry {
+  bool tile_engine = false;
   uint32_t n_tiles = 0, count_waves = 1;
   uint64_t off_tile_cnt = 0, off_tile_base = 0, arena_base = 0;
+  TileParams tp{};  // LDS layout and tile size (tile engine only)
 };
 
-CallGeometry geometry(const fbx_plan& p, uint64_t n_records) {
+uint32_t round16(uint64_t x) { return static_cast<uint32_t>((x + 15u) & ~uint64_t(15)); }
+
+// LDS layout of the tile kernel for tiles of 2^lt records and raw_cap staged bytes.
+void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParams& tp) {
+  const uint32_t T = 1u << lt;
+  tp.log2T = lt;
+  tp.raw_cap = raw_cap;
+  tp.row_stride = (h.n_fields + 1u) | 1u;  // odd: neighbouring records start in different banks
+  uint32_t o = 0;
+  tp.o_off = o; o = round16(o + 8ull * (T + 1));
+  tp.o_rs = o; o = round16(o + 4ull * T);
+  tp.o_re = o; o = round16(o + 4ull * T);
+  tp.o_rows = o; o = round16(o + 2ull * T * tp.row_stride);
+  tp.o_raw = o; o = round16(o + kRawPad + uint64_t(raw_cap) + 32u);
+  tp.o_stage = o; o = round16(o + 8ull * T * h.n_stage);
+  tp.o_cnt = o; o = round16(o + 4ull * T * h.n_ragged);
+  tp.o_start = o; o = round16(o + 4ull * T * h.n_ragged);
+  tp.o_run = o; o = round16(o + 4ull * h.n_ragged);
+  tp.o_base = o; o = round16(o + 8ull * h.n_ragged);
+  tp.lds_bytes = o;
+}
+
+// Tile size: the largest power of two (at most 64 records) whose LDS sections
+// stay inside the budget when the staged text is sized for 1.25 times the mean
+// record length.  Returns false when even one record per tile does not fit the
+// device (very wide plans): the walk kernels then take the call.
+bool tile_geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records, TileParams& tp) {
+  const PlanHost& h = p.host;
+  if (h.n_fields > 32000) return false;
+  const uint64_t avg = n_records ? (raw_len + n_records - 1) / n_records : 0;
+  const uint32_t dev_max = tile_max_lds();
+  const int lt_hi = p.tile_log2 >= 0 ? p.tile_log2 : 6, lt_lo = p.tile_log2 >= 0 ? p.tile_log2 : 0;
+  for (int lt = lt_hi; lt >= lt_lo; --lt) {
+    const uint64_t want = (uint64_t(1) << lt) * avg * 5 / 4 + 64;
+    const uint32_t cap = p.raw_cap ? p.raw_cap : round16(std::min<uint64_t>(std::max<uint64_t>(want, 1024), 65000));
+    tile_lds_layout(h, static_cast<uint32_t>(lt), cap, tp);
+    const uint32_t limit = (lt == lt_lo) ? dev_max : std::min(p.lds_budget, dev_max);
+    if (tp.lds_bytes <= limit) return true;
+  }
+  return false;
+}
+
+CallGeometry geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records) {
   CallGeometry g;
-  g.n_tiles = static_cast<uint32_t>((n_records + kTile - 1) >> kTileLog2);
-  // counting pass: one 256-byte LDS row per ragged operator and wavefront; as many
-  // wavefronts per workgroup (at most 4) as fit into 48 KB
-  const uint32_t per_wave = 8960u + p.host.n_ragged * 256u;  // byte ring + count rows
-  g.count_waves = std::min(4u, std::max(1u, 65536u / per_wave));
+  g.tile_engine = p.fused && tile_geometry(p, raw_len, n_records, g.tp);
+  if (g.tile_engine) {
+    g.n_tiles = static_cast<uint32_t>((n_records + (1ull << g.tp.log2T) - 1) >> g.tp.log2T);
+  } else {
+    g.n_tiles = static_cast<uint32_t>((n_records + kTile - 1) >> kTileLog2);
+    // counting pass: one 256-byte LDS row per ragged operator and wavefront; as many
+    // wavefronts per workgroup (at most 4) as fit into 48 KB
+    const uint32_t per_wave = 8960u + p.host.n_ragged * 256u;  // byte ring + count rows
+    g.count_waves = std::min(4u, std::max(1u, 65536u / per_wave));
+  }
   uint64_t w = p.off_static_end;
   g.off_tile_cnt = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 4);
   g.off_tile_base = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 8);
@@ -166,6 +220,15 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "lds_pad") {
     if (value < 0 || value > 65536) { plan->error = "lds_pad must be in 0..65536"; return FBX_E_ARG; }
     plan->lds_pad = static_cast<uint32_t>(value);
+  } else if (k == "tile_log2") {
+    if (value < -1 || value > 6) { plan->error = "tile_log2 must be in -1..6"; return FBX_E_ARG; }
+    plan->tile_log2 = static_cast<int>(value);
+  } else if (k == "raw_cap") {
+    if (value < 0 || value > 65000 || (value && value < 64)) { plan->error = "raw_cap must be 0 or in 64..65000"; return FBX_E_ARG; }
+    plan->raw_cap = static_cast<uint32_t>(value) & ~15u;
+  } else if (k == "lds_budget") {
+    if (value < 4096 || value > 160 * 1024) { plan->error = "lds_budget must be in 4096..163840"; return FBX_E_ARG; }
+    plan->lds_budget = static_cast<uint32_t>(value);
   } else if (k == "profile") {
     if (value != 0 && value != 1) { plan->error = "profile must be 0 or 1"; return FBX_E_ARG; }
     plan->profile = static_cast<int>(value);
@@ -178,7 +241,7 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
 
 fbx_status fbx_plan_workspace_hint(const fbx_plan* plan, uint64_t raw_len, uint64_t n_records, uint64_t* bytes) {
   if (!plan || !bytes) return FBX_E_ARG;
-  const CallGeometry g = geometry(*plan, n_records);
+  const CallGeometry g = geometry(*plan, raw_len, n_records);
   // fixed-arity operators are exact; a ragged root operator cannot emit more
   // signs than its field has bytes + 1, for which raw_len / #fields + records
   // is a fair guess; a ragged cross or concat is guessed at four times that.
@@ -213,6 +276,8 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
   if (!h.aux.empty()) std::memcpy(img.data() + plan->off_aux, h.aux.data(), h.aux.size());
   if (!h.fields.empty()) std::memcpy(img.data() + plan->off_fields, h.fields.data(), h.fields.size() * sizeof(FieldDesc));
   if (!h.field_ops.empty()) std::memcpy(img.data() + plan->off_field_ops, h.field_ops.data(), h.field_ops.size() * 4);
+  if (!h.tile_lists.empty()) std::memcpy(img.data() + plan->off_tile_lists, h.tile_lists.data(), h.tile_lists.size() * 4);
+  std::memcpy(img.data() + plan->off_tile_list_begin, h.tile_list_begin.data(), h.tile_list_begin.size() * 4);
   hipError_t e = hipMemcpy(d_workspace, img.data(), img.size(), hipMemcpyHostToDevice);
   if (e != hipSuccess) return hip_fail(plan, e, "copying plan tables");
   plan->ws = static_cast<uint8_t*>(d_workspace);
@@ -231,7 +296,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const PlanHost& h = plan->host;
   const uint32_t n_ops = static_cast<uint32_t>(h.ops.size());
-  const CallGeometry g = geometry(*plan, n_records);
+  const CallGeometry g = geometry(*plan, raw_len, n_records);
   if (g.arena_base > plan->ws_bytes) {
     out->arena_high_water = g.arena_base;
     plan->error = "workspace too small for the per-tile tables; need more than " + std::to_string(g.arena_base) + " bytes";
@@ -291,37 +356,72 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   } while (0)
 
   FBX_LAUNCH(launch_reset(ctrl, g.arena_base, st), "reset");
-  tick(0, 0);
-  FBX_LAUNCH(launch_validate(d_rec_off, n_records, raw_len, kTileLog2, ctrl, st), "validate");
-  tick(0, 1);
-  if (h.n_ragged) {
-    if (g.n_tiles) {
-      tick(1, 0);
-      P.layer_lo = 1; P.layer_hi = h.n_layers;
-      FBX_LAUNCH(launch_count(P, st), "count kernel");
-      tick(1, 1);
+  if (g.tile_engine) {
+    // one workgroup per tile takes its records through every layer; offsets are checked tile by tile
+    TileParams Q = g.tp;
+    Q.raw = d_raw; Q.raw_len = raw_len; Q.rec_off = d_rec_off; Q.n_records = n_records;
+    Q.prog = P.prog_ops;
+    Q.lists = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_lists);
+    Q.list_begin = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_list_begin);
+    Q.nonroot = P.nonroot; Q.aux = P.aux; Q.ctrl = ctrl;
+    Q.tile_cnt = P.tile_cnt; Q.tile_base = P.tile_base;
+    Q.n_ops = n_ops; Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged; Q.n_nonroot = P.n_nonroot;
+    Q.n_tiles = g.n_tiles; Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
+    Q.lds_bytes = std::max(Q.lds_bytes, plan->lds_pad);
+    if (h.n_ragged) {
+      // the counting launch also needs the per-call programs: sizes are unknown, addresses unused
+      FBX_LAUNCH(launch_programs(P, st), "program kernel");
+      if (g.n_tiles) {
+        tick(1, 0);
+        FBX_LAUNCH(launch_tile(Q, 0, st), "tile kernel (counting)");
+        tick(1, 1);
+      }
+      tick(2, 0);
+      FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
+      tick(2, 1);
     }
-    tick(2, 0);
-    FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
-    tick(2, 1);
-  }
-  tick(3, 0);
-  FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, plan->fused ? 0 : 1, st), "allocation kernel");
-  tick(3, 1);
-  if (g.n_tiles) {
-    if (plan->fused) {
-      P.layer_lo = 1; P.layer_hi = h.n_layers;
+    tick(3, 0);
+    FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, 0, st), "allocation kernel");
+    tick(3, 1);
+    if (g.n_tiles) {
       tick(4, 0);
-      FBX_LAUNCH(launch_walk(P, st), "walk kernel");
+      FBX_LAUNCH(launch_tile(Q, 1, st), "tile kernel");
       tick(4, 1);
       plan->tile_launch_layer.push_back(1);
-    } else {
-      for (uint32_t l = 1; l <= h.n_layers; ++l) {
-        P.layer_lo = P.layer_hi = l;
-        tick(3 + l, 0);
+    }
+  } else {
+    tick(0, 0);
+    FBX_LAUNCH(launch_validate(d_rec_off, n_records, raw_len, kTileLog2, ctrl, st), "validate");
+    tick(0, 1);
+    if (h.n_ragged) {
+      if (g.n_tiles) {
+        tick(1, 0);
+        P.layer_lo = 1; P.layer_hi = h.n_layers;
+        FBX_LAUNCH(launch_count(P, st), "count kernel");
+        tick(1, 1);
+      }
+      tick(2, 0);
+      FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
+      tick(2, 1);
+    }
+    tick(3, 0);
+    FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, plan->fused ? 0 : 1, st), "allocation kernel");
+    tick(3, 1);
+    if (g.n_tiles) {
+      if (plan->fused) {
+        P.layer_lo = 1; P.layer_hi = h.n_layers;
+        tick(4, 0);
         FBX_LAUNCH(launch_walk(P, st), "walk kernel");
-        tick(3 + l, 1);
-        plan->tile_launch_layer.push_back(l);
+        tick(4, 1);
+        plan->tile_launch_layer.push_back(1);
+      } else {
+        for (uint32_t l = 1; l <= h.n_layers; ++l) {
+          P.layer_lo = P.layer_hi = l;
+          tick(3 + l, 0);
+          FBX_LAUNCH(launch_walk(P, st), "walk kernel");
+          tick(3 + l, 1);
+          plan->tile_launch_layer.push_back(l);
+        }
       }
     }
   }

@@ -37,6 +37,36 @@ struct WalkParams {
   uint32_t lds_pad;             // extra dynamic LDS per workgroup: lowers occupancy (tuning)
 };
 
+// ---- tile kernel: one workgroup takes a tile of 2^log2T records through every layer
+constexpr int kTileThreads = 256;
+constexpr uint32_t kRawPad = 16;  // first byte position of the staged raw text inside its LDS section
+
+struct TileParams {
+  const uint8_t* raw;
+  uint64_t raw_len;
+  const uint64_t* rec_off;
+  uint64_t n_records;
+  const OpProg* prog;          // [n_ops], per call (absolute addresses)
+  const uint32_t* lists;       // work lists (operator indices)
+  const uint32_t* list_begin;  // TL_LAYER + 2 * (n_layers - 1) + 1 entries
+  const uint32_t* nonroot;     // operators of layers >= 2, spec order
+  const uint8_t* aux;
+  Ctrl* ctrl;
+  uint32_t* tile_cnt;          // [n_ragged][n_tiles], written by the counting launch
+  const uint64_t* tile_base;   // [n_ragged][n_tiles], read by the writing launch
+  uint32_t n_ops, n_layers, n_ragged, n_nonroot;
+  uint32_t n_tiles, n_fields, n_stage;
+  uint32_t log2T;       // records per tile = 1 << log2T (at most 64)
+  uint32_t raw_cap;     // bytes of raw text one pass of a workgroup can stage
+  uint32_t row_stride;  // u16 entries per record in the field table (n_fields + 1, padded)
+  // byte offsets of the LDS sections
+  uint32_t o_off, o_rs, o_re, o_rows, o_raw, o_stage, o_cnt, o_start, o_run, o_base;
+  uint32_t lds_bytes;
+};
+
+hipError_t launch_tile(const TileParams& P, int write, hipStream_t st);
+uint32_t tile_max_lds();  // dynamic LDS a workgroup of the tile kernel may ask for on this device
+
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st);
 hipError_t launch_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t raw_len, uint32_t log2T, Ctrl* ctrl,
                            hipStream_t st);
@@ -45,6 +75,7 @@ hipError_t launch_walk(const WalkParams& P, hipStream_t st);
 hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total, uint32_t n_ragged,
                        uint32_t n_tiles, const Ctrl* ctrl, hipStream_t st);
 hipError_t launch_alloc(const WalkParams& P, const uint64_t* row_total, uint64_t ws_bytes, int reuse, hipStream_t st);
+hipError_t launch_programs(const WalkParams& P, hipStream_t st);
 hipError_t launch_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets, uint32_t threads,
                               hipStream_t st);
 hipError_t launch_arena_reset(uint64_t* head, uint64_t value, hipStream_t st);

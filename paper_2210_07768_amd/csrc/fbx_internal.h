@@ -30,7 +30,9 @@ struct OpDesc {
   uint32_t layer;    // 1-based
   uint32_t birth;    // == layer
   uint32_t death;    // last layer that reads this operator's output (>= layer)
-  uint32_t pad[2];
+  uint32_t stage;    // row of the on-chip sign table (single-sign operators that feed a later
+                     // operator), 0xffffffff if none
+  uint32_t pad;
 };
 static_assert(sizeof(OpDesc) == 64, "OpDesc must stay 64 bytes");
 
@@ -58,7 +60,8 @@ struct OpProg {
   uint64_t key;
   uint64_t values;   // absolute device address of the values array
   uint64_t offsets;  // absolute device address of the offsets array (ragged only)
-  uint64_t pad;
+  uint32_t field;    // root operators: positional field index
+  uint32_t stage;    // row of the on-chip sign table, 0xffffffff if none
 };
 static_assert(sizeof(OpProg) == 64, "OpProg must stay 64 bytes");
 struct FieldProg {
@@ -114,7 +117,17 @@ struct PlanHost {
   std::vector<FieldDesc> fields;       // n_fields entries
   std::vector<uint32_t> field_ops;     // root operator indices grouped by field, spec order inside a field
   uint32_t count_fields = 0;           // the counting pass may stop after this many fields
+  // Work lists of the tile kernel: operator indices grouped by how a tile of
+  // records runs them.  List ids: see TileList.
+  std::vector<uint32_t> tile_lists;
+  std::vector<uint32_t> tile_list_begin;  // n_tile_lists + 1 entries into tile_lists
+  uint32_t n_stage = 0;                   // rows of the on-chip sign table
 };
+
+// Work lists of the tile kernel.  Layer 1 has four lists; every later layer l
+// has two, TL_LAYER + 2 * (l - 2) (crosses of two single signs) and the next
+// one (every other cross or concat).
+enum TileList : uint32_t { TL_HASH1 = 0, TL_BUCKET1 = 1, TL_RAGROOT = 2, TL_NGRAM = 3, TL_LAYER = 4 };
 
 // Returns FBX_OK or FBX_E_SPEC (message in err).
 fbx_status parse_plan(const char* spec, size_t len, PlanHost& out, std::string& err);

@@ -318,6 +318,40 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
     err = "more than 512 ragged operators";
     return FBX_E_SPEC;
   }
+  // Tile kernel: single-sign operators that feed a later operator keep their
+  // signs on chip (one table row each); work lists group operators by the code
+  // that runs them, layer by layer.
+  for (HostOp& op : plan.ops) op.d.stage = 0xffffffffu;
+  for (const HostOp& op : plan.ops) {
+    if (op.d.kind != OP_CROSS && op.d.kind != OP_CONCAT) continue;
+    for (uint32_t in : {op.d.a, op.d.b}) {
+      OpDesc& di = plan.ops[in].d;
+      if (di.arity == 1 && di.stage == 0xffffffffu) di.stage = plan.n_stage++;
+    }
+  }
+  const uint32_t n_lists = TL_LAYER + (plan.n_layers > 1 ? 2 * (plan.n_layers - 1) : 0);
+  std::vector<std::vector<uint32_t>> lists(n_lists);
+  for (uint32_t i = 0; i < plan.ops.size(); ++i) {
+    const OpDesc& d = plan.ops[i].d;
+    if (d.layer == 1) {
+      if (d.kind == OP_NGRAM) lists[TL_NGRAM].push_back(i);
+      else if (d.arity == 0) lists[TL_RAGROOT].push_back(i);
+      else if (d.kind == OP_HASH) lists[TL_HASH1].push_back(i);
+      else lists[TL_BUCKET1].push_back(i);
+    } else {
+      const bool single = d.kind == OP_CROSS && plan.ops[d.a].d.arity == 1 && plan.ops[d.b].d.arity == 1;
+      lists[TL_LAYER + 2 * (d.layer - 2) + (single ? 0 : 1)].push_back(i);
+    }
+  }
+  // neighbouring lanes run neighbouring list entries: keep like with like
+  std::stable_sort(lists[TL_RAGROOT].begin(), lists[TL_RAGROOT].end(), [&](uint32_t x, uint32_t y) {
+    return plan.ops[x].d.kind < plan.ops[y].d.kind;
+  });
+  for (const std::vector<uint32_t>& l : lists) {
+    plan.tile_list_begin.push_back(static_cast<uint32_t>(plan.tile_lists.size()));
+    plan.tile_lists.insert(plan.tile_lists.end(), l.begin(), l.end());
+  }
+  plan.tile_list_begin.push_back(static_cast<uint32_t>(plan.tile_lists.size()));
   return FBX_OK;
 }
 

@@ -107,6 +107,45 @@ __global__ void k_arena_reset(uint64_t* head, uint64_t value) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *head = value;
 }
 
+// Flattened per-call programs: everything a kernel needs about an operator (or
+// about a single-valued hash field) in one aligned record.  One block of kBlock threads.
+__device__ void write_programs(const WalkParams& P, bool placed) {
+  const OpDesc* ops = P.ops;
+  const OpDyn* dyn = P.dyn;
+  uint8_t* ws = P.ws;
+  const uint32_t tid = threadIdx.x;
+  __syncthreads();
+  for (uint32_t i = tid; i < P.n_ops; i += kBlock) {
+    const OpDesc& d = ops[i];
+    OpProg g;
+    g.kind = d.kind; g.flags = d.flags; g.arity = d.arity; g.rag_row = d.rag_row;
+    g.aux_off = d.aux_off; g.aux_len = d.aux_len; g.a = d.a; g.b = d.b;
+    g.key = d.key;
+    g.values = placed ? reinterpret_cast<uint64_t>(ws + dyn[i].values_off) : 0;
+    g.offsets = (placed && !d.arity) ? reinterpret_cast<uint64_t>(ws + dyn[i].offsets_off) : 0;
+    g.field = d.field;
+    g.stage = d.stage;
+    if (d.kind == OP_CROSS && ops[d.a].arity == 1 && ops[d.b].arity == 1) {
+      // a cross of two single signs finds both in the on-chip table: rows instead of aux data
+      g.aux_off = ops[d.a].stage;
+      g.aux_len = ops[d.b].stage;
+    }
+    P.prog_ops[i] = g;
+  }
+  for (uint32_t k = tid; k < P.n_fields; k += kBlock) {
+    const FieldDesc& f = P.fields[k];
+    FieldProg g;
+    g.cls = f.cls; g.need = f.need; g.op_begin = f.op_begin; g.op_count = f.op_count;
+    g.key = 0; g.dst = 0;
+    if (f.cls == FC_HASH1) {
+      const uint32_t op = P.field_ops[f.op_begin];
+      g.key = ops[op].key;
+      g.dst = placed ? reinterpret_cast<uint64_t>(ws + dyn[op].values_off) : 0;
+    }
+    P.prog_fields[k] = g;
+  }
+}
+
 // Carve the operators' value / offset arrays out of the pool, once sizes are
 // known.  Emitted operators first (they live until the next call); then layer
 // by layer the intermediates born in that layer, and after each layer the head
@@ -182,32 +221,12 @@ __global__ __launch_bounds__(kBlock) void k_alloc(WalkParams P, const uint64_t* 
     for (uint32_t i = tid; i < n_ops; i += kBlock)
       if (!ops[i].arity) *reinterpret_cast<uint64_t*>(ws + dyn[i].offsets_off) = 0;
   }
-  // flattened programs for the walk
-  __syncthreads();
-  for (uint32_t i = tid; i < n_ops; i += kBlock) {
-    const OpDesc& d = ops[i];
-    OpProg g;
-    g.kind = d.kind; g.flags = d.flags; g.arity = d.arity; g.rag_row = d.rag_row;
-    g.aux_off = d.aux_off; g.aux_len = d.aux_len; g.a = d.a; g.b = d.b;
-    g.key = d.key;
-    g.values = reinterpret_cast<uint64_t>(ws + dyn[i].values_off);
-    g.offsets = d.arity ? 0 : reinterpret_cast<uint64_t>(ws + dyn[i].offsets_off);
-    g.pad = 0;
-    P.prog_ops[i] = g;
-  }
-  for (uint32_t k = tid; k < P.n_fields; k += kBlock) {
-    const FieldDesc& f = P.fields[k];
-    FieldProg g;
-    g.cls = f.cls; g.need = f.need; g.op_begin = f.op_begin; g.op_count = f.op_count;
-    g.key = 0; g.dst = 0;
-    if (f.cls == FC_HASH1) {
-      const uint32_t op = P.field_ops[f.op_begin];
-      g.key = ops[op].key;
-      g.dst = reinterpret_cast<uint64_t>(ws + dyn[op].values_off);
-    }
-    P.prog_fields[k] = g;
-  }
+  write_programs(P, true);
 }
+
+// The per-call programs alone, without placement (array addresses are left zero):
+// all the counting launch of the tile kernel needs.
+__global__ __launch_bounds__(kBlock) void k_programs(WalkParams P) { write_programs(P, false); }
 
 // ----------------------------------------------------------- launch wrappers
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st) {
@@ -232,6 +251,11 @@ hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* 
 
 hipError_t launch_alloc(const WalkParams& P, const uint64_t* row_total, uint64_t ws_bytes, int reuse, hipStream_t st) {
   hipLaunchKernelGGL(k_alloc, dim3(1), dim3(kBlock), 0, st, P, row_total, ws_bytes, reuse);
+  return hipGetLastError();
+}
+
+hipError_t launch_programs(const WalkParams& P, hipStream_t st) {
+  hipLaunchKernelGGL(k_programs, dim3(1), dim3(kBlock), 0, st, P);
   return hipGetLastError();
 }
 

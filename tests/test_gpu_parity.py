@@ -14,6 +14,11 @@ from gpu_harness import assert_same, check, run_gpu, to_device
 pytestmark = pytest.mark.gpu
 
 MODES = [{"fused": 0}, {"fused": 1}]
+# the tile kernel at forced tile sizes and with a small staging section, so that tiles take
+# several passes and some records are read in place
+TILE_MODES = [{"tile_log2": 6}, {"tile_log2": 4}, {"tile_log2": 2, "raw_cap": 2048}, {"tile_log2": 0},
+              {"tile_log2": 5, "raw_cap": 512}, {"tile_log2": 3, "raw_cap": 64}]
+TILE_IDS = ["T64", "T16", "T4_cap2048", "T1", "T32_cap512", "T8_cap64"]
 
 
 def _cat(records):
@@ -37,6 +42,16 @@ def test_configs_small(cfg, n, mode):
     raw, off = w.generate()
     res, want = check(w.spec, raw, off, mode, label=w.name)
     assert res.n_layers == w.n_layers
+
+
+@pytest.mark.parametrize("mode", TILE_MODES, ids=TILE_IDS)
+def test_tile_sizes_passes_and_in_place_records(mode):
+    raw, off = _cat(FRAMING_RECORDS * 29)
+    check(FRAMING_SPEC, raw, off, mode, label="framing")
+    for cfg, n in ((5, 300), (2, 90), (3, 500), (4, 260)):
+        w = W.get(cfg, n)
+        raw, off = w.generate()
+        check(w.spec, raw, off, mode, label=f"{w.name} {mode}")
 
 
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 777])
