@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--records", type=int, default=None, help="override the record count (debugging)")
     ap.add_argument("--fused", type=int, default=1)
     ap.add_argument("--lds-pad", type=int, default=0)
+    ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
+                    help="extra plan option (tuning), e.g. --opt tile_log2=4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a device-to-device copy of this many MiB (3 times) and exit: the known "
@@ -117,6 +119,9 @@ def main():
     plan.set_option("fused", args.fused)
     if args.lds_pad:
         plan.set_option("lds_pad", args.lds_pad)
+    for kv in args.opt:
+        k, v = kv.split("=")
+        plan.set_option(k, int(v))
     res, ws = B.extract_with_retry(plan, d_raw, d_off)
     log(f"[bench] workspace {ws.numel() / 1e9:.2f} GB, {res.n_values_total} signs, "
         f"{len(res.slot_ids)} slots, malformed {res.n_malformed_numeric}")

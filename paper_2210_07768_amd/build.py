@@ -26,6 +26,7 @@ def command() -> list:
         # keep the compiler from forming packed-FP32 instructions anywhere
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-x", "hip",
+    ] + (["-DFBX_TILE_PROF"] if os.environ.get("FBX_TILE_PROF") else []) + [
         "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
         "-o", LIB,
     ] + [os.path.join(CSRC, s) for s in SOURCES]

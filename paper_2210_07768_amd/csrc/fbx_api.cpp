@@ -1,6 +1,7 @@
 // C ABI of libfbx: plan lifetime, workspace layout, and the launch sequence of
 // one extraction call.  See include/fbx.h for the contract of every entry point.
 #include <algorithm>
+#include <cstdio>
 #include <cstring>
 #include <memory>
 #include <string>
@@ -34,7 +35,7 @@ struct fbx_plan {
   // constant-table placement inside the workspace (byte offsets)
   uint64_t off_ctrl = 0, off_dyn = 0, off_ops = 0, off_layer_ops = 0, off_layer_begin = 0, off_nonroot = 0,
            off_aux = 0, off_fields = 0, off_field_ops = 0, off_prog_ops = 0, off_prog_fields = 0, off_row_total = 0,
-           off_tile_lists = 0, off_tile_list_begin = 0, off_static_end = 0;
+           off_tile_lists = 0, off_tile_list_begin = 0, off_rnr = 0, off_prof = 0, off_static_end = 0;
 
   // options
   int fused = 1;
@@ -71,6 +72,8 @@ struct fbx_plan {
     off_row_total = o; o = align_up(o + host.n_ragged * 8ull);
     off_tile_lists = o; o = align_up(o + host.tile_lists.size() * 4);
     off_tile_list_begin = o; o = align_up(o + host.tile_list_begin.size() * 4);
+    off_rnr = o; o = align_up(o + host.ragged_nonroot.size() * 4);
+    off_prof = o; o = align_up(o + 32 * 8);
     off_static_end = o;
   }
 };
@@ -103,6 +106,11 @@ void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParam
   tp.o_start = o; o = round16(o + 4ull * T * h.n_ragged);
   tp.o_run = o; o = round16(o + 4ull * h.n_ragged);
   tp.o_base = o; o = round16(o + 8ull * h.n_ragged);
+  tp.o_prog = o; o = round16(o + sizeof(OpProg) * h.ops.size());
+  tp.o_lists = o; o = round16(o + 4ull * h.tile_lists.size());
+  tp.o_lbeg = o; o = round16(o + 4ull * h.tile_list_begin.size());
+  tp.o_rnr = o; o = round16(o + 4ull * h.ragged_nonroot.size());
+  tp.o_aux = o; o = round16(o + h.aux.size());
   tp.lds_bytes = o;
 }
 
@@ -112,7 +120,7 @@ void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParam
 // device (very wide plans): the walk kernels then take the call.
 bool tile_geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records, TileParams& tp) {
   const PlanHost& h = p.host;
-  if (h.n_fields > 32000) return false;
+  if (h.n_fields > 32000 || h.ops.size() > 2048 || h.aux.size() > 65536) return false;
   const uint64_t avg = n_records ? (raw_len + n_records - 1) / n_records : 0;
   const uint32_t dev_max = tile_max_lds();
   const int lt_hi = p.tile_log2 >= 0 ? p.tile_log2 : 6, lt_lo = p.tile_log2 >= 0 ? p.tile_log2 : 0;
@@ -278,6 +286,8 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
   if (!h.field_ops.empty()) std::memcpy(img.data() + plan->off_field_ops, h.field_ops.data(), h.field_ops.size() * 4);
   if (!h.tile_lists.empty()) std::memcpy(img.data() + plan->off_tile_lists, h.tile_lists.data(), h.tile_lists.size() * 4);
   std::memcpy(img.data() + plan->off_tile_list_begin, h.tile_list_begin.data(), h.tile_list_begin.size() * 4);
+  if (!h.ragged_nonroot.empty())
+    std::memcpy(img.data() + plan->off_rnr, h.ragged_nonroot.data(), h.ragged_nonroot.size() * 4);
   hipError_t e = hipMemcpy(d_workspace, img.data(), img.size(), hipMemcpyHostToDevice);
   if (e != hipSuccess) return hip_fail(plan, e, "copying plan tables");
   plan->ws = static_cast<uint8_t*>(d_workspace);
@@ -363,11 +373,23 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     Q.prog = P.prog_ops;
     Q.lists = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_lists);
     Q.list_begin = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_list_begin);
-    Q.nonroot = P.nonroot; Q.aux = P.aux; Q.ctrl = ctrl;
+    Q.rnr = reinterpret_cast<const uint32_t*>(ws + plan->off_rnr);
+    Q.aux = P.aux; Q.ctrl = ctrl;
     Q.tile_cnt = P.tile_cnt; Q.tile_base = P.tile_base;
-    Q.n_ops = n_ops; Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged; Q.n_nonroot = P.n_nonroot;
+    Q.n_ops = n_ops; Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged;
+    Q.n_rnr = static_cast<uint32_t>(h.ragged_nonroot.size());
+    Q.n_lists = static_cast<uint32_t>(h.tile_list_begin.size()) - 1u;
+    Q.aux_bytes = static_cast<uint32_t>(h.aux.size());
     Q.n_tiles = g.n_tiles; Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
     Q.lds_bytes = std::max(Q.lds_bytes, plan->lds_pad);
+    // persistent workgroups: as many as the LDS (and 2048 lanes per compute unit) let run at once
+    const uint32_t per_cu = std::max(1u, std::min(2048u / kTileThreads, (160u * 1024u) / std::max(Q.lds_bytes, 1u)));
+    Q.grid = tile_cu_count() * per_cu;
+    Q.prof = nullptr;
+#ifdef FBX_TILE_PROF
+    Q.prof = reinterpret_cast<uint64_t*>(ws + plan->off_prof);
+    FBX_LAUNCH(hipMemsetAsync(Q.prof, 0, 32 * 8, st), "clearing phase counters");
+#endif
     if (h.n_ragged) {
       // the counting launch also needs the per-call programs: sizes are unknown, addresses unused
       FBX_LAUNCH(launch_programs(P, st), "program kernel");
@@ -427,6 +449,21 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   }
   FBX_LAUNCH(hipMemcpyAsync(plan->readback.data(), ws, plan->readback.size(), hipMemcpyDeviceToHost, st), "read-back");
   FBX_LAUNCH(hipStreamSynchronize(st), "synchronise");
+#ifdef FBX_TILE_PROF
+  if (g.tile_engine) {
+    uint64_t pc[32];
+    if (hipMemcpy(pc, ws + plan->off_prof, sizeof(pc), hipMemcpyDeviceToHost) == hipSuccess) {
+      for (int k = 0; k < 2; ++k) {
+        uint64_t sum = 0;
+        for (int i = 0; i < 16; ++i) sum += pc[16 * k + i];
+        fprintf(stderr, "[fbx prof] %s T=%u lds=%u grid-cycles=%llu :", k ? "write" : "count", 1u << g.tp.log2T,
+                g.tp.lds_bytes, (unsigned long long)sum);
+        for (int i = 0; i < 13; ++i) fprintf(stderr, " p%d=%.1f%%", i, sum ? 100.0 * pc[16 * k + i] / sum : 0.0);
+        fprintf(stderr, "\n");
+      }
+    }
+  }
+#endif
 #undef FBX_LAUNCH
 
   const Ctrl* c = reinterpret_cast<const Ctrl*>(plan->readback.data() + plan->off_ctrl);

@@ -38,7 +38,7 @@ struct WalkParams {
 };
 
 // ---- tile kernel: one workgroup takes a tile of 2^log2T records through every layer
-constexpr int kTileThreads = 256;
+constexpr int kTileThreads = 512;
 constexpr uint32_t kRawPad = 16;  // first byte position of the staged raw text inside its LDS section
 
 struct TileParams {
@@ -49,23 +49,27 @@ struct TileParams {
   const OpProg* prog;          // [n_ops], per call (absolute addresses)
   const uint32_t* lists;       // work lists (operator indices)
   const uint32_t* list_begin;  // TL_LAYER + 2 * (n_layers - 1) + 1 entries
-  const uint32_t* nonroot;     // operators of layers >= 2, spec order
+  const uint32_t* rnr;         // ragged operators of layers >= 2, spec order
   const uint8_t* aux;
   Ctrl* ctrl;
   uint32_t* tile_cnt;          // [n_ragged][n_tiles], written by the counting launch
   const uint64_t* tile_base;   // [n_ragged][n_tiles], read by the writing launch
-  uint32_t n_ops, n_layers, n_ragged, n_nonroot;
+  uint32_t n_ops, n_layers, n_ragged, n_rnr, n_lists, aux_bytes;
   uint32_t n_tiles, n_fields, n_stage;
+  uint32_t grid;        // workgroups to launch (persistent; they share a tile counter)
   uint32_t log2T;       // records per tile = 1 << log2T (at most 64)
   uint32_t raw_cap;     // bytes of raw text one pass of a workgroup can stage
   uint32_t row_stride;  // u16 entries per record in the field table (n_fields + 1, padded)
   // byte offsets of the LDS sections
   uint32_t o_off, o_rs, o_re, o_rows, o_raw, o_stage, o_cnt, o_start, o_run, o_base;
+  uint32_t o_prog, o_lists, o_lbeg, o_rnr, o_aux;  // plan tables
   uint32_t lds_bytes;
+  uint64_t* prof;  // 32 phase counters (tuning builds only), else NULL
 };
 
 hipError_t launch_tile(const TileParams& P, int write, hipStream_t st);
-uint32_t tile_max_lds();  // dynamic LDS a workgroup of the tile kernel may ask for on this device
+uint32_t tile_max_lds();
+uint32_t tile_cu_count();  // dynamic LDS a workgroup of the tile kernel may ask for on this device
 
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st);
 hipError_t launch_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t raw_len, uint32_t log2T, Ctrl* ctrl,

@@ -89,7 +89,7 @@ struct Ctrl {
   uint64_t n_malformed;
   uint64_t max_tile_bytes;
   uint64_t slow_tiles;     // tiles that did not fit the staged fast path
-  uint64_t pad1;
+  uint32_t ticket[2];      // next tile of the tile kernel's counting / writing launch
 };
 static_assert(sizeof(Ctrl) == 64, "Ctrl must stay 64 bytes");
 
@@ -122,6 +122,7 @@ struct PlanHost {
   std::vector<uint32_t> tile_lists;
   std::vector<uint32_t> tile_list_begin;  // n_tile_lists + 1 entries into tile_lists
   uint32_t n_stage = 0;                   // rows of the on-chip sign table
+  std::vector<uint32_t> ragged_nonroot;   // ragged operators of layers >= 2, spec order
 };
 
 // Work lists of the tile kernel.  Layer 1 has four lists; every later layer l

@@ -352,6 +352,8 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
     plan.tile_lists.insert(plan.tile_lists.end(), l.begin(), l.end());
   }
   plan.tile_list_begin.push_back(static_cast<uint32_t>(plan.tile_lists.size()));
+  for (uint32_t i : plan.nonroot_ops)
+    if (plan.ops[i].d.arity == 0) plan.ragged_nonroot.push_back(i);
   return FBX_OK;
 }
 

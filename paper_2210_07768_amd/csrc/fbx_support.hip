@@ -11,7 +11,7 @@ namespace fbx {
 __global__ void k_reset(Ctrl* ctrl, uint64_t arena_base) {
   if (threadIdx.x == 0) {
     ctrl->err = 0; ctrl->pad0 = 0; ctrl->required = 0; ctrl->head = arena_base; ctrl->high_water = arena_base;
-    ctrl->n_malformed = 0; ctrl->max_tile_bytes = 0; ctrl->slow_tiles = 0; ctrl->pad1 = 0;
+    ctrl->n_malformed = 0; ctrl->max_tile_bytes = 0; ctrl->slow_tiles = 0; ctrl->ticket[0] = 0; ctrl->ticket[1] = 0;
   }
 }
 

@@ -45,6 +45,23 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 extern __shared__ __align__(16) uint8_t smem[];
 
+// Phase timing for tuning builds (-DFBX_TILE_PROF): wavefront 0 charges the cycles
+// since its last mark to a phase; the sums of all workgroups land in P.prof.
+#ifdef FBX_TILE_PROF
+__shared__ unsigned long long s_prof[16];
+__shared__ unsigned long long s_prof_last;
+#define FBX_MARK(n)                                             \
+  do {                                                          \
+    if (threadIdx.x == 0) {                                     \
+      const unsigned long long now_ = clock64();                \
+      s_prof[n] += now_ - s_prof_last;                          \
+      s_prof_last = now_;                                       \
+    }                                                           \
+  } while (0)
+#else
+#define FBX_MARK(n) do {} while (0)
+#endif
+
 __device__ __forceinline__ uint64_t mix64(uint64_t x) {
   x = (x ^ (x >> 30)) * 0xbf58476d1ce4e5b9ull;
   x = (x ^ (x >> 27)) * 0x94d049bb133111ebull;
@@ -65,6 +82,12 @@ struct Sh {
   uint32_t* start;  // [n_ragged][T] their first position, relative to the tile's base
   uint32_t* run;    // [n_ragged] signs of the tile's earlier passes
   uint64_t* base;   // [n_ragged] the tile's base in the operator's values array
+  // plan tables, copied once per workgroup so that no lane waits on memory for a descriptor
+  const OpProg* prog;          // [n_ops]
+  const uint32_t* lists;       // work lists (operator indices)
+  const uint32_t* list_begin;
+  const uint32_t* rnr;         // ragged operators of layers >= 2, spec order
+  const uint8_t* aux;          // bucket boundaries and filter prefixes
 };
 
 __device__ __forceinline__ Sh views(const TileParams& P) {
@@ -79,6 +102,11 @@ __device__ __forceinline__ Sh views(const TileParams& P) {
   s.start = reinterpret_cast<uint32_t*>(smem + P.o_start);
   s.run = reinterpret_cast<uint32_t*>(smem + P.o_run);
   s.base = reinterpret_cast<uint64_t*>(smem + P.o_base);
+  s.prog = reinterpret_cast<const OpProg*>(smem + P.o_prog);
+  s.lists = reinterpret_cast<const uint32_t*>(smem + P.o_lists);
+  s.list_begin = reinterpret_cast<const uint32_t*>(smem + P.o_lbeg);
+  s.rnr = reinterpret_cast<const uint32_t*>(smem + P.o_rnr);
+  s.aux = smem + P.o_aux;
   return s;
 }
 
@@ -123,13 +151,14 @@ __device__ __forceinline__ uint32_t tab_flags(uint32_t w) {
   return ~(((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x | 0x7f7f7f7fu);
 }
 
-// Field table of the staged records.  256 / T lanes (at most 64) share a
+// Field table of the staged records.  kTileThreads / T lanes (at most 64) share a
 // record: each takes an equal run of its dwords, counts its tabs, a prefix sum
 // over the group turns the counts into field numbers, and a second walk writes
 // the positions.  Entries from the record's tab count on hold the record's end.
 __device__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
   const uint32_t tid = threadIdx.x;
-  const uint32_t lg = P.log2T >= 2 ? 8u - P.log2T : 6u;  // log2 of the lanes per record
+  constexpr uint32_t kLogThreads = kTileThreads == 1024 ? 10u : (kTileThreads == 512 ? 9u : 8u);
+  const uint32_t lg = kLogThreads - P.log2T < 6u ? kLogThreads - P.log2T : 6u;  // log2 of the lanes per record
   const uint32_t gsz = 1u << lg;
   const uint32_t j = tid & (gsz - 1u);
   const uint32_t r = tid >> lg;
@@ -174,32 +203,71 @@ __device__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
 }
 
 // ------------------------------------------------------------ token operators
-// FNV-1a over the staged bytes [s, e), eight bytes per window.  The steps of a
-// window nest, so a lane whose token is done leaves the execution mask once.
-__device__ __forceinline__ uint64_t hash_span(const LdsSrc& src, uint32_t s, uint32_t e, uint64_t h) {
+// Eight staged bytes starting at position p (any alignment), in two dwords.
+__device__ __forceinline__ void window8(const LdsSrc& src, uint32_t p, uint32_t& x0, uint32_t& x1) {
   const uint32_t* raw32 = reinterpret_cast<const uint32_t*>(src.raw8);
-  uint32_t p = s, len = e - s;
-  while (len) {
-    const uint32_t a = p >> 2, sh = (p & 3u) * 8u;
-    const uint32_t w0 = raw32[a], w1 = raw32[a + 1], w2 = raw32[a + 2];
-    const uint32_t x0 = __builtin_amdgcn_alignbit(w1, w0, sh), x1 = __builtin_amdgcn_alignbit(w2, w1, sh);
-    const uint32_t n = len < 8u ? len : 8u;
-    uint64_t hh = h;
-#define FBX_STEP(J, X) if (n > (uint32_t)J) { hh = (hh ^ (((X) >> (8 * (J & 3))) & 0xffu)) * kPrime;
+  const uint32_t a = p >> 2, sh = (p & 3u) * 8u;
+  const uint32_t w0 = raw32[a], w1 = raw32[a + 1], w2 = raw32[a + 2];
+  x0 = __builtin_amdgcn_alignbit(w1, w0, sh);
+  x1 = __builtin_amdgcn_alignbit(w2, w1, sh);
+}
+
+// Calls f(byte) for every byte of [s, e), in order.  Staged text is read eight
+// bytes per window; the steps of a window nest, so a lane that is done leaves
+// the execution mask once.
+template <class F>
+__device__ __forceinline__ void for_each_byte(const LdsSrc& src, uint32_t s, uint32_t e, F&& f) {
+  uint32_t p = s;
+  while (p < e) {
+    uint32_t x0, x1;
+    window8(src, p, x0, x1);
+    const uint32_t n = e - p < 8u ? e - p : 8u;
+#define FBX_STEP(J, X) if (n > (uint32_t)J) { f(((X) >> (8 * (J & 3))) & 0xffu);
     FBX_STEP(0, x0) FBX_STEP(1, x0) FBX_STEP(2, x0) FBX_STEP(3, x0)
     FBX_STEP(4, x1) FBX_STEP(5, x1) FBX_STEP(6, x1) FBX_STEP(7, x1)
     }}}}}}}}
 #undef FBX_STEP
-    h = hh;
     p += n;
-    len -= n;
   }
+}
+
+template <class F>
+__device__ __forceinline__ void for_each_byte(const GlobalSrc& src, uint32_t s, uint32_t e, F&& f) {
+  for (uint32_t p = s; p < e; ++p) f(src.byte(p));
+}
+
+// FNV-1a over the bytes [s, e) from state h.
+template <class Src>
+__device__ __forceinline__ uint64_t hash_span(const Src& src, uint32_t s, uint32_t e, uint64_t h) {
+  for_each_byte(src, s, e, [&](uint32_t b) { h = (h ^ b) * kPrime; });
   return h;
 }
 
-__device__ __forceinline__ uint64_t hash_span(const GlobalSrc& src, uint32_t s, uint32_t e, uint64_t h) {
-  for (uint32_t p = s; p < e; ++p) h = (h ^ src.byte(p)) * kPrime;
-  return h;
+// 0x80 in exactly the zero bytes of x.
+__device__ __forceinline__ uint32_t zero_exact(uint32_t x) {
+  return ~(((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x | 0x7f7f7f7fu);
+}
+
+// Number of commas in [s, e).
+__device__ __forceinline__ uint32_t count_commas(const LdsSrc& src, uint32_t s, uint32_t e) {
+  uint32_t c = 0;
+  for (uint32_t p = s; p < e; p += 8u) {
+    uint32_t x0, x1;
+    window8(src, p, x0, x1);
+    const uint32_t n = e - p;  // bytes left, >= 1
+    uint32_t f0 = zero_exact(x0 ^ 0x2c2c2c2cu), f1 = zero_exact(x1 ^ 0x2c2c2c2cu);
+    if (n < 4u) f0 &= (1u << (8u * n)) - 1u;
+    if (n <= 4u) f1 = 0;
+    else if (n < 8u) f1 &= (1u << (8u * (n - 4u))) - 1u;
+    c += __popc(f0) + __popc(f1);
+  }
+  return c;
+}
+
+__device__ __forceinline__ uint32_t count_commas(const GlobalSrc& src, uint32_t s, uint32_t e) {
+  uint32_t c = 0;
+  for (uint32_t p = s; p < e; ++p) c += src.byte(p) == ',' ? 1u : 0u;
+  return c;
 }
 
 struct NumState {
@@ -253,7 +321,7 @@ __device__ __forceinline__ uint64_t single_sign(const Src& src, const OpProg& d,
                                                 uint32_t e, uint32_t& malformed) {
   if (d.kind == OP_HASH) return hash_span(src, s, e, d.key);
   NumState ns;
-  for (uint32_t p = s; p < e; ++p) ns.step(src.byte(p));
+  for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
   return bucket_sign(d, aux, ns, malformed);
 }
 
@@ -262,17 +330,12 @@ template <class Src>
 __device__ __forceinline__ uint32_t ragged_root_count(const Src& src, const OpProg& d, const uint8_t* aux, uint32_t s,
                                                       uint32_t e) {
   const bool multi = d.flags & F_MULTI;
-  if (d.kind != OP_FILTER) {  // multi-valued hash / bucket: items = commas + 1
-    uint32_t c = 1;
-    for (uint32_t p = s; p < e; ++p) c += src.byte(p) == ',' ? 1u : 0u;
-    return c;
-  }
+  if (d.kind != OP_FILTER) return count_commas(src, s, e) + 1u;  // multi-valued hash / bucket
   const uint8_t* pre = aux + d.aux_off;
   const uint32_t plen = d.aux_len;
   uint32_t cnt = 0, k = 0;
   bool match = true;
-  for (uint32_t p = s; p < e; ++p) {
-    const uint32_t b = src.byte(p);
+  for_each_byte(src, s, e, [&](uint32_t b) {
     if (multi && b == ',') {
       cnt += (match && k >= plen) ? 1u : 0u;
       k = 0; match = true;
@@ -280,7 +343,7 @@ __device__ __forceinline__ uint32_t ragged_root_count(const Src& src, const OpPr
       if (k < plen && b != pre[k]) match = false;
       ++k;
     }
-  }
+  });
   cnt += (match && k >= plen) ? 1u : 0u;
   return cnt;
 }
@@ -290,41 +353,40 @@ template <class Src>
 __device__ __forceinline__ void ragged_root_emit(const Src& src, const OpProg& d, const uint8_t* aux, uint32_t s,
                                                  uint32_t e, uint64_t* dst, uint32_t& malformed) {
   const bool multi = d.flags & F_MULTI;
-  if (d.kind == OP_HASH) {
+  if (d.kind == OP_HASH) {  // a ragged hash is always multi-valued
     uint64_t h = d.key;
-    for (uint32_t p = s; p < e; ++p) {
-      const uint32_t b = src.byte(p);
-      if (b == ',') { *dst++ = h; h = d.key; }   // a ragged hash is always multi-valued
+    const uint64_t key = d.key;
+    for_each_byte(src, s, e, [&](uint32_t b) {
+      if (b == ',') { *dst++ = h; h = key; }
       else h = (h ^ b) * kPrime;
-    }
+    });
     *dst = h;
   } else if (d.kind == OP_FILTER) {
     const uint8_t* pre = aux + d.aux_off;
     const uint32_t plen = d.aux_len;
-    uint64_t h = d.key;
+    const uint64_t key = d.key;
+    uint64_t h = key;
     uint32_t k = 0;
     bool match = true;
-    for (uint32_t p = s; p < e; ++p) {
-      const uint32_t b = src.byte(p);
+    for_each_byte(src, s, e, [&](uint32_t b) {
       if (multi && b == ',') {
         if (match && k >= plen) *dst++ = h;
-        h = d.key; k = 0; match = true;
+        h = key; k = 0; match = true;
       } else {
         if (k < plen && b != pre[k]) match = false;
         h = (h ^ b) * kPrime;
         ++k;
       }
-    }
+    });
     if (match && k >= plen) *dst = h;
   } else {  // OP_BUCKET, multi-valued
     NumState ns;
-    for (uint32_t p = s; p < e; ++p) {
-      const uint32_t b = src.byte(p);
+    for_each_byte(src, s, e, [&](uint32_t b) {
       if (b == ',') {
         *dst++ = bucket_sign(d, aux, ns, malformed);
         ns = NumState();
       } else ns.step(b);
-    }
+    });
     *dst = bucket_sign(d, aux, ns, malformed);
   }
 }
@@ -356,38 +418,40 @@ __device__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint
   // ---- counts of the ragged operators, then their positions inside the tile
   if (P.n_ragged) {
     for (uint32_t list = TL_RAGROOT; list <= TL_NGRAM; ++list) {
-      const uint32_t lb = P.list_begin[list], m = P.list_begin[list + 1] - lb;
+      const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
       for (uint32_t base = wave * G; base < m; base += kWaves * G) {
         const uint32_t i = base + og;
         if (i >= m) continue;
-        const OpProg& d = P.prog[P.lists[lb + i]];
+        const OpProg& d = sh.prog[sh.lists[lb + i]];
         uint32_t c = 0;
         if (live) {
           uint32_t s, e;
           src.span(r, d.field, s, e);
           if (d.kind == OP_NGRAM) c = e - s >= d.aux_len ? e - s - d.aux_len + 1u : 0u;
-          else c = ragged_root_count(src, d, P.aux, s, e);
+          else c = ragged_root_count(src, d, sh.aux, s, e);
         }
         if (c > kMaxCount) overflow = true;
         sh.cnt[d.rag_row * T + r] = c;
       }
     }
     __syncthreads();
+    FBX_MARK(4);
     // later layers: counts follow from the inputs' counts, record by record, in spec order
-    if (tid < T) {
-      for (uint32_t k = 0; k < P.n_nonroot; ++k) {
-        const OpProg& d = P.prog[P.nonroot[k]];
-        if (d.rag_row == kNoRow) continue;
-        const OpProg& da = P.prog[d.a];
-        const OpProg& db = P.prog[d.b];
-        const uint64_t ca = da.arity ? da.arity : sh.cnt[da.rag_row * T + tid];
-        const uint64_t cb = db.arity ? db.arity : sh.cnt[db.rag_row * T + tid];
-        const uint64_t c = d.kind == OP_CROSS ? ca * cb : ca + cb;
-        if (c > kMaxCount) overflow = true;
-        sh.cnt[d.rag_row * T + tid] = tid < nb ? (uint32_t)c : 0u;
+    if (P.n_rnr) {
+      if (tid < T) {
+        for (uint32_t k = 0; k < P.n_rnr; ++k) {
+          const OpProg& d = sh.prog[sh.rnr[k]];
+          const OpProg& da = sh.prog[d.a];
+          const OpProg& db = sh.prog[d.b];
+          const uint64_t ca = da.arity ? da.arity : sh.cnt[da.rag_row * T + tid];
+          const uint64_t cb = db.arity ? db.arity : sh.cnt[db.rag_row * T + tid];
+          const uint64_t c = d.kind == OP_CROSS ? ca * cb : ca + cb;
+          if (c > kMaxCount) overflow = true;
+          sh.cnt[d.rag_row * T + tid] = tid < nb ? (uint32_t)c : 0u;
+        }
       }
+      __syncthreads();
     }
-    __syncthreads();
     for (uint32_t base = wave * G; base < P.n_ragged; base += kWaves * G) {
       const uint32_t row = base + og;
       const bool ok = row < P.n_ragged;
@@ -400,31 +464,33 @@ __device__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint
       }
     }
     __syncthreads();
+    FBX_MARK(5);
   }
   if (!WRITE) return;
 
   // ---- layer 1
   // single-valued hashes and buckets: one sign per record
   for (uint32_t list = TL_HASH1; list <= TL_BUCKET1; ++list) {
-    const uint32_t lb = P.list_begin[list], m = P.list_begin[list + 1] - lb;
+    const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
     for (uint32_t base = wave * G; base < m; base += kWaves * G) {
       const uint32_t i = base + og;
       if (i >= m || !live) continue;
-      const OpProg& d = P.prog[P.lists[lb + i]];
+      const OpProg& d = sh.prog[sh.lists[lb + i]];
       uint32_t s, e;
       src.span(r, d.field, s, e);
-      const uint64_t v = single_sign(src, d, P.aux, s, e, malformed);
+      const uint64_t v = single_sign(src, d, sh.aux, s, e, malformed);
       reinterpret_cast<uint64_t*>(d.values)[g] = v;
       if (d.stage != kNoRow) sh.stage[d.stage * T + r] = v;
     }
   }
+  FBX_MARK(6);
   // ragged root operators other than n-grams: a lane writes its record's list
   {
-    const uint32_t lb = P.list_begin[TL_RAGROOT], m = P.list_begin[TL_RAGROOT + 1] - lb;
+    const uint32_t lb = sh.list_begin[TL_RAGROOT], m = sh.list_begin[TL_RAGROOT + 1] - lb;
     for (uint32_t base = wave * G; base < m; base += kWaves * G) {
       const uint32_t i = base + og;
       if (i >= m || !live) continue;
-      const OpProg& d = P.prog[P.lists[lb + i]];
+      const OpProg& d = sh.prog[sh.lists[lb + i]];
       const uint64_t first = sh.base[d.rag_row] + sh.start[d.rag_row * T + r];
       if (d.flags & F_EMIT) {
         uint64_t* off = reinterpret_cast<uint64_t*>(d.offsets);
@@ -433,14 +499,15 @@ __device__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint
       }
       uint32_t s, e;
       src.span(r, d.field, s, e);
-      ragged_root_emit(src, d, P.aux, s, e, reinterpret_cast<uint64_t*>(d.values) + first, malformed);
+      ragged_root_emit(src, d, sh.aux, s, e, reinterpret_cast<uint64_t*>(d.values) + first, malformed);
     }
   }
+  FBX_MARK(7);
   // n-grams: the lanes of a wavefront run over the grams of one record at a time
   {
-    const uint32_t lb = P.list_begin[TL_NGRAM], m = P.list_begin[TL_NGRAM + 1] - lb;
+    const uint32_t lb = sh.list_begin[TL_NGRAM], m = sh.list_begin[TL_NGRAM + 1] - lb;
     for (uint32_t i = 0; i < m; ++i) {
-      const OpProg& d = P.prog[P.lists[lb + i]];
+      const OpProg& d = sh.prog[sh.lists[lb + i]];
       const uint32_t n = d.aux_len;
       uint64_t* vals = reinterpret_cast<uint64_t*>(d.values);
       for (uint32_t rr = wave; rr < nb; rr += kWaves) {
@@ -453,42 +520,42 @@ __device__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint
           off[g_first + rr] = first;
           if (g_first + rr + 1 == R) off[R] = first + ng;
         }
-        for (uint32_t q = lane; q < ng; q += 64) {
-          uint64_t h = d.key;
-          for (uint32_t t = 0; t < n; ++t) h = (h ^ src.byte(s + q + t)) * kPrime;
-          vals[first + q] = h;
-        }
+        const uint64_t key = d.key;
+        for (uint32_t q = lane; q < ng; q += 64) vals[first + q] = hash_span(src, s + q, s + q + n, key);
       }
     }
   }
 
+  FBX_MARK(8);
   // ---- later layers
   for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
     __syncthreads();  // the layer barrier: every sign of the layer before is in place
+    FBX_MARK(9);
     // crosses of two single signs, both on chip
     {
       const uint32_t list = TL_LAYER + 2u * (layer - 2u);
-      const uint32_t lb = P.list_begin[list], m = P.list_begin[list + 1] - lb;
+      const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
       for (uint32_t base = wave * G; base < m; base += kWaves * G) {
         const uint32_t i = base + og;
         if (i >= m || !live) continue;
-        const OpProg& d = P.prog[P.lists[lb + i]];
+        const OpProg& d = sh.prog[sh.lists[lb + i]];
         const uint64_t a = sh.stage[d.aux_off * T + r], b = sh.stage[d.aux_len * T + r];
         const uint64_t v = mix64(mix64(a + d.key) + b);
         reinterpret_cast<uint64_t*>(d.values)[g] = v;
         if (d.stage != kNoRow) sh.stage[d.stage * T + r] = v;
       }
     }
+    FBX_MARK(10);
     // every other cross or concat: inputs are lists in the arrays this workgroup wrote
     {
       const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
-      const uint32_t lb = P.list_begin[list], m = P.list_begin[list + 1] - lb;
+      const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
       for (uint32_t base = wave * G; base < m; base += kWaves * G) {
         const uint32_t i = base + og;
         if (i >= m || !live) continue;
-        const OpProg& d = P.prog[P.lists[lb + i]];
-        const OpProg& da = P.prog[d.a];
-        const OpProg& db = P.prog[d.b];
+        const OpProg& d = sh.prog[sh.lists[lb + i]];
+        const OpProg& da = sh.prog[d.a];
+        const OpProg& db = sh.prog[d.b];
         const uint64_t* pa;
         const uint64_t* pb;
         uint32_t na, nbv;
@@ -525,110 +592,149 @@ __device__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint
         }
       }
     }
+    FBX_MARK(11);
   }
 }
 
 // ------------------------------------------------------------------- kernel
+// Copies n bytes (a multiple of 4) from memory into LDS, all lanes taking part.
+__device__ __forceinline__ void copy_table(uint8_t* dst, const void* src, uint32_t n) {
+  const uint32_t* s32 = reinterpret_cast<const uint32_t*>(src);
+  uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
+  for (uint32_t i = threadIdx.x; i < (n >> 2); i += kTileThreads) d32[i] = s32[i];
+}
+
+// Workgroups are persistent: each copies the plan tables into LDS once and then
+// takes tiles off a shared counter, in increasing order, until none is left.
 template <bool WRITE>
 __global__ __launch_bounds__(kTileThreads) void k_tile(TileParams P) {
   __shared__ uint32_t s_err;
   __shared__ uint32_t s_len;
+  __shared__ uint32_t s_tile;
   const Sh sh = views(P);
   const uint32_t tid = threadIdx.x;
   const uint32_t T = 1u << P.log2T;
-  const uint32_t tile = blockIdx.x;
-  const uint64_t g0 = (uint64_t)tile << P.log2T;
-  const uint32_t nrec = (uint32_t)min((uint64_t)T, P.n_records - g0);
   if (tid == 0) s_err = P.ctrl->err;  // set by an earlier kernel of this call: nothing may be written
-  if (tid <= nrec) sh.off[tid] = P.rec_off[g0 + tid];
-  for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads) {
-    sh.run[row] = 0;
-    if (WRITE) sh.base[row] = P.tile_base[(uint64_t)row * P.n_tiles + tile];
-  }
+  copy_table(smem + P.o_prog, P.prog, P.n_ops * (uint32_t)sizeof(OpProg));
+  copy_table(smem + P.o_lists, P.lists, P.n_ops * 4u);
+  copy_table(smem + P.o_lbeg, P.list_begin, (P.n_lists + 1u) * 4u);
+  copy_table(smem + P.o_rnr, P.rnr, P.n_rnr * 4u);
+  copy_table(smem + P.o_aux, P.aux, P.aux_bytes);
+#ifdef FBX_TILE_PROF
+  if (tid < 16) s_prof[tid] = 0;
+  if (tid == 0) s_prof_last = clock64();
+#endif
   __syncthreads();
   if (s_err) return;
-  uint32_t bad = 0;
-  if (tid < nrec) {
-    const uint64_t a = sh.off[tid], b = sh.off[tid + 1];
-    if (a > b || b > P.raw_len) bad = CE_OFFSETS;
-    else if (b - a >= (1ull << 31)) bad = CE_TILE;
-  }
-  if (__syncthreads_or((int)bad)) {
-    if (bad) atomicOr(&P.ctrl->err, bad);
-    return;
-  }
+  FBX_MARK(0);
 
   uint32_t malformed = 0;
   bool overflow = false;
-  uint32_t r0 = 0;
-  while (r0 < nrec) {  // one turn per pass; all conditions are uniform over the workgroup
-    const uint64_t o0 = sh.off[r0];
-    const uintptr_t addr0 = reinterpret_cast<uintptr_t>(P.raw) + o0;
-    const uint32_t delta = (uint32_t)(addr0 & 15u);
-    // the pass takes records r0 .. r1-1: as many as fit the LDS section
-    uint32_t lo = r0, hi = nrec;
-    while (lo < hi) {
-      const uint32_t mid = (lo + hi + 1u) >> 1;
-      if (sh.off[mid] - o0 + delta <= (uint64_t)P.raw_cap) lo = mid; else hi = mid - 1u;
+  for (;;) {
+    if (tid == 0) s_tile = atomicAdd(&P.ctrl->ticket[WRITE ? 1 : 0], 1u);
+    __syncthreads();
+    const uint32_t tile = s_tile;
+    if (tile >= P.n_tiles) break;
+    const uint64_t g0 = (uint64_t)tile << P.log2T;
+    const uint32_t nrec = (uint32_t)min((uint64_t)T, P.n_records - g0);
+    if (tid <= nrec) sh.off[tid] = P.rec_off[g0 + tid];
+    for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads) {
+      sh.run[row] = 0;
+      if (WRITE) sh.base[row] = P.tile_base[(uint64_t)row * P.n_tiles + tile];
     }
-    const uint32_t r1 = lo;
-    if (r1 > r0) {
-      const uint32_t nb = r1 - r0;
-      const uint32_t nbytes = delta + (uint32_t)(sh.off[r1] - o0);
-      const uint32_t nchunks = (nbytes + 15u) >> 4;
-      const uintptr_t a0 = addr0 - delta;
-      const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(P.raw), ok_hi = ok_lo + P.raw_len;
-      for (uint32_t c = tid; c < nchunks; c += kTileThreads) {
-        const uintptr_t ca = a0 + 16u * c;
-        u32x4 v;
-        if (ca >= ok_lo && ca + 16u <= ok_hi) {
-          v = *reinterpret_cast<const u32x4*>(ca);
-        } else {  // the chunk straddles an end of the caller's buffer: take what exists byte by byte
-          uint32_t w[4] = {0, 0, 0, 0};
-          for (uint32_t i = 0; i < 16; ++i) {
-            const uintptr_t bi = ca + i;
-            if (bi >= ok_lo && bi < ok_hi)
-              w[i >> 2] |= (uint32_t)*reinterpret_cast<const uint8_t*>(bi) << (8u * (i & 3u));
+    __syncthreads();
+    uint32_t bad = 0;
+    if (tid < nrec) {
+      const uint64_t a = sh.off[tid], b = sh.off[tid + 1];
+      if (a > b || b > P.raw_len) bad = CE_OFFSETS;
+      else if (b - a >= (1ull << 31)) bad = CE_TILE;
+    }
+    if (__syncthreads_or((int)bad)) {
+      if (bad) atomicOr(&P.ctrl->err, bad);
+      break;  // the call fails: no point in working off the other tiles
+    }
+    FBX_MARK(1);
+
+    uint32_t r0 = 0;
+    while (r0 < nrec) {  // one turn per pass; all conditions are uniform over the workgroup
+      const uint64_t o0 = sh.off[r0];
+      const uintptr_t addr0 = reinterpret_cast<uintptr_t>(P.raw) + o0;
+      const uint32_t delta = (uint32_t)(addr0 & 15u);
+      // the pass takes records r0 .. r1-1: as many as fit the LDS section
+      uint32_t lo = r0, hi = nrec;
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1u) >> 1;
+        if (sh.off[mid] - o0 + delta <= (uint64_t)P.raw_cap) lo = mid; else hi = mid - 1u;
+      }
+      const uint32_t r1 = lo;
+      if (r1 > r0) {
+        const uint32_t nb = r1 - r0;
+        const uint32_t nbytes = delta + (uint32_t)(sh.off[r1] - o0);
+        const uint32_t nchunks = (nbytes + 15u) >> 4;
+        const uintptr_t a0 = addr0 - delta;
+        const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(P.raw), ok_hi = ok_lo + P.raw_len;
+        for (uint32_t c = tid; c < nchunks; c += kTileThreads) {
+          const uintptr_t ca = a0 + 16u * c;
+          u32x4 v;
+          if (ca >= ok_lo && ca + 16u <= ok_hi) {
+            v = *reinterpret_cast<const u32x4*>(ca);
+          } else {  // the chunk straddles an end of the caller's buffer: take what exists byte by byte
+            uint32_t w[4] = {0, 0, 0, 0};
+            for (uint32_t i = 0; i < 16; ++i) {
+              const uintptr_t bi = ca + i;
+              if (bi >= ok_lo && bi < ok_hi)
+                w[i >> 2] |= (uint32_t)*reinterpret_cast<const uint8_t*>(bi) << (8u * (i & 3u));
+            }
+            v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
           }
-          v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
+          *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = v;
         }
-        *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = v;
+        if (tid < nb) {
+          sh.rs[tid] = kRawPad + delta + (uint32_t)(sh.off[r0 + tid] - o0);
+          sh.re[tid] = kRawPad + delta + (uint32_t)(sh.off[r0 + tid + 1] - o0);
+        }
+        __syncthreads();
+        // one trailing newline is not part of the record
+        if (tid < nb) {
+          const uint32_t e = sh.re[tid];
+          if (e > sh.rs[tid] && sh.raw[e - 1u] == '\n') sh.re[tid] = e - 1u;
+        }
+        __syncthreads();
+        FBX_MARK(2);
+        tokenize(P, sh, nb);
+        __syncthreads();
+        FBX_MARK(3);
+        LdsSrc src{sh.raw, sh.rows, P.row_stride};
+        run_pass<WRITE>(P, sh, src, nb, g0 + r0, malformed, overflow);
+        r0 = r1;
+      } else {
+        // record r0 alone exceeds the section: it is read in place
+        const uint64_t len64 = sh.off[r0 + 1] - o0;
+        if (tid == 0) {
+          uint32_t len = (uint32_t)len64;
+          if (len && P.raw[o0 + len - 1u] == '\n') --len;
+          s_len = len;
+        }
+        __syncthreads();
+        GlobalSrc src{P.raw + o0, s_len};
+        run_pass<WRITE>(P, sh, src, 1u, g0 + r0, malformed, overflow);
+        r0 += 1u;
       }
-      if (tid < nb) {
-        sh.rs[tid] = kRawPad + delta + (uint32_t)(sh.off[r0 + tid] - o0);
-        sh.re[tid] = kRawPad + delta + (uint32_t)(sh.off[r0 + tid + 1] - o0);
-      }
-      __syncthreads();
-      // one trailing newline is not part of the record
-      if (tid < nb) {
-        const uint32_t e = sh.re[tid];
-        if (e > sh.rs[tid] && sh.raw[e - 1u] == '\n') sh.re[tid] = e - 1u;
-      }
-      __syncthreads();
-      tokenize(P, sh, nb);
-      __syncthreads();
-      LdsSrc src{sh.raw, sh.rows, P.row_stride};
-      run_pass<WRITE>(P, sh, src, nb, g0 + r0, malformed, overflow);
-      r0 = r1;
-    } else {
-      // record r0 alone exceeds the section: it is read in place
-      const uint64_t len64 = sh.off[r0 + 1] - o0;
-      if (tid == 0) {
-        uint32_t len = (uint32_t)len64;
-        if (len && P.raw[o0 + len - 1u] == '\n') --len;
-        s_len = len;
-      }
-      __syncthreads();
-      GlobalSrc src{P.raw + o0, s_len};
-      run_pass<WRITE>(P, sh, src, 1u, g0 + r0, malformed, overflow);
-      r0 += 1u;
+      __syncthreads();  // the sections are reused by the next pass
+      FBX_MARK(12);
     }
-    __syncthreads();  // the sections are reused by the next pass
+    if (!WRITE) {
+      for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads)
+        P.tile_cnt[(uint64_t)row * P.n_tiles + tile] = sh.run[row];
+    }
+    __syncthreads();  // s_tile and the tile's sections are rewritten next
   }
 
+#ifdef FBX_TILE_PROF
+  __syncthreads();
+  if (tid < 16 && P.prof) atomicAdd(reinterpret_cast<unsigned long long*>(P.prof) + tid + (WRITE ? 16 : 0), s_prof[tid]);
+#endif
   if (!WRITE) {
-    for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads)
-      P.tile_cnt[(uint64_t)row * P.n_tiles + tile] = sh.run[row];
     if (overflow) atomicOr(&P.ctrl->err, (uint32_t)CE_OVERFLOW);
   } else {
     for (int d = 32; d >= 1; d >>= 1) malformed += __shfl_xor(malformed, d, 64);
@@ -660,9 +766,23 @@ hipError_t launch_tile(const TileParams& P, int write, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds_bytes);
     if (e != hipSuccess) return e;
   }
-  if (write) hipLaunchKernelGGL(k_tile<true>, dim3(P.n_tiles), dim3(kTileThreads), P.lds_bytes, st, P);
-  else hipLaunchKernelGGL(k_tile<false>, dim3(P.n_tiles), dim3(kTileThreads), P.lds_bytes, st, P);
+  const uint32_t grid = std::min(P.n_tiles, P.grid);
+  if (write) hipLaunchKernelGGL(k_tile<true>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
+  else hipLaunchKernelGGL(k_tile<false>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
   return hipGetLastError();
+}
+
+uint32_t tile_cu_count() {
+  static uint32_t cached = 0;
+  if (!cached) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cached = (uint32_t)v;
+    else
+      cached = 256u;
+  }
+  return cached;
 }
 
 }  // namespace fbx
