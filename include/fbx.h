@@ -58,6 +58,10 @@ typedef struct {
   uint32_t n_layers;
   const fbx_slot_view* slots;   /* HOST, n_slots entries in spec order; valid until the next
                                    fbx_extract or fbx_plan_destroy on this plan             */
+  uint32_t tile_launches;       /* launches of the tile kernel this call took: 2 = counting +
+                                   writing, 1 = one launch (no ragged slots, or ragged arrays
+                                   sized from the previous call), 0 = the walk kernels ran    */
+  uint32_t reserved;
 } fbx_result;
 
 /*

@@ -39,7 +39,8 @@ class Result(ctypes.Structure):
     _fields_ = [("n_records", ctypes.c_uint64), ("n_values_total", ctypes.c_uint64),
                 ("n_malformed_numeric", ctypes.c_uint64), ("arena_high_water", ctypes.c_uint64),
                 ("n_slots", ctypes.c_uint32), ("n_layers", ctypes.c_uint32),
-                ("slots", ctypes.POINTER(SlotView))]
+                ("slots", ctypes.POINTER(SlotView)),
+                ("tile_launches", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 _lib = None
@@ -100,6 +101,7 @@ class ExtractResult:
         self.n_malformed_numeric = 0
         self.arena_high_water = 0
         self.n_layers = 0
+        self.tile_launches = 0
         self.slots: Dict[int, Slot] = {}
         self.slot_ids: List[int] = []
 
@@ -176,6 +178,7 @@ class Plan:
         out.n_records, out.n_values_total = res.n_records, res.n_values_total
         out.n_malformed_numeric, out.arena_high_water = res.n_malformed_numeric, res.arena_high_water
         out.n_layers = res.n_layers
+        out.tile_launches = res.tile_launches
         base = self._ws.data_ptr()
         ws64 = self._ws[: self._ws.numel() // 8 * 8].view(torch.int64)
         for i in range(res.n_slots):

@@ -35,7 +35,7 @@ struct fbx_plan {
   // constant-table placement inside the workspace (byte offsets)
   uint64_t off_ctrl = 0, off_dyn = 0, off_ops = 0, off_layer_ops = 0, off_layer_begin = 0, off_nonroot = 0,
            off_aux = 0, off_fields = 0, off_field_ops = 0, off_prog_ops = 0, off_prog_fields = 0, off_row_total = 0,
-           off_tile_lists = 0, off_tile_list_begin = 0, off_rnr = 0, off_prof = 0, off_static_end = 0;
+           off_tile_lists = 0, off_tile_list_begin = 0, off_rnr = 0, off_prof = 0, off_actual = 0, off_cap = 0, off_static_end = 0;
 
   // options
   int fused = 1;
@@ -44,6 +44,15 @@ struct fbx_plan {
   int tile_log2 = -1;             // -1: chosen per call
   uint32_t raw_cap = 0;           // 0: chosen per call
   uint32_t lds_budget = 64u * 1024u;
+  uint32_t dbg = 0;
+  int one_launch = 1;             // size ragged arrays from the last call and skip the counting launch
+
+  // what the last successful call taught about ragged sizes (signs per ragged operator)
+  bool learned = false;
+  uint64_t learned_records = 0;
+  std::vector<uint64_t> learned_total;   // by ragged row
+  std::vector<uint64_t> cap_host;        // capacities of the current call, by ragged row
+  int last_mode = 0;                     // 1: counting + writing launch, 2: one launch
 
   // results of the last call
   std::vector<uint8_t> readback;  // Ctrl + OpDyn[n_ops]
@@ -59,7 +68,8 @@ struct fbx_plan {
     const uint64_t n = host.ops.size();
     uint64_t o = 0;
     off_ctrl = o; o += sizeof(Ctrl);
-    off_dyn = o; o = align_up(o + n * sizeof(OpDyn));
+    off_dyn = o; o += n * sizeof(OpDyn);
+    off_actual = o; o = align_up(o + host.n_ragged * 8ull);  // read back together with the placements
     off_ops = o; o = align_up(o + n * sizeof(OpDesc));
     off_layer_ops = o; o = align_up(o + n * 4);
     off_layer_begin = o; o = align_up(o + (host.n_layers + 1) * 4);
@@ -74,6 +84,7 @@ struct fbx_plan {
     off_tile_list_begin = o; o = align_up(o + host.tile_list_begin.size() * 4);
     off_rnr = o; o = align_up(o + host.ragged_nonroot.size() * 4);
     off_prof = o; o = align_up(o + 32 * 8);
+    off_cap = o; o = align_up(o + host.n_ragged * 8ull);
     off_static_end = o;
   }
 };
@@ -92,11 +103,14 @@ uint32_t round16(uint64_t x) { return static_cast<uint32_t>((x + 15u) & ~uint64_
 // LDS layout of the tile kernel for tiles of 2^lt records and raw_cap staged bytes.
 void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParams& tp) {
   const uint32_t T = 1u << lt;
+  tp.n_mh = 0;
+  for (uint32_t i = h.tile_list_begin[TL_RAGROOT]; i < h.tile_list_begin[TL_RAGROOT + 1]; ++i)
+    if (h.ops[h.tile_lists[i]].d.kind == OP_HASH) ++tp.n_mh;  // the list is sorted by kind, hashes first
   tp.log2T = lt;
   tp.raw_cap = raw_cap;
   tp.row_stride = (h.n_fields + 1u) | 1u;  // odd: neighbouring records start in different banks
   uint32_t o = 0;
-  tp.o_off = o; o = round16(o + 8ull * (T + 1));
+  tp.o_off = o; o = round16(o + 2 * 8ull * (T + 1));  // this tile's offsets and the next one's
   tp.o_rs = o; o = round16(o + 4ull * T);
   tp.o_re = o; o = round16(o + 4ull * T);
   tp.o_rows = o; o = round16(o + 2ull * T * tp.row_stride);
@@ -106,6 +120,10 @@ void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParam
   tp.o_start = o; o = round16(o + 4ull * T * h.n_ragged);
   tp.o_run = o; o = round16(o + 4ull * h.n_ragged);
   tp.o_base = o; o = round16(o + 8ull * h.n_ragged);
+  tp.o_tot = o; o = round16(o + 4ull * h.n_ragged);
+  tp.o_ioff = o; o = round16(o + 4ull * (tp.n_mh + 1));
+  tp.item_cap = 16;
+  tp.o_ctab = o; o = round16(o + 2ull * tp.n_mh * T * tp.item_cap);
   tp.o_prog = o; o = round16(o + sizeof(OpProg) * h.ops.size());
   tp.o_lists = o; o = round16(o + 4ull * h.tile_lists.size());
   tp.o_lbeg = o; o = round16(o + 4ull * h.tile_list_begin.size());
@@ -194,7 +212,7 @@ fbx_status fbx_plan_create(const char* spec, size_t spec_len, fbx_plan** out) {
     if (p->host.ops[i].d.flags & F_EMIT) p->emitted.push_back(i);
   p->slots.resize(p->emitted.size());
   p->layout();
-  p->readback.resize(p->off_dyn + p->host.ops.size() * sizeof(OpDyn));
+  p->readback.resize(p->off_actual + p->host.n_ragged * 8ull);
   *out = p.release();
   return FBX_OK;
 }
@@ -237,6 +255,11 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "lds_budget") {
     if (value < 4096 || value > 160 * 1024) { plan->error = "lds_budget must be in 4096..163840"; return FBX_E_ARG; }
     plan->lds_budget = static_cast<uint32_t>(value);
+  } else if (k == "one_launch") {
+    if (value != 0 && value != 1) { plan->error = "one_launch must be 0 or 1"; return FBX_E_ARG; }
+    plan->one_launch = static_cast<int>(value);
+  } else if (k == "debug_skip") {
+    plan->dbg = static_cast<uint32_t>(value);
   } else if (k == "profile") {
     if (value != 0 && value != 1) { plan->error = "profile must be 0 or 1"; return FBX_E_ARG; }
     plan->profile = static_cast<int>(value);
@@ -365,108 +388,161 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     if (e_ != hipSuccess) return hip_fail(plan, e_, what);     \
   } while (0)
 
-  FBX_LAUNCH(launch_reset(ctrl, g.arena_base, st), "reset");
-  if (g.tile_engine) {
-    // one workgroup per tile takes its records through every layer; offsets are checked tile by tile
-    TileParams Q = g.tp;
-    Q.raw = d_raw; Q.raw_len = raw_len; Q.rec_off = d_rec_off; Q.n_records = n_records;
-    Q.prog = P.prog_ops;
-    Q.lists = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_lists);
-    Q.list_begin = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_list_begin);
-    Q.rnr = reinterpret_cast<const uint32_t*>(ws + plan->off_rnr);
-    Q.aux = P.aux; Q.ctrl = ctrl;
-    Q.tile_cnt = P.tile_cnt; Q.tile_base = P.tile_base;
-    Q.n_ops = n_ops; Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged;
-    Q.n_rnr = static_cast<uint32_t>(h.ragged_nonroot.size());
-    Q.n_lists = static_cast<uint32_t>(h.tile_list_begin.size()) - 1u;
-    Q.aux_bytes = static_cast<uint32_t>(h.aux.size());
-    Q.n_tiles = g.n_tiles; Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
-    Q.lds_bytes = std::max(Q.lds_bytes, plan->lds_pad);
-    // persistent workgroups: as many as the LDS (and 2048 lanes per compute unit) let run at once
-    const uint32_t per_cu = std::max(1u, std::min(2048u / kTileThreads, (160u * 1024u) / std::max(Q.lds_bytes, 1u)));
-    Q.grid = tile_cu_count() * per_cu;
-    Q.prof = nullptr;
+  // One attempt: everything is enqueued on the stream, then one synchronisation.
+  auto run = [&](bool one) -> fbx_status {
+    for (Timer& t : plan->timers) t.used = false;
+    plan->tile_launch_layer.clear();
+    FBX_LAUNCH(launch_reset(ctrl, g.arena_base, st), "reset");
+    if (g.tile_engine) {
+      // one workgroup per tile takes its records through every layer; offsets are checked tile by tile
+      TileParams Q = g.tp;
+      Q.raw = d_raw; Q.raw_len = raw_len; Q.rec_off = d_rec_off; Q.n_records = n_records;
+      Q.prog = P.prog_ops;
+      Q.lists = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_lists);
+      Q.list_begin = reinterpret_cast<const uint32_t*>(ws + plan->off_tile_list_begin);
+      Q.rnr = reinterpret_cast<const uint32_t*>(ws + plan->off_rnr);
+      Q.aux = P.aux; Q.ctrl = ctrl;
+      Q.tile_cnt = P.tile_cnt; Q.tile_base = P.tile_base;
+      Q.lb_state = nullptr; Q.row_cap = nullptr; Q.row_actual = nullptr;
+      Q.n_ops = n_ops; Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged;
+      Q.n_rnr = static_cast<uint32_t>(h.ragged_nonroot.size());
+      Q.n_lists = static_cast<uint32_t>(h.tile_list_begin.size()) - 1u;
+      Q.aux_bytes = static_cast<uint32_t>(h.aux.size());
+
+      Q.n_tiles = g.n_tiles; Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
+      Q.lds_bytes = std::max(Q.lds_bytes, plan->lds_pad);
+      // persistent workgroups: as many as the LDS (and 2048 lanes per compute unit) let run at once
+      const uint32_t per_cu = std::max(1u, std::min(2048u / kTileThreads, (160u * 1024u) / std::max(Q.lds_bytes, 1u)));
+      Q.grid = tile_cu_count() * per_cu;
+      Q.prof = nullptr;
+      Q.dbg = plan->dbg;
 #ifdef FBX_TILE_PROF
-    Q.prof = reinterpret_cast<uint64_t*>(ws + plan->off_prof);
-    FBX_LAUNCH(hipMemsetAsync(Q.prof, 0, 32 * 8, st), "clearing phase counters");
+      Q.prof = reinterpret_cast<uint64_t*>(ws + plan->off_prof);
+      FBX_LAUNCH(hipMemsetAsync(Q.prof, 0, 32 * 8, st), "clearing phase counters");
 #endif
-    if (h.n_ragged) {
-      // the counting launch also needs the per-call programs: sizes are unknown, addresses unused
-      FBX_LAUNCH(launch_programs(P, st), "program kernel");
-      if (g.n_tiles) {
-        tick(1, 0);
-        FBX_LAUNCH(launch_tile(Q, 0, st), "tile kernel (counting)");
-        tick(1, 1);
-      }
-      tick(2, 0);
-      FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
-      tick(2, 1);
-    }
-    tick(3, 0);
-    FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, 0, st), "allocation kernel");
-    tick(3, 1);
-    if (g.n_tiles) {
-      tick(4, 0);
-      FBX_LAUNCH(launch_tile(Q, 1, st), "tile kernel");
-      tick(4, 1);
-      plan->tile_launch_layer.push_back(1);
-    }
-  } else {
-    tick(0, 0);
-    FBX_LAUNCH(launch_validate(d_rec_off, n_records, raw_len, kTileLog2, ctrl, st), "validate");
-    tick(0, 1);
-    if (h.n_ragged) {
-      if (g.n_tiles) {
-        tick(1, 0);
-        P.layer_lo = 1; P.layer_hi = h.n_layers;
-        FBX_LAUNCH(launch_count(P, st), "count kernel");
-        tick(1, 1);
-      }
-      tick(2, 0);
-      FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
-      tick(2, 1);
-    }
-    tick(3, 0);
-    FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, plan->fused ? 0 : 1, st), "allocation kernel");
-    tick(3, 1);
-    if (g.n_tiles) {
-      if (plan->fused) {
-        P.layer_lo = 1; P.layer_hi = h.n_layers;
+      if (one) {
+        // one launch: arrays sized from what the last call produced, bases found by look-back
+        Q.row_cap = reinterpret_cast<const uint64_t*>(ws + plan->off_cap);
+        Q.row_actual = reinterpret_cast<uint64_t*>(ws + plan->off_actual);
+        Q.lb_state = P.tile_base;
+        FBX_LAUNCH(hipMemcpyAsync(ws + plan->off_cap, plan->cap_host.data(), h.n_ragged * 8ull, hipMemcpyHostToDevice, st),
+                   "capacity upload");
+        tick(3, 0);
+        FBX_LAUNCH(launch_alloc(P, Q.row_cap, plan->ws_bytes, 0, st), "allocation kernel");
+        tick(3, 1);
+        FBX_LAUNCH(launch_fill64(Q.lb_state, uint64_t(h.n_ragged) * g.n_tiles, 0, st), "look-back state");
         tick(4, 0);
-        FBX_LAUNCH(launch_walk(P, st), "walk kernel");
+        FBX_LAUNCH(launch_tile(Q, 2, st), "tile kernel (one launch)");
         tick(4, 1);
         plan->tile_launch_layer.push_back(1);
       } else {
-        for (uint32_t l = 1; l <= h.n_layers; ++l) {
-          P.layer_lo = P.layer_hi = l;
-          tick(3 + l, 0);
+        if (h.n_ragged) {
+          // the counting launch also needs the per-call programs: sizes are unknown, addresses unused
+          FBX_LAUNCH(launch_programs(P, st), "program kernel");
+          if (g.n_tiles) {
+            tick(1, 0);
+            FBX_LAUNCH(launch_tile(Q, 0, st), "tile kernel (counting)");
+            tick(1, 1);
+          }
+          tick(2, 0);
+          FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
+          tick(2, 1);
+        }
+        tick(3, 0);
+        FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, 0, st), "allocation kernel");
+        tick(3, 1);
+        if (g.n_tiles) {
+          tick(4, 0);
+          FBX_LAUNCH(launch_tile(Q, 1, st), "tile kernel");
+          tick(4, 1);
+          plan->tile_launch_layer.push_back(1);
+        }
+      }
+    } else {
+      tick(0, 0);
+      FBX_LAUNCH(launch_validate(d_rec_off, n_records, raw_len, kTileLog2, ctrl, st), "validate");
+      tick(0, 1);
+      if (h.n_ragged) {
+        if (g.n_tiles) {
+          tick(1, 0);
+          P.layer_lo = 1; P.layer_hi = h.n_layers;
+          FBX_LAUNCH(launch_count(P, st), "count kernel");
+          tick(1, 1);
+        }
+        tick(2, 0);
+        FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
+        tick(2, 1);
+      }
+      tick(3, 0);
+      FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, plan->fused ? 0 : 1, st), "allocation kernel");
+      tick(3, 1);
+      if (g.n_tiles) {
+        if (plan->fused) {
+          P.layer_lo = 1; P.layer_hi = h.n_layers;
+          tick(4, 0);
           FBX_LAUNCH(launch_walk(P, st), "walk kernel");
-          tick(3 + l, 1);
-          plan->tile_launch_layer.push_back(l);
+          tick(4, 1);
+          plan->tile_launch_layer.push_back(1);
+        } else {
+          for (uint32_t l = 1; l <= h.n_layers; ++l) {
+            P.layer_lo = P.layer_hi = l;
+            tick(3 + l, 0);
+            FBX_LAUNCH(launch_walk(P, st), "walk kernel");
+            tick(3 + l, 1);
+            plan->tile_launch_layer.push_back(l);
+          }
         }
       }
     }
-  }
-  FBX_LAUNCH(hipMemcpyAsync(plan->readback.data(), ws, plan->readback.size(), hipMemcpyDeviceToHost, st), "read-back");
-  FBX_LAUNCH(hipStreamSynchronize(st), "synchronise");
+    FBX_LAUNCH(hipMemcpyAsync(plan->readback.data(), ws, plan->readback.size(), hipMemcpyDeviceToHost, st), "read-back");
+    FBX_LAUNCH(hipStreamSynchronize(st), "synchronise");
 #ifdef FBX_TILE_PROF
-  if (g.tile_engine) {
-    uint64_t pc[32];
-    if (hipMemcpy(pc, ws + plan->off_prof, sizeof(pc), hipMemcpyDeviceToHost) == hipSuccess) {
-      for (int k = 0; k < 2; ++k) {
-        uint64_t sum = 0;
-        for (int i = 0; i < 16; ++i) sum += pc[16 * k + i];
-        fprintf(stderr, "[fbx prof] %s T=%u lds=%u grid-cycles=%llu :", k ? "write" : "count", 1u << g.tp.log2T,
-                g.tp.lds_bytes, (unsigned long long)sum);
-        for (int i = 0; i < 13; ++i) fprintf(stderr, " p%d=%.1f%%", i, sum ? 100.0 * pc[16 * k + i] / sum : 0.0);
-        fprintf(stderr, "\n");
+    if (g.tile_engine) {
+      uint64_t pc[32];
+      if (hipMemcpy(pc, ws + plan->off_prof, sizeof(pc), hipMemcpyDeviceToHost) == hipSuccess) {
+        for (int k = 0; k < 2; ++k) {
+          uint64_t sum = 0;
+          for (int i = 0; i < 16; ++i) sum += pc[16 * k + i];
+          fprintf(stderr, "[fbx prof] %s T=%u lds=%u grid-cycles=%llu :", k ? "write" : "count", 1u << g.tp.log2T,
+                  g.tp.lds_bytes, (unsigned long long)sum);
+          for (int i = 0; i < 13; ++i) fprintf(stderr, " p%d=%.1f%%", i, sum ? 100.0 * pc[16 * k + i] / sum : 0.0);
+          fprintf(stderr, "\n");
+        }
       }
     }
-  }
 #endif
+    return FBX_OK;
+  };
+  // Ragged arrays can be sized from what the last call produced (plus a margin): then the
+  // counting launch is skipped.  A batch that does not fit its arrays, or a tile that needs
+  // several passes, sends the call back to the exact sequence.
+  bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records;
+  if (one) {
+    plan->cap_host.resize(h.n_ragged);
+    for (uint32_t r = 0; r < h.n_ragged; ++r) {
+      const unsigned __int128 scaled =
+          (unsigned __int128)plan->learned_total[r] * n_records / plan->learned_records;
+      const unsigned __int128 cap = scaled + scaled / 64 + 256;
+      plan->cap_host[r] = cap > (unsigned __int128)(1ull << 60) ? (1ull << 60) : (uint64_t)cap;
+    }
+  }
+  const Ctrl* c = reinterpret_cast<const Ctrl*>(plan->readback.data() + plan->off_ctrl);
+  for (;;) {
+    fbx_status rs = run(one);
+    if (rs != FBX_OK) return rs;
+    if (c->err & CE_STALL) {
+      plan->error = "internal: a bounded wait between tiles ran out";
+      return FBX_E_HIP;
+    }
+    if (one && (c->err & (CE_SPEC | CE_NOMEM))) {
+      one = false;  // fall back to counting first
+      continue;
+    }
+    break;
+  }
+  plan->last_mode = one ? 2 : 1;
 #undef FBX_LAUNCH
 
-  const Ctrl* c = reinterpret_cast<const Ctrl*>(plan->readback.data() + plan->off_ctrl);
   const OpDyn* y = reinterpret_cast<const OpDyn*>(plan->readback.data() + plan->off_dyn);
   if (c->err & CE_OFFSETS) {
     plan->error = "record offsets must be non-decreasing and end within raw_len";
@@ -485,6 +561,17 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     plan->error = "workspace too small: need " + std::to_string(c->required) + " bytes";
     return FBX_E_NOMEM;
   }
+  const uint64_t* actual = reinterpret_cast<const uint64_t*>(plan->readback.data() + plan->off_actual);
+  if (h.n_ragged && n_records) {  // remember the sizes for the next call
+    plan->learned_total.resize(h.n_ragged);
+    for (const HostOp& op : h.ops)
+      if (!op.d.arity) {
+        const size_t i = static_cast<size_t>(&op - h.ops.data());
+        plan->learned_total[op.d.rag_row] = one ? actual[op.d.rag_row] : y[i].n_values;
+      }
+    plan->learned_records = n_records;
+    plan->learned = true;
+  }
   uint64_t total = 0;
   for (size_t s = 0; s < plan->emitted.size(); ++s) {
     const uint32_t i = plan->emitted[s];
@@ -492,7 +579,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     fbx_slot_view& v = plan->slots[s];
     v.slot_id = h.ops[i].slot;
     v.fixed_arity = d.arity;
-    v.n_values = y[i].n_values;
+    v.n_values = (one && !d.arity) ? actual[d.rag_row] : y[i].n_values;
     v.values = reinterpret_cast<const uint64_t*>(ws + y[i].values_off);
     v.offsets = d.arity ? nullptr : reinterpret_cast<const uint64_t*>(ws + y[i].offsets_off);
     total += v.n_values;
@@ -504,6 +591,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   out->n_slots = static_cast<uint32_t>(plan->slots.size());
   out->n_layers = h.n_layers;
   out->slots = plan->slots.data();
+  out->tile_launches = g.tile_engine ? (one ? 1u : (h.n_ragged ? 2u : 1u)) : 0u;
   return FBX_OK;
 }
 

@@ -54,7 +54,11 @@ struct TileParams {
   Ctrl* ctrl;
   uint32_t* tile_cnt;          // [n_ragged][n_tiles], written by the counting launch
   const uint64_t* tile_base;   // [n_ragged][n_tiles], read by the writing launch
+  uint64_t* lb_state;          // [n_ragged][n_tiles] look-back words (mode 2; shares the tile_base storage)
+  const uint64_t* row_cap;     // [n_ragged] signs the arrays were sized for (mode 2)
+  uint64_t* row_actual;        // [n_ragged] signs actually produced (mode 2)
   uint32_t n_ops, n_layers, n_ragged, n_rnr, n_lists, aux_bytes;
+  uint32_t n_mh;        // multi-valued hashes: the first n_mh entries of the ragged root list
   uint32_t n_tiles, n_fields, n_stage;
   uint32_t grid;        // workgroups to launch (persistent; they share a tile counter)
   uint32_t log2T;       // records per tile = 1 << log2T (at most 64)
@@ -63,11 +67,17 @@ struct TileParams {
   // byte offsets of the LDS sections
   uint32_t o_off, o_rs, o_re, o_rows, o_raw, o_stage, o_cnt, o_start, o_run, o_base;
   uint32_t o_prog, o_lists, o_lbeg, o_rnr, o_aux;  // plan tables
+  uint32_t o_tot, o_ioff, o_ctab;
+  uint32_t item_cap;    // comma positions kept per record and multi-valued hash
   uint32_t lds_bytes;
   uint64_t* prof;  // 32 phase counters (tuning builds only), else NULL
+  uint32_t dbg;    // phases to leave out (tuning builds only; results are then wrong)
 };
 
-hipError_t launch_tile(const TileParams& P, int write, hipStream_t st);
+// mode 0: counting launch; 1: writing launch (bases from the scan over tiles);
+// 2: counting and writing in one launch (bases by look-back, arrays sized by row_cap)
+hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st);
+hipError_t launch_fill64(uint64_t* p, uint64_t n, uint64_t value, hipStream_t st);
 uint32_t tile_max_lds();
 uint32_t tile_cu_count();  // dynamic LDS a workgroup of the tile kernel may ask for on this device
 

@@ -3,6 +3,8 @@
 // paper and the per-call carving of operator arrays).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "fbx_device.h"
 
 namespace fbx {
@@ -228,6 +230,10 @@ __global__ __launch_bounds__(kBlock) void k_alloc(WalkParams P, const uint64_t* 
 // all the counting launch of the tile kernel needs.
 __global__ __launch_bounds__(kBlock) void k_programs(WalkParams P) { write_programs(P, false); }
 
+__global__ void k_fill64(uint64_t* p, uint64_t n, uint64_t value) {
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) p[i] = value;
+}
+
 // ----------------------------------------------------------- launch wrappers
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st) {
   hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctrl, arena_base);
@@ -251,6 +257,13 @@ hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* 
 
 hipError_t launch_alloc(const WalkParams& P, const uint64_t* row_total, uint64_t ws_bytes, int reuse, hipStream_t st) {
   hipLaunchKernelGGL(k_alloc, dim3(1), dim3(kBlock), 0, st, P, row_total, ws_bytes, reuse);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill64(uint64_t* p, uint64_t n, uint64_t value, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const uint32_t blocks = (uint32_t)std::min<uint64_t>((n + 255) / 256, 8192);
+  hipLaunchKernelGGL(k_fill64, dim3(blocks), dim3(256), 0, st, p, n, value);
   return hipGetLastError();
 }
 

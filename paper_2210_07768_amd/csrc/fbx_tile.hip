@@ -24,6 +24,10 @@
 //     turned into positions by a prefix sum over the tile's records on top of
 //     the tile's base (a counting launch of this same kernel and a scan over
 //     tiles provide it).
+//  6. Workgroups are persistent and software-pipelined: while a tile is worked
+//     on, the ticket of the tile after the next, the record offsets of the next
+//     tile and then its raw text are already on their way (the text waits in
+//     registers until the LDS section is free).
 //
 // A tile whose text does not fit the LDS section is worked off in several
 // passes of fewer records; a single record that does not fit alone is walked
@@ -43,6 +47,16 @@ constexpr uint32_t kMaxCount = 0x3ffffffu;  // signs per record and operator
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Pointers the compiler knows to be global memory (plain global loads and stores
+// instead of flat ones, which would also wait on the LDS counter).
+#define FBX_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ FBX_GLOBAL T* gptr(uint64_t addr) { return reinterpret_cast<FBX_GLOBAL T*>(addr); }
+template <class T>
+__device__ __forceinline__ FBX_GLOBAL T* gptr(T* p) { return reinterpret_cast<FBX_GLOBAL T*>(reinterpret_cast<uintptr_t>(p)); }
+using G64 = FBX_GLOBAL uint64_t*;
+using CG64 = const FBX_GLOBAL uint64_t*;
+
 extern __shared__ __align__(16) uint8_t smem[];
 
 // Phase timing for tuning builds (-DFBX_TILE_PROF): wavefront 0 charges the cycles
@@ -58,8 +72,10 @@ __shared__ unsigned long long s_prof_last;
       s_prof_last = now_;                                       \
     }                                                           \
   } while (0)
+#define FBX_SKIP(bit) (P.dbg & (bit))
 #else
 #define FBX_MARK(n) do {} while (0)
+#define FBX_SKIP(bit) false
 #endif
 
 __device__ __forceinline__ uint64_t mix64(uint64_t x) {
@@ -72,7 +88,7 @@ __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 
 // Views of the LDS sections of one workgroup.
 struct Sh {
-  uint64_t* off;    // [T + 1] record offsets of the tile
+  uint64_t* off;    // [2][T + 1] record offsets of this tile and of the next one
   uint32_t* rs;     // [T] LDS position of the first byte of a staged record
   uint32_t* re;     // [T] LDS position one past its last byte (newline dropped)
   uint16_t* rows;   // [T][row_stride]: row[0] = rs - 1, row[1 + k] = end of field k
@@ -82,6 +98,9 @@ struct Sh {
   uint32_t* start;  // [n_ragged][T] their first position, relative to the tile's base
   uint32_t* run;    // [n_ragged] signs of the tile's earlier passes
   uint64_t* base;   // [n_ragged] the tile's base in the operator's values array
+  uint32_t* tot;    // [n_ragged] signs of this pass
+  uint32_t* ioff;   // [n_mh + 1] first item of every multi-valued hash among the pass's items
+  uint16_t* ctab;   // [n_mh][T][item_cap] comma positions of the multi-valued hash fields
   // plan tables, copied once per workgroup so that no lane waits on memory for a descriptor
   const OpProg* prog;          // [n_ops]
   const uint32_t* lists;       // work lists (operator indices)
@@ -102,6 +121,9 @@ __device__ __forceinline__ Sh views(const TileParams& P) {
   s.start = reinterpret_cast<uint32_t*>(smem + P.o_start);
   s.run = reinterpret_cast<uint32_t*>(smem + P.o_run);
   s.base = reinterpret_cast<uint64_t*>(smem + P.o_base);
+  s.tot = reinterpret_cast<uint32_t*>(smem + P.o_tot);
+  s.ioff = reinterpret_cast<uint32_t*>(smem + P.o_ioff);
+  s.ctab = reinterpret_cast<uint16_t*>(smem + P.o_ctab);
   s.prog = reinterpret_cast<const OpProg*>(smem + P.o_prog);
   s.lists = reinterpret_cast<const uint32_t*>(smem + P.o_lists);
   s.list_begin = reinterpret_cast<const uint32_t*>(smem + P.o_lbeg);
@@ -113,6 +135,7 @@ __device__ __forceinline__ Sh views(const TileParams& P) {
 // ------------------------------------------------------------ byte sources
 // Where a lane reads record bytes from.  Positions are 32-bit.
 struct LdsSrc {
+  static constexpr bool kTable = true;  // positions fit the 16-bit comma table
   const uint8_t* raw8;
   const uint16_t* rows;
   uint32_t stride;
@@ -128,7 +151,8 @@ struct LdsSrc {
 
 // One record read in place (it does not fit the LDS section); positions count from its first byte.
 struct GlobalSrc {
-  const uint8_t* rec;
+  static constexpr bool kTable = false;
+  const FBX_GLOBAL uint8_t* rec;
   uint32_t len;  // newline dropped
   __device__ __forceinline__ uint32_t byte(uint32_t p) const { return rec[p]; }
   __device__ __forceinline__ void span(uint32_t, uint32_t k, uint32_t& s, uint32_t& e) const {
@@ -152,10 +176,11 @@ __device__ __forceinline__ uint32_t tab_flags(uint32_t w) {
 }
 
 // Field table of the staged records.  kTileThreads / T lanes (at most 64) share a
-// record: each takes an equal run of its dwords, counts its tabs, a prefix sum
-// over the group turns the counts into field numbers, and a second walk writes
-// the positions.  Entries from the record's tab count on hold the record's end.
-__device__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
+// record: each takes an equal run of its 16-byte chunks, counts its tabs, a
+// prefix sum over the group turns the counts into field numbers, and a second
+// walk writes the positions.  Entries from the record's tab count on hold the
+// record's end.
+__device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
   const uint32_t tid = threadIdx.x;
   constexpr uint32_t kLogThreads = kTileThreads == 1024 ? 10u : (kTileThreads == 512 ? 9u : 8u);
   const uint32_t lg = kLogThreads - P.log2T < 6u ? kLogThreads - P.log2T : 6u;  // log2 of the lanes per record
@@ -166,20 +191,33 @@ __device__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
   const bool act = r < nb;
   uint32_t rs = 0, re = 0;
   if (act) { rs = sh.rs[r]; re = sh.re[r]; }
-  const uint32_t ab = rs & ~3u;
-  const uint32_t nd = (act && re > rs) ? (re - ab + 3u) >> 2 : 0u;  // dwords that cover the record
-  const uint32_t c = (nd + gsz - 1u) >> lg;                         // dwords per lane
-  const uint32_t d0 = min(j * c, nd), d1 = min(d0 + c, nd);
-  const uint32_t* raw32 = reinterpret_cast<const uint32_t*>(sh.raw);
-  auto flags_at = [&](uint32_t d) {
-    uint32_t f = tab_flags(raw32[(ab >> 2) + d]);
-    if (d == 0) f &= 0xffffffffu << ((rs & 3u) * 8u);  // bytes before the record
-    const uint32_t rem = re - (ab + 4u * d);           // bytes of the record from this dword on (>= 1)
-    if (rem < 4u) f &= (1u << (rem * 8u)) - 1u;        // bytes after the record
-    return f;
+  const uint32_t ab = rs & ~15u;
+  const uint32_t nc = (act && re > rs) ? (re - ab + 15u) >> 4 : 0u;  // 16-byte chunks that cover the record
+  const uint32_t c = (nc + gsz - 1u) >> lg;                          // chunks per lane
+  const uint32_t c0 = min(j * c, nc), c1 = min(c0 + c, nc);
+  // tab flags of the four dwords of chunk ci, bytes outside the record masked off
+  auto chunk_flags = [&](uint32_t ci, uint32_t (&f)[4]) {
+    const uint32_t cp = ab + 16u * ci;
+    const u32x4 w = *reinterpret_cast<const u32x4*>(sh.raw + cp);
+    f[0] = tab_flags(w.x); f[1] = tab_flags(w.y); f[2] = tab_flags(w.z); f[3] = tab_flags(w.w);
+    if (cp < rs || cp + 16u > re) {
+#pragma unroll
+      for (uint32_t i = 0; i < 4; ++i) {
+        const uint32_t pos = cp + 4u * i;
+        const uint32_t lo = rs > pos ? rs - pos : 0u;  // valid bytes of the dword: [lo, hi)
+        const uint32_t hi = re > pos ? re - pos : 0u;
+        uint32_t m = (lo >= 4u || hi == 0u) ? 0u : (0xffffffffu << (8u * lo));
+        if (hi < 4u) m &= (1u << (8u * hi)) - 1u;
+        f[i] &= m;
+      }
+    }
   };
   uint32_t cnt = 0;
-  for (uint32_t d = d0; d < d1; ++d) cnt += __popc(flags_at(d));
+  for (uint32_t ci = c0; ci < c1; ++ci) {
+    uint32_t f[4];
+    chunk_flags(ci, f);
+    cnt += __popc(f[0]) + __popc(f[1]) + __popc(f[2]) + __popc(f[3]);
+  }
   uint32_t incl = cnt;
   for (uint32_t s = 1; s < gsz; s <<= 1) {
     const uint32_t t = __shfl_up(incl, s, 64);
@@ -189,13 +227,23 @@ __device__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
   if (!act) return;
   uint32_t k = incl - cnt;
   uint16_t* row = sh.rows + r * P.row_stride;
-  for (uint32_t d = d0; d < d1; ++d) {
-    uint32_t f = flags_at(d);
-    while (f) {
-      const uint32_t b = (uint32_t)__ffs((int)f) - 1u;  // 7, 15, 23 or 31
-      if (k < F) row[1u + k] = (uint16_t)(ab + 4u * d + (b >> 3));
+  // second walk: from tab to tab.  A window of eight bytes at the current position
+  // (any alignment) shows the next tab, so every lane places one tab per turn.
+  const uint32_t* raw32 = reinterpret_cast<const uint32_t*>(sh.raw);
+  const uint32_t be = min(re, ab + 16u * c1);
+  uint32_t p = max(rs, ab + 16u * c0);
+  while (p < be) {
+    const uint32_t a = p >> 2, sh8 = (p & 3u) * 8u;
+    const uint32_t w0 = raw32[a], w1 = raw32[a + 1], w2 = raw32[a + 2];
+    const uint32_t f0 = tab_flags(__builtin_amdgcn_alignbit(w1, w0, sh8));
+    const uint32_t f1 = tab_flags(__builtin_amdgcn_alignbit(w2, w1, sh8));
+    const uint32_t i0 = ((uint32_t)__ffs((int)f0) - 1u) >> 3, i1 = 4u + (((uint32_t)__ffs((int)f1) - 1u) >> 3);
+    const uint32_t idx = f0 ? i0 : (f1 ? i1 : 8u);
+    p += idx;
+    if (idx < 8u && p < be) {
+      if (k < F) row[1u + k] = (uint16_t)p;
       ++k;
-      f &= f - 1u;
+      ++p;
     }
   }
   if (j == 0) row[0] = (uint16_t)(rs - 1u);
@@ -268,6 +316,25 @@ __device__ __forceinline__ uint32_t count_commas(const GlobalSrc& src, uint32_t 
   uint32_t c = 0;
   for (uint32_t p = s; p < e; ++p) c += src.byte(p) == ',' ? 1u : 0u;
   return c;
+}
+
+// Position of the first comma in [p, e), or e.
+__device__ __forceinline__ uint32_t next_comma(const LdsSrc& src, uint32_t p, uint32_t e) {
+  while (p < e) {
+    uint32_t x0, x1;
+    window8(src, p, x0, x1);
+    const uint32_t f0 = zero_exact(x0 ^ 0x2c2c2c2cu), f1 = zero_exact(x1 ^ 0x2c2c2c2cu);
+    const uint32_t i0 = ((uint32_t)__ffs((int)f0) - 1u) >> 3, i1 = 4u + (((uint32_t)__ffs((int)f1) - 1u) >> 3);
+    const uint32_t idx = f0 ? i0 : (f1 ? i1 : 8u);
+    p += idx;
+    if (idx < 8u) break;
+  }
+  return p < e ? p : e;
+}
+
+__device__ __forceinline__ uint32_t next_comma(const GlobalSrc& src, uint32_t p, uint32_t e) {
+  while (p < e && src.byte(p) != ',') ++p;
+  return p;
 }
 
 struct NumState {
@@ -351,7 +418,7 @@ __device__ __forceinline__ uint32_t ragged_root_count(const Src& src, const OpPr
 // Writes the signs of a ragged root operator (not n-gram) on [s, e) to dst[0 .. count).
 template <class Src>
 __device__ __forceinline__ void ragged_root_emit(const Src& src, const OpProg& d, const uint8_t* aux, uint32_t s,
-                                                 uint32_t e, uint64_t* dst, uint32_t& malformed) {
+                                                 uint32_t e, G64 dst, uint32_t& malformed) {
   const bool multi = d.flags & F_MULTI;
   if (d.kind == OP_HASH) {  // a ragged hash is always multi-valued
     uint64_t h = d.key;
@@ -402,219 +469,529 @@ __device__ __forceinline__ uint32_t group_incl_scan(uint32_t v, uint32_t T) {
   return v;
 }
 
-// Runs every layer on the nb records of one pass.  g_first is the batch-wide
-// index of the pass's first record.  WRITE = false stops after the counts.
-template <bool WRITE, class Src>
-__device__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint32_t nb, uint64_t g_first,
-                         uint32_t& malformed, bool& overflow) {
-  const uint32_t T = 1u << P.log2T, G = 64u >> P.log2T;  // G operators per wavefront at a time
-  const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-  const uint32_t r = lane & (T - 1u), og = lane >> P.log2T;
-  const bool live = r < nb;
-  const uint64_t g = g_first + r;
-  const uint64_t R = P.n_records;
-  constexpr uint32_t kWaves = kTileThreads / 64;
+constexpr uint32_t kWaves = kTileThreads / 64;
 
-  // ---- counts of the ragged operators, then their positions inside the tile
-  if (P.n_ragged) {
-    for (uint32_t list = TL_RAGROOT; list <= TL_NGRAM; ++list) {
-      const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
-      for (uint32_t base = wave * G; base < m; base += kWaves * G) {
-        const uint32_t i = base + og;
-        if (i >= m) continue;
-        const OpProg& d = sh.prog[sh.lists[lb + i]];
-        uint32_t c = 0;
-        if (live) {
-          uint32_t s, e;
-          src.span(r, d.field, s, e);
-          if (d.kind == OP_NGRAM) c = e - s >= d.aux_len ? e - s - d.aux_len + 1u : 0u;
-          else c = ragged_root_count(src, d, sh.aux, s, e);
-        }
-        if (c > kMaxCount) overflow = true;
-        sh.cnt[d.rag_row * T + r] = c;
-      }
-    }
-    __syncthreads();
-    FBX_MARK(4);
-    // later layers: counts follow from the inputs' counts, record by record, in spec order
-    if (P.n_rnr) {
-      if (tid < T) {
-        for (uint32_t k = 0; k < P.n_rnr; ++k) {
-          const OpProg& d = sh.prog[sh.rnr[k]];
-          const OpProg& da = sh.prog[d.a];
-          const OpProg& db = sh.prog[d.b];
-          const uint64_t ca = da.arity ? da.arity : sh.cnt[da.rag_row * T + tid];
-          const uint64_t cb = db.arity ? db.arity : sh.cnt[db.rag_row * T + tid];
-          const uint64_t c = d.kind == OP_CROSS ? ca * cb : ca + cb;
-          if (c > kMaxCount) overflow = true;
-          sh.cnt[d.rag_row * T + tid] = tid < nb ? (uint32_t)c : 0u;
-        }
-      }
-      __syncthreads();
-    }
-    for (uint32_t base = wave * G; base < P.n_ragged; base += kWaves * G) {
-      const uint32_t row = base + og;
-      const bool ok = row < P.n_ragged;
-      const uint32_t v = ok ? sh.cnt[row * T + r] : 0u;
-      const uint32_t incl = group_incl_scan(v, T);
-      if (ok) {
-        const uint32_t before = sh.run[row];
-        sh.start[row * T + r] = before + incl - v;
-        if (r == T - 1u) sh.run[row] = before + incl;
-      }
-    }
-    __syncthreads();
-    FBX_MARK(5);
+// Work counters of a pass (cleared between passes): s_ctr[0] hands out the
+// single-valued hash / bucket units of layer 1, which fill every phase that has
+// idle wavefronts; s_ctr[1] the counting units, s_ctr[2] the derivation,
+// s_ctr[3] the ragged root units, s_ctr[4 + (l & 1)] the units of layer l.
+// s_ctr[6] the placement unit.  s_done[0..2]: finished units of the counting, the
+// derivation and the placement phase.
+__shared__ uint32_t s_ctr[7];
+__shared__ uint32_t s_done[3];
+__shared__ uint32_t s_good;   // MODE 2: the tile's bases are known and inside the arrays
+
+// Next unit of a phase, the same for every lane of the wavefront.
+__device__ __forceinline__ uint32_t grab_unit(uint32_t* ctr) {
+  uint32_t u = 0;
+  if (lane_id() == 0) u = atomicAdd(ctr, 1u);
+  return __builtin_amdgcn_readfirstlane(u);
+}
+
+template <class Src>
+struct Pass {
+  const TileParams& P;
+  const Sh& sh;
+  const Src& src;
+  uint32_t nb;        // records of this pass
+  uint64_t g_first;   // batch-wide index of its first record
+  uint32_t T, G;      // records per tile; operators a wavefront runs side by side
+  uint32_t r, og;     // this lane's record and operator slot
+  bool live;
+  uint64_t g;
+  uint32_t& malformed;
+  bool& overflow;
+
+  __device__ __forceinline__ uint32_t units_of(uint32_t list) const {
+    return (sh.list_begin[list + 1] - sh.list_begin[list] + G - 1u) / G;
   }
-  if (!WRITE) return;
+  // the operator of this lane in unit u of a list, or null
+  __device__ __forceinline__ const OpProg* op_of(uint32_t list, uint32_t u) const {
+    const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
+    const uint32_t i = u * G + og;
+    return i < m ? &sh.prog[sh.lists[lb + i]] : nullptr;
+  }
+
+  // ---- counts of the ragged root operators (lists TL_RAGROOT, TL_NGRAM, taken as one)
+  __device__ __forceinline__ uint32_t count_units() const { return units_of(TL_RAGROOT) + units_of(TL_NGRAM); }
+  __device__ __forceinline__ void count_unit(uint32_t u) {
+    const uint32_t ur = units_of(TL_RAGROOT);
+    const OpProg* d = u < ur ? op_of(TL_RAGROOT, u) : op_of(TL_NGRAM, u - ur);
+    if (!d) return;
+    uint32_t c = 0;
+    if (live) {
+      uint32_t s, e;
+      src.span(r, d->field, s, e);
+      if (d->kind == OP_NGRAM) {
+        c = e - s >= d->aux_len ? e - s - d->aux_len + 1u : 0u;
+      } else if (d->kind == OP_HASH) {
+        // multi-valued hash: from comma to comma; the first item_cap positions are kept for the item lanes
+        const uint32_t i = u * G + og;  // hashes lead the ragged root list
+        uint16_t* tab = sh.ctab + (i * T + r) * P.item_cap;
+        uint32_t p = s;
+        for (;;) {
+          p = next_comma(src, p, e);
+          if (p >= e) break;
+          if (Src::kTable && c < P.item_cap) tab[c] = (uint16_t)p;
+          ++c;
+          ++p;
+        }
+        ++c;  // items = commas + 1
+      } else {
+        c = ragged_root_count(src, *d, sh.aux, s, e);
+      }
+    }
+    if (c > kMaxCount) overflow = true;
+    sh.cnt[d->rag_row * T + r] = c;
+  }
+
+  // Counts of the later layers follow from the inputs' counts, record by record,
+  // in spec order.  One wavefront does it (its LDS traffic stays in order).
+  __device__ __forceinline__ void derive() {
+    const uint32_t lane = lane_id();
+    if (lane < T) {
+      for (uint32_t k = 0; k < P.n_rnr; ++k) {
+        const OpProg& d = sh.prog[sh.rnr[k]];
+        const OpProg& da = sh.prog[d.a];
+        const OpProg& db = sh.prog[d.b];
+        const uint64_t ca = da.arity ? da.arity : sh.cnt[da.rag_row * T + lane];
+        const uint64_t cb = db.arity ? db.arity : sh.cnt[db.rag_row * T + lane];
+        const uint64_t c = d.kind == OP_CROSS ? ca * cb : ca + cb;
+        if (c > kMaxCount) overflow = true;
+        sh.cnt[d.rag_row * T + lane] = lane < nb ? (uint32_t)c : 0u;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      }
+    }
+  }
+  // Counts become positions inside the tile: a prefix sum over the records of G rows at a time.
+  __device__ __forceinline__ uint32_t scan_units() const { return (P.n_ragged + G - 1u) / G; }
+  __device__ __forceinline__ void scan_unit(uint32_t u) {
+    const uint32_t row = u * G + og;
+    const bool ok = row < P.n_ragged;
+    const uint32_t v = ok ? sh.cnt[row * T + r] : 0u;
+    const uint32_t incl = group_incl_scan(v, T);
+    if (ok) {
+      const uint32_t before = sh.run[row];
+      sh.start[row * T + r] = before + incl - v;
+      if (r == T - 1u) { sh.run[row] = before + incl; sh.tot[row] = incl; }
+    }
+  }
 
   // ---- layer 1
-  // single-valued hashes and buckets: one sign per record
-  for (uint32_t list = TL_HASH1; list <= TL_BUCKET1; ++list) {
-    const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
-    for (uint32_t base = wave * G; base < m; base += kWaves * G) {
-      const uint32_t i = base + og;
-      if (i >= m || !live) continue;
-      const OpProg& d = sh.prog[sh.lists[lb + i]];
-      uint32_t s, e;
-      src.span(r, d.field, s, e);
-      const uint64_t v = single_sign(src, d, sh.aux, s, e, malformed);
-      reinterpret_cast<uint64_t*>(d.values)[g] = v;
-      if (d.stage != kNoRow) sh.stage[d.stage * T + r] = v;
+  __device__ __forceinline__ void hash1_unit(uint32_t u) {
+    const OpProg* d = op_of(TL_HASH1, u);
+    if (!d || !live) return;
+    uint32_t s, e;
+    src.span(r, d->field, s, e);
+    const uint64_t v = hash_span(src, s, e, d->key);
+    gptr<uint64_t>(d->values)[g] = v;
+    if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
+  }
+  __device__ __forceinline__ void bucket1_unit(uint32_t u) {
+    const OpProg* d = op_of(TL_BUCKET1, u);
+    if (!d || !live) return;
+    uint32_t s, e;
+    src.span(r, d->field, s, e);
+    NumState ns;
+    for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
+    const uint64_t v = bucket_sign(*d, sh.aux, ns, malformed);
+    gptr<uint64_t>(d->values)[g] = v;
+    if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
+  }
+  // where this lane's list of a ragged operator starts; writes its offsets entry
+  __device__ __forceinline__ uint64_t place(const OpProg& d, uint32_t rr, uint64_t gg) const {
+    const uint64_t first = sh.base[d.rag_row] + sh.start[d.rag_row * T + rr];
+    if (d.flags & F_EMIT) {
+      G64 off = gptr<uint64_t>(d.offsets);
+      off[gg] = first;
+      if (gg + 1 == P.n_records) off[gg + 1] = first + sh.cnt[d.rag_row * T + rr];
+    }
+    return first;
+  }
+  // the other ragged root operators (filters, multi-valued buckets): a lane writes its record's list
+  __device__ __forceinline__ uint32_t other_units() const {
+    return (sh.list_begin[TL_RAGROOT + 1] - sh.list_begin[TL_RAGROOT] - P.n_mh + G - 1u) / G;
+  }
+  __device__ __forceinline__ void other_unit(uint32_t u) {
+    const uint32_t lb = sh.list_begin[TL_RAGROOT] + P.n_mh, m = sh.list_begin[TL_RAGROOT + 1] - lb;
+    const uint32_t i = u * G + og;
+    const OpProg* d = i < m ? &sh.prog[sh.lists[lb + i]] : nullptr;
+    if (!d || !live) return;
+    const uint64_t first = place(*d, r, g);
+    uint32_t s, e;
+    src.span(r, d->field, s, e);
+    ragged_root_emit(src, *d, sh.aux, s, e, gptr<uint64_t>(d->values) + first, malformed);
+  }
+  // Multi-valued hashes (the first P.n_mh entries of the ragged root list): lanes
+  // are items.  All items of the pass, operator after operator and record after
+  // record, form one index space; a lane finds its operator and record by two
+  // small searches, its item's bounds in the comma table, and writes the sign to
+  // the item's own position: neighbouring lanes write neighbouring signs.
+  __device__ __forceinline__ void item_offsets() {  // every wavefront, after the positions are known
+    const uint32_t lane = lane_id();
+    uint32_t carry = 0;
+    for (uint32_t i0 = 0; i0 < P.n_mh; i0 += 64u) {
+      const uint32_t i = i0 + lane;
+      uint32_t v = 0;
+      if (i < P.n_mh) v = sh.tot[sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]].rag_row];
+      uint32_t incl = v;
+      for (uint32_t d = 1; d < 64u; d <<= 1) {
+        const uint32_t t = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += t;
+      }
+      if (i < P.n_mh) sh.ioff[i] = carry + incl - v;
+      carry += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) sh.ioff[P.n_mh] = carry;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  }
+  __device__ __forceinline__ uint32_t item_units() const { return (sh.ioff[P.n_mh] + 63u) >> 6; }
+  __device__ __forceinline__ void item_unit(uint32_t u) {
+    const uint32_t q = u * 64u + lane_id();
+    if (q >= sh.ioff[P.n_mh]) return;
+    // operator: the last one whose first item is <= q
+    uint32_t lo = 0, hi = P.n_mh - 1u;
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi + 1u) >> 1;
+      if (sh.ioff[mid] <= q) lo = mid; else hi = mid - 1u;
+    }
+    const uint32_t i = lo;
+    const OpProg& d = sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]];
+    const uint32_t row = d.rag_row;
+    const uint32_t before = sh.run[row] - sh.tot[row];     // signs of the tile's earlier passes
+    const uint32_t pos = before + (q - sh.ioff[i]);         // the item's position inside the tile
+    // record: the last one whose first position is <= pos (every record has at least one item)
+    const uint32_t* st = sh.start + row * T;
+    lo = 0; hi = nb - 1u;
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi + 1u) >> 1;
+      if (st[mid] <= pos) lo = mid; else hi = mid - 1u;
+    }
+    const uint32_t rr = lo, j = pos - st[rr], cnt = sh.cnt[row * T + rr];
+    uint32_t s, e;
+    src.span(rr, d.field, s, e);
+    const uint16_t* tab = sh.ctab + (i * T + rr) * P.item_cap;
+    const uint32_t cap = Src::kTable ? P.item_cap : 0u;
+    uint32_t is, ie;
+    if (j == 0) {
+      is = s;
+    } else if (j <= cap) {
+      is = (uint32_t)tab[j - 1u] + 1u;
+    } else {  // beyond the table: walk on from its last comma
+      is = cap ? (uint32_t)tab[cap - 1u] + 1u : s;
+      for (uint32_t c = cap; c < j; ++c) is = next_comma(src, is, e) + 1u;
+    }
+    if (j + 1u == cnt) ie = e;
+    else if (j < cap) ie = tab[j];
+    else ie = next_comma(src, is, e);
+    const uint64_t first = sh.base[row] + pos;
+    if (j == 0 && (d.flags & F_EMIT)) {
+      G64 off = gptr<uint64_t>(d.offsets);
+      const uint64_t gg = g_first + rr;
+      off[gg] = first;
+      if (gg + 1 == P.n_records) off[gg + 1] = first + cnt;
+    }
+    gptr<uint64_t>(d.values)[first] = hash_span(src, is, ie, d.key);
+  }
+
+  // n-grams: the lanes of a wavefront run over the grams of one record; unit = (operator, record)
+  __device__ __forceinline__ uint32_t ngram_units() const {
+    return (sh.list_begin[TL_NGRAM + 1] - sh.list_begin[TL_NGRAM]) * nb;
+  }
+  __device__ __forceinline__ void ngram_unit(uint32_t u) {
+    const uint32_t lane = lane_id();
+    const OpProg& d = sh.prog[sh.lists[sh.list_begin[TL_NGRAM] + u / nb]];
+    const uint32_t rr = u % nb;
+    uint32_t s, e;
+    src.span(rr, d.field, s, e);
+    const uint32_t ng = sh.cnt[d.rag_row * T + rr], n = d.aux_len;
+    uint64_t first = 0;
+    if (lane == 0) first = place(d, rr, g_first + rr);
+    first = __shfl(first, 0, 64);
+    G64 vals = gptr<uint64_t>(d.values) + first;
+    const uint64_t key = d.key;
+    for (uint32_t q = lane; q < ng; q += 64) vals[q] = hash_span(src, s + q, s + q + n, key);
+  }
+
+  // ---- later layers
+  // crosses of two single signs, both on chip
+  __device__ __forceinline__ void x11_unit(uint32_t layer, uint32_t u) {
+    const OpProg* d = op_of(TL_LAYER + 2u * (layer - 2u), u);
+    if (!d || !live) return;
+    const uint64_t a = sh.stage[d->aux_off * T + r], b = sh.stage[d->aux_len * T + r];
+    const uint64_t v = mix64(mix64(a + d->key) + b);
+    gptr<uint64_t>(d->values)[g] = v;
+    if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
+  }
+  // this lane's list of an earlier operator (in the arrays this workgroup wrote)
+  __device__ __forceinline__ void input_list(const OpProg& d, CG64& ptr, uint32_t& n) const {
+    if (d.arity) {
+      n = d.arity;
+      ptr = gptr<const uint64_t>(d.values) + g * d.arity;
+    } else {
+      n = sh.cnt[d.rag_row * T + r];
+      ptr = gptr<const uint64_t>(d.values) + sh.base[d.rag_row] + sh.start[d.rag_row * T + r];
     }
   }
-  FBX_MARK(6);
-  // ragged root operators other than n-grams: a lane writes its record's list
-  {
-    const uint32_t lb = sh.list_begin[TL_RAGROOT], m = sh.list_begin[TL_RAGROOT + 1] - lb;
-    for (uint32_t base = wave * G; base < m; base += kWaves * G) {
-      const uint32_t i = base + og;
-      if (i >= m || !live) continue;
-      const OpProg& d = sh.prog[sh.lists[lb + i]];
-      const uint64_t first = sh.base[d.rag_row] + sh.start[d.rag_row * T + r];
-      if (d.flags & F_EMIT) {
-        uint64_t* off = reinterpret_cast<uint64_t*>(d.offsets);
-        off[g] = first;
-        if (g + 1 == R) off[R] = first + sh.cnt[d.rag_row * T + r];
+  // every other cross or concat; inputs are read four at a time so that their
+  // loads overlap instead of queueing behind the stores
+  __device__ __forceinline__ void gen_unit(uint32_t layer, uint32_t u) {
+    const OpProg* dp = op_of(TL_LAYER + 2u * (layer - 2u) + 1u, u);
+    if (!dp || !live) return;
+    const OpProg& d = *dp;
+    const OpProg& da = sh.prog[d.a];
+    const OpProg& db = sh.prog[d.b];
+    CG64 pa, pb;
+    uint32_t na, nbv;
+    input_list(da, pa, na);
+    input_list(db, pb, nbv);
+    G64 dst = gptr<uint64_t>(d.values) + (d.arity ? g * d.arity : place(d, r, g));
+    const uint64_t key = d.key;
+    if (d.kind == OP_CROSS) {
+      for (uint32_t x = 0; x < na; ++x) {
+        const uint64_t ma = mix64((da.arity == 1 && da.stage != kNoRow ? sh.stage[da.stage * T + r] : pa[x]) + key);
+        for (uint32_t y0 = 0; y0 < nbv; y0 += 4) {
+          uint64_t bv[4];
+#pragma unroll
+          for (uint32_t t = 0; t < 4; ++t) bv[t] = y0 + t < nbv ? pb[y0 + t] : 0;
+#pragma unroll
+          for (uint32_t t = 0; t < 4; ++t) if (y0 + t < nbv) dst[t] = mix64(ma + bv[t]);
+          dst += min(4u, nbv - y0);
+        }
       }
-      uint32_t s, e;
-      src.span(r, d.field, s, e);
-      ragged_root_emit(src, d, sh.aux, s, e, reinterpret_cast<uint64_t*>(d.values) + first, malformed);
+    } else {
+      for (uint32_t pass = 0; pass < 2; ++pass) {
+        CG64 p = pass ? pb : pa;
+        const uint32_t n = pass ? nbv : na;
+        for (uint32_t y0 = 0; y0 < n; y0 += 4) {
+          uint64_t bv[4];
+#pragma unroll
+          for (uint32_t t = 0; t < 4; ++t) bv[t] = y0 + t < n ? p[y0 + t] : 0;
+#pragma unroll
+          for (uint32_t t = 0; t < 4; ++t) if (y0 + t < n) dst[t] = bv[t];
+          dst += min(4u, n - y0);
+        }
+      }
+    }
+  }
+};
+
+// ---- ordered placement without a counting launch (MODE 2)
+// Every (ragged operator, tile) has one 64-bit word: two flag bits and the number
+// of signs.  A tile first publishes its own count (AGGREGATE), then adds up the
+// words of the tiles before it, newest first, until it meets one that already
+// holds the sum of everything before and including itself (PREFIX), and finally
+// publishes its own such sum.  Tiles are taken off the ticket counter in order,
+// so every word a tile waits for belongs to a tile that is already running; a
+// wait that still exceeds kSpinLimit polls is given up and reported.  ABORT marks
+// a tile that cannot be placed (bad offsets, text larger than the LDS section,
+// capacity exceeded); it spreads to all later tiles, which then write nothing.
+constexpr uint64_t kLbAggregate = 1ull << 62, kLbPrefix = 2ull << 62, kLbAbort = 3ull << 62;
+constexpr uint64_t kLbValue = (1ull << 62) - 1ull;
+constexpr uint32_t kSpinLimit = 1u << 24;
+
+__device__ __forceinline__ void lb_store(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t lb_load(uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Marks the tile as not placeable for every ragged operator.
+__device__ __forceinline__ void lb_abort_tile(const TileParams& P, uint32_t tile) {
+  for (uint32_t row = threadIdx.x; row < P.n_ragged; row += kTileThreads)
+    lb_store(P.lb_state + (uint64_t)row * P.n_tiles + tile, kLbAbort);
+}
+
+// One wavefront, lanes = ragged operators: publishes the tile's counts, finds the
+// tile's bases.  Returns false (in every lane) when the tile must not be written.
+__device__ __forceinline__ bool lb_place_tile(const TileParams& P, const Sh& sh, uint32_t tile) {
+  const uint32_t lane = lane_id();
+  bool good = true;
+  for (uint32_t row0 = 0; row0 < P.n_ragged; row0 += 64u) {
+    const uint32_t row = row0 + lane;
+    const bool ok = row < P.n_ragged;
+    const uint64_t agg = ok ? sh.tot[row] : 0u;
+    uint64_t* st = P.lb_state + (uint64_t)(ok ? row : 0u) * P.n_tiles;
+    uint64_t excl = 0;
+    bool abort = false;
+    if (ok && tile > 0) {
+      lb_store(st + tile, kLbAggregate | agg);
+      uint32_t t = tile - 1u, spins = 0;
+      for (;;) {
+        const uint64_t v = lb_load(st + t);
+        const uint64_t flag = v & ~kLbValue;
+        if (flag == kLbPrefix) { excl += v & kLbValue; break; }
+        if (flag == kLbAbort) { abort = true; break; }
+        if (flag == kLbAggregate) { excl += v & kLbValue; --t; spins = 0; continue; }  // tile 0 never holds this flag
+        if (++spins > kSpinLimit) {
+          atomicOr(&P.ctrl->err, (uint32_t)CE_STALL);
+          abort = true;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+      }
+    }
+    if (ok) {
+      if (!abort && excl + agg > gptr(P.row_cap)[row]) {  // the array was sized too small: nothing may be written
+        atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
+        abort = true;
+      }
+      lb_store(st + tile, abort ? kLbAbort : (kLbPrefix | (excl + agg)));
+      sh.base[row] = excl;
+      if (tile + 1u == P.n_tiles) gptr(P.row_actual)[row] = excl + agg;
+    }
+    if (__any(abort)) good = false;
+  }
+  return good;
+}
+
+// Runs every layer on the nb records of one pass.  WRITE = false stops after the
+// counts.  hook() is called once by every lane after the first barrier (the
+// caller starts the next tile's loads there).
+template <int MODE, class Src, class Hook>
+__device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint32_t nb, uint64_t g_first,
+                                         uint32_t tile, uint32_t& malformed, bool& overflow, Hook&& hook) {
+  constexpr bool WRITE = MODE != 0;
+  const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+  const uint32_t T = 1u << P.log2T;
+  Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow};
+  ps.live = ps.r < nb;
+  ps.g = g_first + ps.r;
+  // the single-valued hashes and buckets of layer 1 fill whatever phase has idle wavefronts
+  const uint32_t uh = WRITE ? ps.units_of(TL_HASH1) : 0u, ub = WRITE ? ps.units_of(TL_BUCKET1) : 0u;
+  auto fill_one = [&]() -> bool {
+    const uint32_t u = grab_unit(&s_ctr[0]);
+    if (u >= uh + ub) return false;
+    if (FBX_SKIP(1u)) return true;
+    if (u < uh) ps.hash1_unit(u); else ps.bucket1_unit(u - uh);
+    return true;
+  };
+
+  // A phase whose few long units would leave most wavefronts idle: wavefronts that
+  // find no unit left hash single-valued fields until the last unit is done.
+  auto critical_phase = [&](uint32_t total, uint32_t* ctr, uint32_t* done, auto&& unit) {
+    for (uint32_t u = grab_unit(ctr); u < total; u = grab_unit(ctr)) {
+      unit(u);
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+      if (lane == 0) atomicAdd(done, 1u);
+    }
+    if (WRITE) {
+      while (*reinterpret_cast<volatile uint32_t*>(done) < total && fill_one()) {}
+    }
+    __syncthreads();
+  };
+
+  // ---- phase A: counts of the ragged root operators
+  if (P.n_ragged) critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], [&](uint32_t u) { ps.count_unit(u); });
+  else __syncthreads();
+  FBX_MARK(4);
+  hook();
+  // ---- phase B: one wavefront derives the counts of later layers
+  if (P.n_rnr) {
+    critical_phase(1u, &s_ctr[2], &s_done[1], [&](uint32_t) { ps.derive(); });
+    FBX_MARK(5);
+  }
+  // ---- phase B2: counts become positions
+  if (P.n_ragged) {
+    const uint32_t us = ps.scan_units();
+    for (uint32_t u = wave; u < us; u += kWaves) ps.scan_unit(u);
+    __syncthreads();
+    FBX_MARK(6);
+  }
+  if (!WRITE) return;
+  // ---- phase B3 (no counting launch): the tile's bases come from the tiles before it
+  if (MODE == 2 && P.n_ragged) {
+    if (__syncthreads_or((int)overflow)) {  // absurd counts: nothing of this tile may be placed
+      lb_abort_tile(P, tile);
+      return;
+    }
+    critical_phase(1u, &s_ctr[6], &s_done[2], [&](uint32_t) {
+      const bool good = lb_place_tile(P, sh, tile);
+      if (lane == 0) s_good = good ? 1u : 0u;
+    });
+    if (!s_good) {  // the call fails or falls back: leave the arrays alone
+      return;
+    }
+  }
+
+  // ---- phase C: ragged root operators first (the long units), then the rest of layer 1
+  if (P.n_ragged) {
+    uint32_t um = 0;
+    if (P.n_mh) { ps.item_offsets(); um = ps.item_units(); }
+    const uint32_t uo = ps.other_units(), un = ps.ngram_units();
+    for (uint32_t u = grab_unit(&s_ctr[3]); u < um + uo + un; u = grab_unit(&s_ctr[3])) {
+      if (FBX_SKIP(4u)) continue;
+      if (u < uo) ps.other_unit(u);
+      else if (u < uo + um) ps.item_unit(u - uo);
+      else ps.ngram_unit(u - uo - um);
     }
   }
   FBX_MARK(7);
-  // n-grams: the lanes of a wavefront run over the grams of one record at a time
-  {
-    const uint32_t lb = sh.list_begin[TL_NGRAM], m = sh.list_begin[TL_NGRAM + 1] - lb;
-    for (uint32_t i = 0; i < m; ++i) {
-      const OpProg& d = sh.prog[sh.lists[lb + i]];
-      const uint32_t n = d.aux_len;
-      uint64_t* vals = reinterpret_cast<uint64_t*>(d.values);
-      for (uint32_t rr = wave; rr < nb; rr += kWaves) {
-        uint32_t s, e;
-        src.span(rr, d.field, s, e);
-        const uint32_t ng = sh.cnt[d.rag_row * T + rr];
-        const uint64_t first = sh.base[d.rag_row] + sh.start[d.rag_row * T + rr];
-        if (lane == 0 && (d.flags & F_EMIT)) {
-          uint64_t* off = reinterpret_cast<uint64_t*>(d.offsets);
-          off[g_first + rr] = first;
-          if (g_first + rr + 1 == R) off[R] = first + ng;
-        }
-        const uint64_t key = d.key;
-        for (uint32_t q = lane; q < ng; q += 64) vals[first + q] = hash_span(src, s + q, s + q + n, key);
-      }
-    }
-  }
-
+  while (fill_one()) {}
   FBX_MARK(8);
-  // ---- later layers
+  // ---- later layers: the single crosses of layer l, then its list crosses / concats
   for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
-    __syncthreads();  // the layer barrier: every sign of the layer before is in place
+    __syncthreads();  // the layer barrier: every sign this layer reads is in place
     FBX_MARK(9);
-    // crosses of two single signs, both on chip
-    {
-      const uint32_t list = TL_LAYER + 2u * (layer - 2u);
-      const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
-      for (uint32_t base = wave * G; base < m; base += kWaves * G) {
-        const uint32_t i = base + og;
-        if (i >= m || !live) continue;
-        const OpProg& d = sh.prog[sh.lists[lb + i]];
-        const uint64_t a = sh.stage[d.aux_off * T + r], b = sh.stage[d.aux_len * T + r];
-        const uint64_t v = mix64(mix64(a + d.key) + b);
-        reinterpret_cast<uint64_t*>(d.values)[g] = v;
-        if (d.stage != kNoRow) sh.stage[d.stage * T + r] = v;
-      }
+    uint32_t* ctr = &s_ctr[4u + (layer & 1u)];
+    if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
+    const uint32_t ux = ps.units_of(TL_LAYER + 2u * (layer - 2u)), ug = ps.units_of(TL_LAYER + 2u * (layer - 2u) + 1u);
+    for (uint32_t u = grab_unit(ctr); u < ug + ux; u = grab_unit(ctr)) {
+      if (FBX_SKIP(2u)) continue;
+      if (u < ug) ps.gen_unit(layer, u);
+      else ps.x11_unit(layer, u - ug);
     }
     FBX_MARK(10);
-    // every other cross or concat: inputs are lists in the arrays this workgroup wrote
-    {
-      const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
-      const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
-      for (uint32_t base = wave * G; base < m; base += kWaves * G) {
-        const uint32_t i = base + og;
-        if (i >= m || !live) continue;
-        const OpProg& d = sh.prog[sh.lists[lb + i]];
-        const OpProg& da = sh.prog[d.a];
-        const OpProg& db = sh.prog[d.b];
-        const uint64_t* pa;
-        const uint64_t* pb;
-        uint32_t na, nbv;
-        if (da.arity) { na = da.arity; pa = reinterpret_cast<const uint64_t*>(da.values) + g * da.arity; }
-        else {
-          na = sh.cnt[da.rag_row * T + r];
-          pa = reinterpret_cast<const uint64_t*>(da.values) + sh.base[da.rag_row] + sh.start[da.rag_row * T + r];
-        }
-        if (db.arity) { nbv = db.arity; pb = reinterpret_cast<const uint64_t*>(db.values) + g * db.arity; }
-        else {
-          nbv = sh.cnt[db.rag_row * T + r];
-          pb = reinterpret_cast<const uint64_t*>(db.values) + sh.base[db.rag_row] + sh.start[db.rag_row * T + r];
-        }
-        uint64_t* dst;
-        if (d.arity) {
-          dst = reinterpret_cast<uint64_t*>(d.values) + g * d.arity;
-        } else {
-          const uint64_t first = sh.base[d.rag_row] + sh.start[d.rag_row * T + r];
-          dst = reinterpret_cast<uint64_t*>(d.values) + first;
-          if (d.flags & F_EMIT) {
-            uint64_t* off = reinterpret_cast<uint64_t*>(d.offsets);
-            off[g] = first;
-            if (g + 1 == R) off[R] = first + sh.cnt[d.rag_row * T + r];
-          }
-        }
-        if (d.kind == OP_CROSS) {
-          for (uint32_t x = 0; x < na; ++x) {
-            const uint64_t ma = mix64(pa[x] + d.key);
-            for (uint32_t y = 0; y < nbv; ++y) *dst++ = mix64(ma + pb[y]);
-          }
-        } else {
-          for (uint32_t x = 0; x < na; ++x) *dst++ = pa[x];
-          for (uint32_t y = 0; y < nbv; ++y) *dst++ = pb[y];
-        }
-      }
-    }
-    FBX_MARK(11);
   }
 }
 
 // ------------------------------------------------------------------- kernel
 // Copies n bytes (a multiple of 4) from memory into LDS, all lanes taking part.
 __device__ __forceinline__ void copy_table(uint8_t* dst, const void* src, uint32_t n) {
-  const uint32_t* s32 = reinterpret_cast<const uint32_t*>(src);
+  const FBX_GLOBAL uint32_t* s32 = gptr(reinterpret_cast<const uint32_t*>(src));
   uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
   for (uint32_t i = threadIdx.x; i < (n >> 2); i += kTileThreads) d32[i] = s32[i];
 }
 
+// Sixteen raw bytes at address ca; what lies outside the caller's buffer reads as zero.
+__device__ __forceinline__ u32x4 load_chunk(uintptr_t ca, uintptr_t ok_lo, uintptr_t ok_hi) {
+  u32x4 v;
+  if (ca >= ok_lo && ca + 16u <= ok_hi) {
+    v = *gptr<const u32x4>((uint64_t)ca);
+  } else {  // the chunk straddles an end of the buffer: take what exists byte by byte
+    uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+    for (uint32_t i = 0; i < 16; ++i) {
+      const uintptr_t bi = ca + i;
+      uint32_t b = 0;
+      if (bi >= ok_lo && bi < ok_hi) b = (uint32_t)*gptr<const uint8_t>((uint64_t)bi) << (8u * (i & 3u));
+      const uint32_t q = i >> 2;
+      w0 |= q == 0 ? b : 0u; w1 |= q == 1 ? b : 0u; w2 |= q == 2 ? b : 0u; w3 |= q == 3 ? b : 0u;
+    }
+    v.x = w0; v.y = w1; v.z = w2; v.w = w3;
+  }
+  return v;
+}
+
+constexpr uint32_t kPre = 4;  // 16-byte chunks a lane may hold for the next tile (larger tiles load when their turn comes)
+
 // Workgroups are persistent: each copies the plan tables into LDS once and then
 // takes tiles off a shared counter, in increasing order, until none is left.
-template <bool WRITE>
-__global__ __launch_bounds__(kTileThreads) void k_tile(TileParams P) {
-  __shared__ uint32_t s_err;
-  __shared__ uint32_t s_len;
-  __shared__ uint32_t s_tile;
+template <int MODE>
+__global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
+  constexpr bool WRITE = MODE != 0;
+  __shared__ uint32_t s_err, s_len, s_cur, s_nxt;
   const Sh sh = views(P);
   const uint32_t tid = threadIdx.x;
   const uint32_t T = 1u << P.log2T;
-  if (tid == 0) s_err = P.ctrl->err;  // set by an earlier kernel of this call: nothing may be written
+  const FBX_GLOBAL uint64_t* rec_off = gptr(P.rec_off);
+  uint32_t* ticket = &P.ctrl->ticket[WRITE ? 1 : 0];  // (MODE 2 needs the order the counter gives: see lb_place_tile)
+  const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(P.raw), ok_hi = ok_lo + P.raw_len;
+  if (tid == 0) {
+    s_err = P.ctrl->err;  // set by an earlier kernel of this call: nothing may be written
+    s_cur = atomicAdd(ticket, 1u);
+    s_nxt = atomicAdd(ticket, 1u);
+  }
   copy_table(smem + P.o_prog, P.prog, P.n_ops * (uint32_t)sizeof(OpProg));
   copy_table(smem + P.o_lists, P.lists, P.n_ops * 4u);
   copy_table(smem + P.o_lbeg, P.list_begin, (P.n_lists + 1u) * 4u);
@@ -626,72 +1003,121 @@ __global__ __launch_bounds__(kTileThreads) void k_tile(TileParams P) {
 #endif
   __syncthreads();
   if (s_err) return;
+  // the first tile's offsets arrive the plain way
+  uint32_t par = 0;
+  if (s_cur < P.n_tiles) {
+    const uint64_t g0 = (uint64_t)s_cur << P.log2T;
+    const uint32_t nrec = (uint32_t)min((uint64_t)T, P.n_records - g0);
+    if (tid <= nrec) sh.off[tid] = rec_off[g0 + tid];
+  }
+  __syncthreads();
   FBX_MARK(0);
 
   uint32_t malformed = 0;
   bool overflow = false;
+  u32x4 pre[kPre];      // the next tile's raw text on its way (this lane's chunks)
+  bool have_pre = false;
   for (;;) {
-    if (tid == 0) s_tile = atomicAdd(&P.ctrl->ticket[WRITE ? 1 : 0], 1u);
-    __syncthreads();
-    const uint32_t tile = s_tile;
+    const uint32_t tile = s_cur, nxt = s_nxt;
     if (tile >= P.n_tiles) break;
+    uint32_t after_next = 0;
+    if (tid == 0) after_next = atomicAdd(ticket, 1u);  // used at the end of this turn
+    uint64_t* off = sh.off + par * (T + 1u);
+    uint64_t* off2 = sh.off + (par ^ 1u) * (T + 1u);
     const uint64_t g0 = (uint64_t)tile << P.log2T;
     const uint32_t nrec = (uint32_t)min((uint64_t)T, P.n_records - g0);
-    if (tid <= nrec) sh.off[tid] = P.rec_off[g0 + tid];
+    // the next tile's offsets: requested now, parked in LDS after the next barrier
+    uint32_t nrec2 = 0;
+    uint64_t off_next = 0;
+    if (nxt < P.n_tiles) {
+      const uint64_t g1 = (uint64_t)nxt << P.log2T;
+      nrec2 = (uint32_t)min((uint64_t)T, P.n_records - g1);
+      if (tid <= nrec2) off_next = rec_off[g1 + tid];
+    }
     for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads) {
       sh.run[row] = 0;
-      if (WRITE) sh.base[row] = P.tile_base[(uint64_t)row * P.n_tiles + tile];
+      if (MODE == 1) sh.base[row] = gptr(P.tile_base)[(uint64_t)row * P.n_tiles + tile];
     }
-    __syncthreads();
+    if (tid < 7) s_ctr[tid] = 0;
+    if (tid >= 8 && tid < 11) s_done[tid - 8] = 0;
+    bool nrec_ok = true;
     uint32_t bad = 0;
     if (tid < nrec) {
-      const uint64_t a = sh.off[tid], b = sh.off[tid + 1];
+      const uint64_t a = off[tid], b = off[tid + 1];
       if (a > b || b > P.raw_len) bad = CE_OFFSETS;
       else if (b - a >= (1ull << 31)) bad = CE_TILE;
     }
     if (__syncthreads_or((int)bad)) {
       if (bad) atomicOr(&P.ctrl->err, bad);
-      break;  // the call fails: no point in working off the other tiles
+      if (MODE != 2) break;  // the call fails: no point in working off the other tiles
+      // without a counting launch later tiles wait for this one: tell them, then go on
+      lb_abort_tile(P, tile);
+      nrec_ok = false;
     }
     FBX_MARK(1);
 
-    uint32_t r0 = 0;
+    bool first_pass = true;
+    bool next_pre = false;
+    // Called by every lane after the first barrier of the tile's first pass: the next
+    // tile's offsets are in LDS by then, so its text can be requested.  Only the two
+    // outer offsets decide what is read; the tile itself is checked when its turn comes.
+    auto start_next_tile = [&]() {
+      if (!first_pass || nxt >= P.n_tiles) return;
+      const uint64_t lo = off2[0], hi = off2[nrec2];
+      const uintptr_t addr = ok_lo + lo;
+      const uint32_t delta = (uint32_t)(addr & 15u);
+      if (lo <= hi && hi <= P.raw_len && hi - lo + delta <= (uint64_t)min(P.raw_cap, kPre * kTileThreads * 16u)) {
+        const uint32_t nchunks = (delta + (uint32_t)(hi - lo) + 15u) >> 4;
+        const uintptr_t a0 = addr - delta;
+#pragma unroll
+        for (uint32_t k = 0; k < kPre; ++k) {
+          const uint32_t c = tid + k * kTileThreads;
+          if (c < nchunks) pre[k] = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
+        }
+        next_pre = true;
+      }
+    };
+
+    uint32_t r0 = nrec_ok ? 0u : nrec;
+    if (MODE == 2 && nrec_ok) {
+      // placement needs the whole tile's counts at once: a tile that takes several passes
+      // (or holds a record that is read in place) sends the call back to the counting launch
+      const uint32_t d0 = (uint32_t)((ok_lo + off[0]) & 15u);
+      if (off[nrec] - off[0] + d0 > (uint64_t)P.raw_cap) {
+        if (tid == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
+        lb_abort_tile(P, tile);
+        r0 = nrec;
+      }
+    }
+    if (r0 >= nrec && tid <= nrec2) off2[tid] = off_next;  // (a tile that is left out still hands on the next one's offsets)
     while (r0 < nrec) {  // one turn per pass; all conditions are uniform over the workgroup
-      const uint64_t o0 = sh.off[r0];
-      const uintptr_t addr0 = reinterpret_cast<uintptr_t>(P.raw) + o0;
+      const uint64_t o0 = off[r0];
+      const uintptr_t addr0 = ok_lo + o0;
       const uint32_t delta = (uint32_t)(addr0 & 15u);
       // the pass takes records r0 .. r1-1: as many as fit the LDS section
       uint32_t lo = r0, hi = nrec;
       while (lo < hi) {
         const uint32_t mid = (lo + hi + 1u) >> 1;
-        if (sh.off[mid] - o0 + delta <= (uint64_t)P.raw_cap) lo = mid; else hi = mid - 1u;
+        if (off[mid] - o0 + delta <= (uint64_t)P.raw_cap) lo = mid; else hi = mid - 1u;
       }
       const uint32_t r1 = lo;
       if (r1 > r0) {
         const uint32_t nb = r1 - r0;
-        const uint32_t nbytes = delta + (uint32_t)(sh.off[r1] - o0);
-        const uint32_t nchunks = (nbytes + 15u) >> 4;
-        const uintptr_t a0 = addr0 - delta;
-        const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(P.raw), ok_hi = ok_lo + P.raw_len;
-        for (uint32_t c = tid; c < nchunks; c += kTileThreads) {
-          const uintptr_t ca = a0 + 16u * c;
-          u32x4 v;
-          if (ca >= ok_lo && ca + 16u <= ok_hi) {
-            v = *reinterpret_cast<const u32x4*>(ca);
-          } else {  // the chunk straddles an end of the caller's buffer: take what exists byte by byte
-            uint32_t w[4] = {0, 0, 0, 0};
-            for (uint32_t i = 0; i < 16; ++i) {
-              const uintptr_t bi = ca + i;
-              if (bi >= ok_lo && bi < ok_hi)
-                w[i >> 2] |= (uint32_t)*reinterpret_cast<const uint8_t*>(bi) << (8u * (i & 3u));
-            }
-            v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
+        const uint32_t nchunks = (delta + (uint32_t)(off[r1] - o0) + 15u) >> 4;
+        if (first_pass && have_pre) {  // the whole tile was requested a turn ago
+#pragma unroll
+          for (uint32_t k = 0; k < kPre; ++k) {
+            const uint32_t c = tid + k * kTileThreads;
+            if (c < nchunks) *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = pre[k];
           }
-          *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = v;
+        } else {
+          const uintptr_t a0 = addr0 - delta;
+          for (uint32_t c = tid; c < nchunks; c += kTileThreads)
+            *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
         }
         if (tid < nb) {
-          sh.rs[tid] = kRawPad + delta + (uint32_t)(sh.off[r0 + tid] - o0);
-          sh.re[tid] = kRawPad + delta + (uint32_t)(sh.off[r0 + tid + 1] - o0);
+          sh.rs[tid] = kRawPad + delta + (uint32_t)(off[r0 + tid] - o0);
+          sh.re[tid] = kRawPad + delta + (uint32_t)(off[r0 + tid + 1] - o0);
         }
         __syncthreads();
         // one trailing newline is not part of the record
@@ -699,35 +1125,44 @@ __global__ __launch_bounds__(kTileThreads) void k_tile(TileParams P) {
           const uint32_t e = sh.re[tid];
           if (e > sh.rs[tid] && sh.raw[e - 1u] == '\n') sh.re[tid] = e - 1u;
         }
+        if (first_pass && tid <= nrec2) off2[tid] = off_next;
         __syncthreads();
         FBX_MARK(2);
-        tokenize(P, sh, nb);
+        if (!FBX_SKIP(8u)) tokenize(P, sh, nb);
         __syncthreads();
         FBX_MARK(3);
         LdsSrc src{sh.raw, sh.rows, P.row_stride};
-        run_pass<WRITE>(P, sh, src, nb, g0 + r0, malformed, overflow);
+        run_pass<MODE>(P, sh, src, nb, g0 + r0, tile, malformed, overflow, start_next_tile);
         r0 = r1;
       } else {
         // record r0 alone exceeds the section: it is read in place
-        const uint64_t len64 = sh.off[r0 + 1] - o0;
+        const uint64_t len64 = off[r0 + 1] - o0;
         if (tid == 0) {
           uint32_t len = (uint32_t)len64;
-          if (len && P.raw[o0 + len - 1u] == '\n') --len;
+          if (len && gptr(P.raw)[o0 + len - 1u] == '\n') --len;
           s_len = len;
         }
+        if (first_pass && tid <= nrec2) off2[tid] = off_next;
         __syncthreads();
-        GlobalSrc src{P.raw + o0, s_len};
-        run_pass<WRITE>(P, sh, src, 1u, g0 + r0, malformed, overflow);
+        GlobalSrc src{gptr(P.raw) + o0, s_len};
+        run_pass<MODE>(P, sh, src, 1u, g0 + r0, tile, malformed, overflow, start_next_tile);
         r0 += 1u;
       }
+      first_pass = false;
       __syncthreads();  // the sections are reused by the next pass
-      FBX_MARK(12);
+      if (tid < 7) s_ctr[tid] = 0;
+      if (tid >= 8 && tid < 11) s_done[tid - 8] = 0;
+      FBX_MARK(11);
     }
     if (!WRITE) {
       for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads)
-        P.tile_cnt[(uint64_t)row * P.n_tiles + tile] = sh.run[row];
+        gptr(P.tile_cnt)[(uint64_t)row * P.n_tiles + tile] = sh.run[row];
     }
-    __syncthreads();  // s_tile and the tile's sections are rewritten next
+    have_pre = next_pre;
+    par ^= 1u;
+    if (tid == 0) { s_cur = nxt; s_nxt = after_next; }
+    __syncthreads();
+    FBX_MARK(12);
   }
 
 #ifdef FBX_TILE_PROF
@@ -737,6 +1172,7 @@ __global__ __launch_bounds__(kTileThreads) void k_tile(TileParams P) {
   if (!WRITE) {
     if (overflow) atomicOr(&P.ctrl->err, (uint32_t)CE_OVERFLOW);
   } else {
+    if (MODE == 2 && overflow) atomicOr(&P.ctrl->err, (uint32_t)CE_OVERFLOW);
     for (int d = 32; d >= 1; d >>= 1) malformed += __shfl_xor(malformed, d, 64);
     if (lane_id() == 0 && malformed)
       atomicAdd(reinterpret_cast<unsigned long long*>(&P.ctrl->n_malformed), (unsigned long long)malformed);
@@ -759,16 +1195,18 @@ uint32_t tile_max_lds() {
   return cached;
 }
 
-hipError_t launch_tile(const TileParams& P, int write, hipStream_t st) {
+hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st) {
   if (P.n_tiles == 0) return hipSuccess;
-  const void* fn = write ? reinterpret_cast<const void*>(&k_tile<true>) : reinterpret_cast<const void*>(&k_tile<false>);
+  const void* fn = mode == 0 ? reinterpret_cast<const void*>(&k_tile<0>)
+                             : (mode == 1 ? reinterpret_cast<const void*>(&k_tile<1>) : reinterpret_cast<const void*>(&k_tile<2>));
   if (P.lds_bytes > 48u * 1024u) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds_bytes);
     if (e != hipSuccess) return e;
   }
   const uint32_t grid = std::min(P.n_tiles, P.grid);
-  if (write) hipLaunchKernelGGL(k_tile<true>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
-  else hipLaunchKernelGGL(k_tile<false>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
+  if (mode == 0) hipLaunchKernelGGL(k_tile<0>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
+  else if (mode == 1) hipLaunchKernelGGL(k_tile<1>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
+  else hipLaunchKernelGGL(k_tile<2>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
   return hipGetLastError();
 }
 

@@ -171,6 +171,61 @@ def test_repeated_calls_are_bit_identical_and_plan_is_reusable():
     plan.close()
 
 
+def test_one_launch_mode_matches_and_falls_back():
+    # The second call on a plan sizes its ragged arrays from the first one and skips the
+    # counting launch (bases by look-back between tiles); results must not change.  A batch
+    # whose lists outgrow those arrays, or whose tiles need several passes, goes back to the
+    # counting launch on its own.
+    from gpu_harness import expand
+    for cfg, n in ((5, 3000), (2, 400), (4, 900), (3, 2000)):
+        w = W.get(cfg, n)
+        raw, off = w.generate()
+        want = O.extract(w.spec, raw, off)
+        plan = B.Plan(w.spec)
+        d_raw, d_off = to_device(raw, off)
+        res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.2)
+        assert res.tile_launches == (2 if any(s.offsets is not None for s in res.slots.values()) else 1)
+        for _ in range(3):
+            res = plan.extract(d_raw, d_off)
+            assert res.tile_launches == 1, w.name
+            assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, w.name)
+        # another batch of the same kind but a different size
+        raw2, off2 = w.generate(rec_begin=10000, n_records=n // 3)
+        d_raw2, d_off2 = to_device(raw2, off2)
+        res2 = plan.extract(d_raw2, d_off2)
+        assert res2.tile_launches == 1, w.name
+        assert_same({s: expand(res2.slots[s], n // 3) for s in res2.slot_ids}, res2, O.extract(w.spec, raw2, off2), w.name)
+        plan.close()
+    # lists that grow tenfold between calls: the arrays sized from the first call are too small
+    spec = ("fbx 1\nfields 2\n"
+            "op a hash slot=0 seed=1 emit=1 field=0 multi=1\n"
+            "op b hash slot=1 seed=2 emit=1 field=1 multi=0\n"
+            "op c cross slot=2 seed=3 emit=1 a=a b=b\n")
+    short = [b"x\ty\n"] * 5000
+    long_ = [b"a,b,c,d,e,f,g,h,i,j,k,l\tz\n"] * 5000
+    plan = B.Plan(spec)
+    import torch
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    plan.set_workspace(ws)
+    for recs, launches in ((short, 2), (short, 1), (long_, 2), (long_, 1), (short, 1)):
+        raw, off = _cat(recs)
+        d_raw, d_off = to_device(np.frombuffer(raw, np.uint8), off)
+        res = plan.extract(d_raw, d_off)
+        assert res.tile_launches == launches
+        assert_same({s: expand(res.slots[s], len(recs)) for s in res.slot_ids}, res, O.extract(spec, np.frombuffer(raw, np.uint8), off))
+    # bad offsets in one-launch mode are still an error, and the plan keeps working afterwards
+    raw, off = _cat(short)
+    bad = off.copy(); bad[100] = bad[103]
+    d_raw, d_off = to_device(np.frombuffer(raw, np.uint8), bad)
+    with pytest.raises(B.FbxError) as e:
+        plan.extract(d_raw, d_off)
+    assert e.value.status == B.E_INPUT
+    d_raw, d_off = to_device(np.frombuffer(raw, np.uint8), off)
+    res = plan.extract(d_raw, d_off)
+    assert_same({s: expand(res.slots[s], len(short)) for s in res.slot_ids}, res, O.extract(spec, np.frombuffer(raw, np.uint8), off))
+    plan.close()
+
+
 def test_results_do_not_depend_on_op_order_or_launch_mode():
     w = W.get(4, 300)
     raw, off = w.generate()
