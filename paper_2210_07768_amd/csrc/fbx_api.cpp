@@ -2,6 +2,7 @@
 // one extraction call.  See include/fbx.h for the contract of every entry point.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <string>
@@ -43,8 +44,9 @@ struct fbx_plan {
   int profile = 0;
   int tile_log2 = -1;             // -1: chosen per call
   uint32_t raw_cap = 0;           // 0: chosen per call
-  uint32_t lds_budget = 64u * 1024u;
+  uint32_t lds_budget = 80u * 1024u;  // two workgroups per compute unit
   uint32_t dbg = 0;
+  uint32_t grid_limit = 0;
   int one_launch = 1;             // size ragged arrays from the last call and skip the counting launch
 
   // what the last successful call taught about ragged sizes (signs per ragged operator)
@@ -258,6 +260,9 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "one_launch") {
     if (value != 0 && value != 1) { plan->error = "one_launch must be 0 or 1"; return FBX_E_ARG; }
     plan->one_launch = static_cast<int>(value);
+  } else if (k == "grid_limit") {
+    if (value < 0 || value > 65536) { plan->error = "grid_limit must be in 0..65536"; return FBX_E_ARG; }
+    plan->grid_limit = static_cast<uint32_t>(value);
   } else if (k == "debug_skip") {
     plan->dbg = static_cast<uint32_t>(value);
   } else if (k == "profile") {
@@ -411,9 +416,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
 
       Q.n_tiles = g.n_tiles; Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
       Q.lds_bytes = std::max(Q.lds_bytes, plan->lds_pad);
-      // persistent workgroups: as many as the LDS (and 2048 lanes per compute unit) let run at once
-      const uint32_t per_cu = std::max(1u, std::min(2048u / kTileThreads, (160u * 1024u) / std::max(Q.lds_bytes, 1u)));
-      Q.grid = tile_cu_count() * per_cu;
+      Q.grid = plan->grid_limit;  // 0: as many persistent workgroups as run at the same time
       Q.prof = nullptr;
       Q.dbg = plan->dbg;
 #ifdef FBX_TILE_PROF
@@ -516,7 +519,10 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   // Ragged arrays can be sized from what the last call produced (plus a margin): then the
   // counting launch is skipped.  A batch that does not fit its arrays, or a tile that needs
   // several passes, sends the call back to the exact sequence.
-  bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records;
+  // (every tile reads 512 bytes of placement words per ragged operator: only worth it when that is
+  // little next to the tile's own text)
+  bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records &&
+             uint64_t(h.n_ragged) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T;
   if (one) {
     plan->cap_host.resize(h.n_ragged);
     for (uint32_t r = 0; r < h.n_ragged; ++r) {

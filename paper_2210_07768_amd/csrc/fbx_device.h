@@ -60,7 +60,7 @@ struct TileParams {
   uint32_t n_ops, n_layers, n_ragged, n_rnr, n_lists, aux_bytes;
   uint32_t n_mh;        // multi-valued hashes: the first n_mh entries of the ragged root list
   uint32_t n_tiles, n_fields, n_stage;
-  uint32_t grid;        // workgroups to launch (persistent; they share a tile counter)
+  uint32_t grid;        // upper limit of workgroups to launch (0: as many as run at the same time)
   uint32_t log2T;       // records per tile = 1 << log2T (at most 64)
   uint32_t raw_cap;     // bytes of raw text one pass of a workgroup can stage
   uint32_t row_stride;  // u16 entries per record in the field table (n_fields + 1, padded)

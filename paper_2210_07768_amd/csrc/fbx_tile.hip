@@ -488,6 +488,18 @@ __device__ __forceinline__ uint32_t grab_unit(uint32_t* ctr) {
   return __builtin_amdgcn_readfirstlane(u);
 }
 
+// flag bits and helpers of the one-launch placement (see lb_place_row)
+constexpr uint64_t kLbAggregate = 1ull << 62, kLbPrefix = 2ull << 62, kLbAbort = 3ull << 62;
+constexpr uint64_t kLbValue = (1ull << 62) - 1ull;
+constexpr uint32_t kSpinLimit = 1u << 22;
+
+__device__ __forceinline__ void lb_store(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t lb_load(uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <class Src>
 struct Pass {
   const TileParams& P;
@@ -501,6 +513,7 @@ struct Pass {
   uint64_t g;
   uint32_t& malformed;
   bool& overflow;
+  uint32_t lb_tile;   // tile number when counts are to be published (one-launch mode), else kNoRow
 
   __device__ __forceinline__ uint32_t units_of(uint32_t list) const {
     return (sh.list_begin[list + 1] - sh.list_begin[list] + G - 1u) / G;
@@ -573,7 +586,12 @@ struct Pass {
     if (ok) {
       const uint32_t before = sh.run[row];
       sh.start[row * T + r] = before + incl - v;
-      if (r == T - 1u) { sh.run[row] = before + incl; sh.tot[row] = incl; }
+      if (r == T - 1u) {
+        sh.run[row] = before + incl;
+        sh.tot[row] = incl;
+        if (lb_tile != kNoRow)  // one-launch mode: later tiles may need it at once
+          lb_store(P.lb_state + (uint64_t)row * P.n_tiles + lb_tile, kLbAggregate | incl);
+      }
     }
   }
 
@@ -777,25 +795,19 @@ struct Pass {
 };
 
 // ---- ordered placement without a counting launch (MODE 2)
-// Every (ragged operator, tile) has one 64-bit word: two flag bits and the number
-// of signs.  A tile first publishes its own count (AGGREGATE), then adds up the
-// words of the tiles before it, newest first, until it meets one that already
-// holds the sum of everything before and including itself (PREFIX), and finally
-// publishes its own such sum.  Tiles are taken off the ticket counter in order,
-// so every word a tile waits for belongs to a tile that is already running; a
-// wait that still exceeds kSpinLimit polls is given up and reported.  ABORT marks
-// a tile that cannot be placed (bad offsets, text larger than the LDS section,
-// capacity exceeded); it spreads to all later tiles, which then write nothing.
-constexpr uint64_t kLbAggregate = 1ull << 62, kLbPrefix = 2ull << 62, kLbAbort = 3ull << 62;
-constexpr uint64_t kLbValue = (1ull << 62) - 1ull;
-constexpr uint32_t kSpinLimit = 1u << 24;
-
-__device__ __forceinline__ void lb_store(uint64_t* p, uint64_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t lb_load(uint64_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+// Every (ragged operator, tile) has one 64-bit word: two flag bits and a number
+// of signs.  A tile publishes its count (AGGREGATE) as soon as it knows it.  To
+// find its base it then reads the words of the 64 tiles before it at once, one per
+// lane: the nearest word that already holds "signs up to and including this tile"
+// (PREFIX) plus the counts of the tiles in between is the answer; if all 64 are
+// counts the window moves on.  The tile finally publishes its own PREFIX, so the
+// distance to the nearest PREFIX stays a small fraction of the tiles in flight.
+// Workgroups take every W-th tile, so a tile only ever waits for tiles that
+// other running workgroups are counting right now; waits that still exceed
+// kSpinLimit polls are given up and reported.  ABORT marks a tile that cannot be
+// placed (bad offsets, text larger than the LDS section, array capacity
+// exceeded); it spreads to all later tiles, which then write nothing, and the
+// call is repeated with a counting launch.
 
 // Marks the tile as not placeable for every ragged operator.
 __device__ __forceinline__ void lb_abort_tile(const TileParams& P, uint32_t tile) {
@@ -803,47 +815,51 @@ __device__ __forceinline__ void lb_abort_tile(const TileParams& P, uint32_t tile
     lb_store(P.lb_state + (uint64_t)row * P.n_tiles + tile, kLbAbort);
 }
 
-// One wavefront, lanes = ragged operators: publishes the tile's counts, finds the
-// tile's bases.  Returns false (in every lane) when the tile must not be written.
-__device__ __forceinline__ bool lb_place_tile(const TileParams& P, const Sh& sh, uint32_t tile) {
+// One wavefront finds the base of one ragged operator for this tile (whose count is
+// already published).  Returns false (in every lane) when the tile must not be written.
+__device__ __forceinline__ bool lb_place_row(const TileParams& P, const Sh& sh, uint32_t tile, uint32_t row) {
   const uint32_t lane = lane_id();
-  bool good = true;
-  for (uint32_t row0 = 0; row0 < P.n_ragged; row0 += 64u) {
-    const uint32_t row = row0 + lane;
-    const bool ok = row < P.n_ragged;
-    const uint64_t agg = ok ? sh.tot[row] : 0u;
-    uint64_t* st = P.lb_state + (uint64_t)(ok ? row : 0u) * P.n_tiles;
-    uint64_t excl = 0;
-    bool abort = false;
-    if (ok && tile > 0) {
-      lb_store(st + tile, kLbAggregate | agg);
-      uint32_t t = tile - 1u, spins = 0;
-      for (;;) {
-        const uint64_t v = lb_load(st + t);
-        const uint64_t flag = v & ~kLbValue;
-        if (flag == kLbPrefix) { excl += v & kLbValue; break; }
-        if (flag == kLbAbort) { abort = true; break; }
-        if (flag == kLbAggregate) { excl += v & kLbValue; --t; spins = 0; continue; }  // tile 0 never holds this flag
-        if (++spins > kSpinLimit) {
-          atomicOr(&P.ctrl->err, (uint32_t)CE_STALL);
-          abort = true;
-          break;
-        }
-        __builtin_amdgcn_s_sleep(2);
-      }
-    }
-    if (ok) {
-      if (!abort && excl + agg > gptr(P.row_cap)[row]) {  // the array was sized too small: nothing may be written
-        atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
+  uint64_t* st = P.lb_state + (uint64_t)row * P.n_tiles;
+  const uint64_t agg = sh.tot[row];
+  uint64_t excl = 0;
+  bool abort = false;
+  uint32_t upper = tile, spins = 0;  // the window is the 64 tiles below `upper`, lane 0 the nearest
+  for (;;) {
+    const bool inside = upper > lane;  // in front of tile 0 lies a prefix of zero
+    const uint64_t v = inside ? lb_load(st + (upper - 1u - lane)) : kLbPrefix;
+    const uint64_t flag = v & ~kLbValue;
+    const uint64_t stops = __ballot(flag == kLbPrefix || flag == kLbAbort);
+    const uint32_t stop = stops ? (uint32_t)__ffsll((unsigned long long)stops) - 1u : 64u;
+    const uint64_t below = stop == 64u ? ~0ull : ((1ull << stop) - 1ull);
+    if (__ballot(flag == 0ull) & below) {  // a tile in between has not counted yet
+      if (++spins > kSpinLimit) {
+        if (lane == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_STALL);
         abort = true;
+        break;
       }
-      lb_store(st + tile, abort ? kLbAbort : (kLbPrefix | (excl + agg)));
-      sh.base[row] = excl;
-      if (tile + 1u == P.n_tiles) gptr(P.row_actual)[row] = excl + agg;
+      __builtin_amdgcn_s_sleep(4);
+      continue;
     }
-    if (__any(abort)) good = false;
+    uint64_t part = (lane < stop || (lane == stop && flag == kLbPrefix)) ? (v & kLbValue) : 0ull;
+    for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
+    excl += part;
+    if (stop < 64u) {
+      abort = __shfl(flag, (int)stop, 64) == kLbAbort;
+      break;
+    }
+    upper -= 64u;  // all counts: look further back (upper >= 64 here, else lane `upper` had stopped the window)
+    spins = 0;
   }
-  return good;
+  if (!abort && excl + agg > gptr(P.row_cap)[row]) {  // the array was sized too small: nothing may be written
+    if (lane == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
+    abort = true;
+  }
+  if (lane == 0) {
+    lb_store(st + tile, abort ? kLbAbort : (kLbPrefix | (excl + agg)));
+    sh.base[row] = excl;
+    if (tile + 1u == P.n_tiles) gptr(P.row_actual)[row] = excl + agg;
+  }
+  return !abort;
 }
 
 // Runs every layer on the nb records of one pass.  WRITE = false stops after the
@@ -855,7 +871,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   constexpr bool WRITE = MODE != 0;
   const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
   const uint32_t T = 1u << P.log2T;
-  Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow};
+  Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow, MODE == 2 ? tile : kNoRow};
   ps.live = ps.r < nb;
   ps.g = g_first + ps.r;
   // the single-valued hashes and buckets of layer 1 fill whatever phase has idle wavefronts
@@ -892,6 +908,12 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     critical_phase(1u, &s_ctr[2], &s_done[1], [&](uint32_t) { ps.derive(); });
     FBX_MARK(5);
   }
+  if (MODE == 2 && P.n_ragged) {
+    if (__syncthreads_or((int)overflow)) {  // absurd counts: nothing of this tile may be placed
+      lb_abort_tile(P, tile);
+      return;
+    }
+  }
   // ---- phase B2: counts become positions
   if (P.n_ragged) {
     const uint32_t us = ps.scan_units();
@@ -902,13 +924,8 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   if (!WRITE) return;
   // ---- phase B3 (no counting launch): the tile's bases come from the tiles before it
   if (MODE == 2 && P.n_ragged) {
-    if (__syncthreads_or((int)overflow)) {  // absurd counts: nothing of this tile may be placed
-      lb_abort_tile(P, tile);
-      return;
-    }
-    critical_phase(1u, &s_ctr[6], &s_done[2], [&](uint32_t) {
-      const bool good = lb_place_tile(P, sh, tile);
-      if (lane == 0) s_good = good ? 1u : 0u;
+    critical_phase(P.n_ragged, &s_ctr[6], &s_done[2], [&](uint32_t row) {
+      if (!lb_place_row(P, sh, tile, row) && lane == 0) s_good = 0u;
     });
     if (!s_good) {  // the call fails or falls back: leave the arrays alone
       return;
@@ -976,7 +993,7 @@ __device__ __forceinline__ u32x4 load_chunk(uintptr_t ca, uintptr_t ok_lo, uintp
 constexpr uint32_t kPre = 4;  // 16-byte chunks a lane may hold for the next tile (larger tiles load when their turn comes)
 
 // Workgroups are persistent: each copies the plan tables into LDS once and then
-// takes tiles off a shared counter, in increasing order, until none is left.
+// takes every W-th tile until none is left.
 template <int MODE>
 __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   constexpr bool WRITE = MODE != 0;
@@ -987,10 +1004,17 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   const FBX_GLOBAL uint64_t* rec_off = gptr(P.rec_off);
   uint32_t* ticket = &P.ctrl->ticket[WRITE ? 1 : 0];  // (MODE 2 needs the order the counter gives: see lb_place_tile)
   const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(P.raw), ok_hi = ok_lo + P.raw_len;
+  // Workgroups number themselves in the order in which they start running; workgroup s
+  // takes tiles s, s + W, s + 2 W, ... (W = working workgroups of the launch).  Tiles that
+  // are worked on at the same time are then neighbours in the tile order, which is what
+  // the placement of the one-launch mode needs: nobody holds a tile that others wait for
+  // while busy with an earlier one.
+  const uint32_t n_workers = gridDim.x;
   if (tid == 0) {
     s_err = P.ctrl->err;  // set by an earlier kernel of this call: nothing may be written
-    s_cur = atomicAdd(ticket, 1u);
-    s_nxt = atomicAdd(ticket, 1u);
+    const uint32_t slot = atomicAdd(ticket, 1u);
+    s_cur = slot;
+    s_nxt = slot + n_workers;
   }
   copy_table(smem + P.o_prog, P.prog, P.n_ops * (uint32_t)sizeof(OpProg));
   copy_table(smem + P.o_lists, P.lists, P.n_ops * 4u);
@@ -1020,8 +1044,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   for (;;) {
     const uint32_t tile = s_cur, nxt = s_nxt;
     if (tile >= P.n_tiles) break;
-    uint32_t after_next = 0;
-    if (tid == 0) after_next = atomicAdd(ticket, 1u);  // used at the end of this turn
+    const uint32_t after_next = nxt + n_workers;  // (tile numbers past the end just end the loop)
     uint64_t* off = sh.off + par * (T + 1u);
     uint64_t* off2 = sh.off + (par ^ 1u) * (T + 1u);
     const uint64_t g0 = (uint64_t)tile << P.log2T;
@@ -1040,6 +1063,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
     }
     if (tid < 7) s_ctr[tid] = 0;
     if (tid >= 8 && tid < 11) s_done[tid - 8] = 0;
+    if (tid == 11) s_good = 1u;
     bool nrec_ok = true;
     uint32_t bad = 0;
     if (tid < nrec) {
@@ -1152,6 +1176,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       __syncthreads();  // the sections are reused by the next pass
       if (tid < 7) s_ctr[tid] = 0;
       if (tid >= 8 && tid < 11) s_done[tid - 8] = 0;
+      if (tid == 11) s_good = 1u;
       FBX_MARK(11);
     }
     if (!WRITE) {
@@ -1203,10 +1228,19 @@ hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds_bytes);
     if (e != hipSuccess) return e;
   }
-  const uint32_t grid = std::min(P.n_tiles, P.grid);
-  if (mode == 0) hipLaunchKernelGGL(k_tile<0>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
-  else if (mode == 1) hipLaunchKernelGGL(k_tile<1>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
-  else hipLaunchKernelGGL(k_tile<2>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, P);
+  // as many workgroups as can run at the same time (the one-launch mode relies on it)
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kTileThreads, P.lds_bytes) != hipSuccess || per_cu < 1) {
+    (void)hipGetLastError();
+    per_cu = 1;
+  }
+  uint32_t capacity = tile_cu_count() * (uint32_t)per_cu;
+  if (P.grid && P.grid < capacity) capacity = P.grid;
+  TileParams Q = P;
+  const uint32_t grid = std::min(P.n_tiles, capacity);
+  if (mode == 0) hipLaunchKernelGGL(k_tile<0>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
+  else if (mode == 1) hipLaunchKernelGGL(k_tile<1>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
+  else hipLaunchKernelGGL(k_tile<2>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
   return hipGetLastError();
 }
 

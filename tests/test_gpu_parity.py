@@ -157,7 +157,10 @@ def test_repeated_calls_are_bit_identical_and_plan_is_reusable():
     from gpu_harness import expand
     first = {s: expand(res.slots[s], 600) for s in res.slot_ids}
     assert_same(first, res, want)
-    for _ in range(10):
+    for k in range(10):
+        if k % 2:
+            ws.fill_(0x5A)      # stale results must not be able to stand in for missing writes
+            plan.set_workspace(ws)
         res = plan.extract(d_raw, d_off)
         again = {s: expand(res.slots[s], 600) for s in res.slot_ids}
         for s in first:
@@ -186,14 +189,19 @@ def test_one_launch_mode_matches_and_falls_back():
         res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.2)
         assert res.tile_launches == (2 if any(s.offsets is not None for s in res.slots.values()) else 1)
         for _ in range(3):
+            ws.fill_(0xAB)          # nothing an earlier call wrote may stand in for this call's results
+            plan.set_workspace(ws)
             res = plan.extract(d_raw, d_off)
-            assert res.tile_launches == 1, w.name
+            # (plans with many ragged operators and short tiles keep the counting launch)
+            assert res.tile_launches == (1 if cfg in (5, 3) else 2), w.name
             assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, w.name)
         # another batch of the same kind but a different size
         raw2, off2 = w.generate(rec_begin=10000, n_records=n // 3)
         d_raw2, d_off2 = to_device(raw2, off2)
+        ws.fill_(0xCD)
+        plan.set_workspace(ws)
         res2 = plan.extract(d_raw2, d_off2)
-        assert res2.tile_launches == 1, w.name
+        assert res2.tile_launches == (1 if cfg in (5, 3) else 2), w.name
         assert_same({s: expand(res2.slots[s], n // 3) for s in res2.slot_ids}, res2, O.extract(w.spec, raw2, off2), w.name)
         plan.close()
     # lists that grow tenfold between calls: the arrays sized from the first call are too small
@@ -201,8 +209,9 @@ def test_one_launch_mode_matches_and_falls_back():
             "op a hash slot=0 seed=1 emit=1 field=0 multi=1\n"
             "op b hash slot=1 seed=2 emit=1 field=1 multi=0\n"
             "op c cross slot=2 seed=3 emit=1 a=a b=b\n")
-    short = [b"x\ty\n"] * 5000
-    long_ = [b"a,b,c,d,e,f,g,h,i,j,k,l\tz\n"] * 5000
+    pad = b"p" * 60   # (tiny records keep the counting launch: the placement words would outweigh them)
+    short = [b"x\t" + pad + b"\n"] * 5000
+    long_ = [b"a,b,c,d,e,f,g,h,i,j,k,l\t" + pad + b"\n"] * 5000
     plan = B.Plan(spec)
     import torch
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
@@ -210,6 +219,8 @@ def test_one_launch_mode_matches_and_falls_back():
     for recs, launches in ((short, 2), (short, 1), (long_, 2), (long_, 1), (short, 1)):
         raw, off = _cat(recs)
         d_raw, d_off = to_device(np.frombuffer(raw, np.uint8), off)
+        ws.fill_(0xEF)
+        plan.set_workspace(ws)
         res = plan.extract(d_raw, d_off)
         assert res.tile_launches == launches
         assert_same({s: expand(res.slots[s], len(recs)) for s in res.slot_ids}, res, O.extract(spec, np.frombuffer(raw, np.uint8), off))
