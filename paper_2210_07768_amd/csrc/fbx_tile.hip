@@ -474,10 +474,10 @@ constexpr uint32_t kWaves = kTileThreads / 64;
 // Work counters of a pass (cleared between passes): s_ctr[0] hands out the
 // single-valued hash / bucket units of layer 1, which fill every phase that has
 // idle wavefronts; s_ctr[1] the counting units, s_ctr[2] the derivation,
-// s_ctr[3] the ragged root units, s_ctr[4 + (l & 1)] the units of layer l.
-// s_ctr[6] the placement unit.  s_done[0..2]: finished units of the counting, the
+// s_ctr[3] the ragged root units, s_ctr[4 + (l & 1)] the single crosses of layer l,
+// s_ctr[6] the placement units, s_ctr[7 + (l & 1)] the list operators of layer l.  s_done[0..2]: finished units of the counting, the
 // derivation and the placement phase.
-__shared__ uint32_t s_ctr[7];
+__shared__ uint32_t s_ctr[9];
 __shared__ uint32_t s_done[3];
 __shared__ uint32_t s_good;   // MODE 2: the tile's bases are known and inside the arrays
 
@@ -863,8 +863,8 @@ __device__ __forceinline__ bool lb_place_row(const TileParams& P, const Sh& sh, 
 }
 
 // Runs every layer on the nb records of one pass.  WRITE = false stops after the
-// counts.  hook() is called once by every lane after the first barrier (the
-// caller starts the next tile's loads there).
+// counts.  hook() is called by every lane right after barriers (the caller
+// advances the next tile's loads there).
 template <int MODE, class Src, class Hook>
 __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint32_t nb, uint64_t g_first,
                                          uint32_t tile, uint32_t& malformed, bool& overflow, Hook&& hook) {
@@ -907,6 +907,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   if (P.n_rnr) {
     critical_phase(1u, &s_ctr[2], &s_done[1], [&](uint32_t) { ps.derive(); });
     FBX_MARK(5);
+    hook();
   }
   if (MODE == 2 && P.n_ragged) {
     if (__syncthreads_or((int)overflow)) {  // absurd counts: nothing of this tile may be placed
@@ -920,20 +921,39 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     for (uint32_t u = wave; u < us; u += kWaves) ps.scan_unit(u);
     __syncthreads();
     FBX_MARK(6);
+    hook();
   }
   if (!WRITE) return;
-  // ---- phase B3 (no counting launch): the tile's bases come from the tiles before it
-  if (MODE == 2 && P.n_ragged) {
+
+  // ---- phase C: the rest of layer 1's single signs
+  while (fill_one()) {}
+  FBX_MARK(7);
+  // ---- the single crosses of every later layer: they only read signs kept on chip
+  for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
+    __syncthreads();  // the layer barrier: every sign this layer reads is in place
+    hook();
+    uint32_t* ctr = &s_ctr[4u + (layer & 1u)];
+    if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
+    const uint32_t ux = ps.units_of(TL_LAYER + 2u * (layer - 2u));
+    for (uint32_t u = grab_unit(ctr); u < ux; u = grab_unit(ctr)) {
+      if (FBX_SKIP(2u)) continue;
+      ps.x11_unit(layer, u);
+    }
+  }
+  FBX_MARK(8);
+  if (!P.n_ragged) return;  // (list operators need a ragged input somewhere below them)
+
+  // ---- one-launch mode: the tile's bases come from the tiles before it.  This is as late as
+  // it can be: the count went out long ago, so the tiles before this one have had time to count.
+  if (MODE == 2) {
     critical_phase(P.n_ragged, &s_ctr[6], &s_done[2], [&](uint32_t row) {
       if (!lb_place_row(P, sh, tile, row) && lane == 0) s_good = 0u;
     });
-    if (!s_good) {  // the call fails or falls back: leave the arrays alone
-      return;
-    }
+    FBX_MARK(9);
+    if (!s_good) return;  // the call fails or falls back: leave the arrays alone
   }
-
-  // ---- phase C: ragged root operators first (the long units), then the rest of layer 1
-  if (P.n_ragged) {
+  // ---- ragged root operators
+  {
     uint32_t um = 0;
     if (P.n_mh) { ps.item_offsets(); um = ps.item_units(); }
     const uint32_t uo = ps.other_units(), un = ps.ngram_units();
@@ -944,22 +964,17 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
       else ps.ngram_unit(u - uo - um);
     }
   }
-  FBX_MARK(7);
-  while (fill_one()) {}
-  FBX_MARK(8);
-  // ---- later layers: the single crosses of layer l, then its list crosses / concats
+  FBX_MARK(10);
+  // ---- the list crosses / concats, layer by layer
   for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
-    __syncthreads();  // the layer barrier: every sign this layer reads is in place
-    FBX_MARK(9);
-    uint32_t* ctr = &s_ctr[4u + (layer & 1u)];
-    if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
-    const uint32_t ux = ps.units_of(TL_LAYER + 2u * (layer - 2u)), ug = ps.units_of(TL_LAYER + 2u * (layer - 2u) + 1u);
-    for (uint32_t u = grab_unit(ctr); u < ug + ux; u = grab_unit(ctr)) {
+    __syncthreads();  // the layer barrier
+    uint32_t* ctr = &s_ctr[7u + (layer & 1u)];
+    if (tid == 0) s_ctr[7u + ((layer + 1u) & 1u)] = 0;
+    const uint32_t ug = ps.units_of(TL_LAYER + 2u * (layer - 2u) + 1u);
+    for (uint32_t u = grab_unit(ctr); u < ug; u = grab_unit(ctr)) {
       if (FBX_SKIP(2u)) continue;
-      if (u < ug) ps.gen_unit(layer, u);
-      else ps.x11_unit(layer, u - ug);
+      ps.gen_unit(layer, u);
     }
-    FBX_MARK(10);
   }
 }
 
@@ -993,7 +1008,7 @@ __device__ __forceinline__ u32x4 load_chunk(uintptr_t ca, uintptr_t ok_lo, uintp
 constexpr uint32_t kPre = 4;  // 16-byte chunks a lane may hold for the next tile (larger tiles load when their turn comes)
 
 // Workgroups are persistent: each copies the plan tables into LDS once and then
-// takes every W-th tile until none is left.
+// takes tiles off a shared counter until none is left.
 template <int MODE>
 __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   constexpr bool WRITE = MODE != 0;
@@ -1004,17 +1019,13 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   const FBX_GLOBAL uint64_t* rec_off = gptr(P.rec_off);
   uint32_t* ticket = &P.ctrl->ticket[WRITE ? 1 : 0];  // (MODE 2 needs the order the counter gives: see lb_place_tile)
   const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(P.raw), ok_hi = ok_lo + P.raw_len;
-  // Workgroups number themselves in the order in which they start running; workgroup s
-  // takes tiles s, s + W, s + 2 W, ... (W = working workgroups of the launch).  Tiles that
-  // are worked on at the same time are then neighbours in the tile order, which is what
-  // the placement of the one-launch mode needs: nobody holds a tile that others wait for
-  // while busy with an earlier one.
-  const uint32_t n_workers = gridDim.x;
+  // Tiles are taken off a counter.  A workgroup takes its next tile when it starts on the
+  // current one (that early, so that the next tile's offsets and text can be on their way),
+  // never more than one ahead: tiles are then started in the order of their numbers, give
+  // or take how long single tiles take, which is what the one-launch placement needs.
   if (tid == 0) {
     s_err = P.ctrl->err;  // set by an earlier kernel of this call: nothing may be written
-    const uint32_t slot = atomicAdd(ticket, 1u);
-    s_cur = slot;
-    s_nxt = slot + n_workers;
+    s_cur = atomicAdd(ticket, 1u);
   }
   copy_table(smem + P.o_prog, P.prog, P.n_ops * (uint32_t)sizeof(OpProg));
   copy_table(smem + P.o_lists, P.lists, P.n_ops * 4u);
@@ -1042,28 +1053,21 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   u32x4 pre[kPre];      // the next tile's raw text on its way (this lane's chunks)
   bool have_pre = false;
   for (;;) {
-    const uint32_t tile = s_cur, nxt = s_nxt;
+    const uint32_t tile = s_cur;
     if (tile >= P.n_tiles) break;
-    const uint32_t after_next = nxt + n_workers;  // (tile numbers past the end just end the loop)
+    uint32_t my_ticket = 0;
+    if (tid == 0) my_ticket = atomicAdd(ticket, 1u);  // the next tile; the answer is picked up a barrier later
     uint64_t* off = sh.off + par * (T + 1u);
     uint64_t* off2 = sh.off + (par ^ 1u) * (T + 1u);
     const uint64_t g0 = (uint64_t)tile << P.log2T;
     const uint32_t nrec = (uint32_t)min((uint64_t)T, P.n_records - g0);
-    // the next tile's offsets: requested now, parked in LDS after the next barrier
-    uint32_t nrec2 = 0;
-    uint64_t off_next = 0;
-    if (nxt < P.n_tiles) {
-      const uint64_t g1 = (uint64_t)nxt << P.log2T;
-      nrec2 = (uint32_t)min((uint64_t)T, P.n_records - g1);
-      if (tid <= nrec2) off_next = rec_off[g1 + tid];
-    }
     for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads) {
       sh.run[row] = 0;
       if (MODE == 1) sh.base[row] = gptr(P.tile_base)[(uint64_t)row * P.n_tiles + tile];
     }
-    if (tid < 7) s_ctr[tid] = 0;
-    if (tid >= 8 && tid < 11) s_done[tid - 8] = 0;
-    if (tid == 11) s_good = 1u;
+    if (tid < 9) s_ctr[tid] = 0;
+    if (tid >= 9 && tid < 12) s_done[tid - 9] = 0;
+    if (tid == 12) s_good = 1u;
     bool nrec_ok = true;
     uint32_t bad = 0;
     if (tid < nrec) {
@@ -1080,26 +1084,44 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
     }
     FBX_MARK(1);
 
-    bool first_pass = true;
+    // The next tile arrives in steps, one per barrier of this tile, so that no step waits for
+    // memory: (0) its number, (1) its record offsets are requested, (2) they are parked in LDS
+    // and its text is requested into registers.  Only the two outer offsets decide what is
+    // read; the tile itself is checked when its turn comes.
+    uint32_t pf_stage = 0, nxt = 0xffffffffu, nrec2 = 0;
+    uint64_t off_next = 0, nx_lo = 0, nx_hi = 0;
     bool next_pre = false;
-    // Called by every lane after the first barrier of the tile's first pass: the next
-    // tile's offsets are in LDS by then, so its text can be requested.  Only the two
-    // outer offsets decide what is read; the tile itself is checked when its turn comes.
-    auto start_next_tile = [&]() {
-      if (!first_pass || nxt >= P.n_tiles) return;
-      const uint64_t lo = off2[0], hi = off2[nrec2];
-      const uintptr_t addr = ok_lo + lo;
-      const uint32_t delta = (uint32_t)(addr & 15u);
-      if (lo <= hi && hi <= P.raw_len && hi - lo + delta <= (uint64_t)min(P.raw_cap, kPre * kTileThreads * 16u)) {
-        const uint32_t nchunks = (delta + (uint32_t)(hi - lo) + 15u) >> 4;
-        const uintptr_t a0 = addr - delta;
-#pragma unroll
-        for (uint32_t k = 0; k < kPre; ++k) {
-          const uint32_t c = tid + k * kTileThreads;
-          if (c < nchunks) pre[k] = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
+    auto next_tile_step = [&]() {  // every lane, right after a barrier
+      if (pf_stage == 0) {
+        if (tid == 0) s_nxt = my_ticket;
+      } else if (pf_stage == 1) {
+        nxt = s_nxt;
+        if (nxt < P.n_tiles) {
+          const uint64_t g1 = (uint64_t)nxt << P.log2T;
+          nrec2 = (uint32_t)min((uint64_t)T, P.n_records - g1);
+          if (tid <= nrec2) off_next = rec_off[g1 + tid];
+          nx_lo = rec_off[g1];
+          nx_hi = rec_off[g1 + nrec2];
         }
-        next_pre = true;
+      } else if (pf_stage == 2) {
+        if (nxt < P.n_tiles) {
+          if (tid <= nrec2) off2[tid] = off_next;
+          const uintptr_t addr = ok_lo + nx_lo;
+          const uint32_t delta = (uint32_t)(addr & 15u);
+          if (nx_lo <= nx_hi && nx_hi <= P.raw_len &&
+              nx_hi - nx_lo + delta <= (uint64_t)min(P.raw_cap, kPre * kTileThreads * 16u)) {
+            const uint32_t nchunks = (delta + (uint32_t)(nx_hi - nx_lo) + 15u) >> 4;
+            const uintptr_t a0 = addr - delta;
+#pragma unroll
+            for (uint32_t k = 0; k < kPre; ++k) {
+              const uint32_t c = tid + k * kTileThreads;
+              if (c < nchunks) pre[k] = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
+            }
+            next_pre = true;
+          }
+        }
       }
+      if (pf_stage < 3) ++pf_stage;
     };
 
     uint32_t r0 = nrec_ok ? 0u : nrec;
@@ -1113,7 +1135,6 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
         r0 = nrec;
       }
     }
-    if (r0 >= nrec && tid <= nrec2) off2[tid] = off_next;  // (a tile that is left out still hands on the next one's offsets)
     while (r0 < nrec) {  // one turn per pass; all conditions are uniform over the workgroup
       const uint64_t o0 = off[r0];
       const uintptr_t addr0 = ok_lo + o0;
@@ -1128,7 +1149,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       if (r1 > r0) {
         const uint32_t nb = r1 - r0;
         const uint32_t nchunks = (delta + (uint32_t)(off[r1] - o0) + 15u) >> 4;
-        if (first_pass && have_pre) {  // the whole tile was requested a turn ago
+        if (r0 == 0 && have_pre) {  // the whole tile was requested a turn ago
 #pragma unroll
           for (uint32_t k = 0; k < kPre; ++k) {
             const uint32_t c = tid + k * kTileThreads;
@@ -1149,14 +1170,13 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
           const uint32_t e = sh.re[tid];
           if (e > sh.rs[tid] && sh.raw[e - 1u] == '\n') sh.re[tid] = e - 1u;
         }
-        if (first_pass && tid <= nrec2) off2[tid] = off_next;
         __syncthreads();
         FBX_MARK(2);
         if (!FBX_SKIP(8u)) tokenize(P, sh, nb);
         __syncthreads();
         FBX_MARK(3);
         LdsSrc src{sh.raw, sh.rows, P.row_stride};
-        run_pass<MODE>(P, sh, src, nb, g0 + r0, tile, malformed, overflow, start_next_tile);
+        run_pass<MODE>(P, sh, src, nb, g0 + r0, tile, malformed, overflow, next_tile_step);
         r0 = r1;
       } else {
         // record r0 alone exceeds the section: it is read in place
@@ -1166,26 +1186,29 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
           if (len && gptr(P.raw)[o0 + len - 1u] == '\n') --len;
           s_len = len;
         }
-        if (first_pass && tid <= nrec2) off2[tid] = off_next;
         __syncthreads();
         GlobalSrc src{gptr(P.raw) + o0, s_len};
-        run_pass<MODE>(P, sh, src, 1u, g0 + r0, tile, malformed, overflow, start_next_tile);
+        run_pass<MODE>(P, sh, src, 1u, g0 + r0, tile, malformed, overflow, next_tile_step);
         r0 += 1u;
       }
-      first_pass = false;
       __syncthreads();  // the sections are reused by the next pass
-      if (tid < 7) s_ctr[tid] = 0;
-      if (tid >= 8 && tid < 11) s_done[tid - 8] = 0;
-      if (tid == 11) s_good = 1u;
+      if (tid < 9) s_ctr[tid] = 0;
+      if (tid >= 9 && tid < 12) s_done[tid - 9] = 0;
+      if (tid == 12) s_good = 1u;
       FBX_MARK(11);
     }
     if (!WRITE) {
       for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads)
         gptr(P.tile_cnt)[(uint64_t)row * P.n_tiles + tile] = sh.run[row];
     }
+    while (pf_stage < 3) {  // (a tile with few barriers: the remaining steps each get their own)
+      __syncthreads();
+      next_tile_step();
+    }
     have_pre = next_pre;
     par ^= 1u;
-    if (tid == 0) { s_cur = nxt; s_nxt = after_next; }
+    __syncthreads();
+    if (tid == 0) s_cur = s_nxt;
     __syncthreads();
     FBX_MARK(12);
   }
