@@ -122,7 +122,7 @@ def main():
     for kv in args.opt:
         k, v = kv.split("=")
         plan.set_option(k, int(v))
-    res, ws = B.extract_with_retry(plan, d_raw, d_off)
+    res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.03)  # a few percent of headroom, as a serving loop would keep
     log(f"[bench] workspace {ws.numel() / 1e9:.2f} GB, {res.n_values_total} signs, "
         f"{len(res.slot_ids)} slots, malformed {res.n_malformed_numeric}")
 

@@ -133,7 +133,9 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len,
                        const uint64_t* d_rec_off, uint64_t n_records, void* hip_stream,
                        fbx_result* out);
 
-/* Last error text of a plan (or of the last failed fbx_plan_create when plan is NULL). */
+/* Last error text of a plan (or of the last failed fbx_plan_create when plan is NULL).  After an
+ * fbx_extract that returned FBX_OK it is empty, or a note on why the call took the longer of its
+ * two launch sequences. */
 const char* fbx_last_error(const fbx_plan* plan);
 const char* fbx_status_str(fbx_status s);
 

@@ -102,6 +102,7 @@ class ExtractResult:
         self.arena_high_water = 0
         self.n_layers = 0
         self.tile_launches = 0
+        self.note = ""
         self.slots: Dict[int, Slot] = {}
         self.slot_ids: List[int] = []
 
@@ -179,6 +180,7 @@ class Plan:
         out.n_malformed_numeric, out.arena_high_water = res.n_malformed_numeric, res.arena_high_water
         out.n_layers = res.n_layers
         out.tile_launches = res.tile_launches
+        out.note = lib().fbx_last_error(self._h).decode()
         base = self._ws.data_ptr()
         ws64 = self._ws[: self._ws.numel() // 8 * 8].view(torch.int64)
         for i in range(res.n_slots):

@@ -55,6 +55,7 @@ struct fbx_plan {
   std::vector<uint64_t> learned_total;   // by ragged row
   std::vector<uint64_t> cap_host;        // capacities of the current call, by ragged row
   int last_mode = 0;                     // 1: counting + writing launch, 2: one launch
+  uint64_t margin_failed_ws = 0;         // workspace size at which the sized arrays did not fit (no retry below it)
 
   // results of the last call
   std::vector<uint8_t> readback;  // Ctrl + OpDyn[n_ops]
@@ -522,6 +523,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   // (every tile reads 512 bytes of placement words per ragged operator: only worth it when that is
   // little next to the tile's own text)
   bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records &&
+             plan->ws_bytes > plan->margin_failed_ws &&
              uint64_t(h.n_ragged) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T;
   if (one) {
     plan->cap_host.resize(h.n_ragged);
@@ -533,6 +535,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     }
   }
   const Ctrl* c = reinterpret_cast<const Ctrl*>(plan->readback.data() + plan->off_ctrl);
+  const char* fell_back = nullptr;
   for (;;) {
     fbx_status rs = run(one);
     if (rs != FBX_OK) return rs;
@@ -541,6 +544,9 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
       return FBX_E_HIP;
     }
     if (one && (c->err & (CE_SPEC | CE_NOMEM))) {
+      fell_back = (c->err & CE_SPEC) ? "one-launch attempt fell back to the counting launch: a tile larger than the LDS section, or more signs than the arrays were sized for"
+                                     : "one-launch attempt fell back to the counting launch: the margin on the arrays did not fit the workspace";
+      if (!(c->err & CE_SPEC)) plan->margin_failed_ws = plan->ws_bytes;
       one = false;  // fall back to counting first
       continue;
     }
@@ -597,6 +603,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   out->n_slots = static_cast<uint32_t>(plan->slots.size());
   out->n_layers = h.n_layers;
   out->slots = plan->slots.data();
+  plan->error = fell_back ? fell_back : "";  // (not an error: fbx_last_error doubles as a note after FBX_OK)
   out->tile_launches = g.tile_engine ? (one ? 1u : (h.n_ragged ? 2u : 1u)) : 0u;
   return FBX_OK;
 }
