@@ -645,7 +645,7 @@ struct Pass {
   // record, form one index space; a lane finds its operator and record by two
   // small searches, its item's bounds in the comma table, and writes the sign to
   // the item's own position: neighbouring lanes write neighbouring signs.
-  __device__ __forceinline__ void item_offsets() {  // every wavefront, after the positions are known
+  __device__ __forceinline__ void item_offsets() {  // one wavefront, after the positions are known
     const uint32_t lane = lane_id();
     uint32_t carry = 0;
     for (uint32_t i0 = 0; i0 < P.n_mh; i0 += 64u) {
@@ -925,7 +925,9 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   }
   if (!WRITE) return;
 
-  // ---- phase C: the rest of layer 1's single signs
+  // ---- phase C: the rest of layer 1's single signs; one wavefront first lays out the item
+  // index space of the multi-valued hashes (needed after at least one more barrier)
+  if (P.n_mh && wave == kWaves - 1) ps.item_offsets();
   while (fill_one()) {}
   FBX_MARK(7);
   // ---- the single crosses of every later layer: they only read signs kept on chip
@@ -951,11 +953,12 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     });
     FBX_MARK(9);
     if (!s_good) return;  // the call fails or falls back: leave the arrays alone
+  } else if (P.n_mh) {
+    __syncthreads();  // the item index space laid out in phase C is read by every wavefront
   }
   // ---- ragged root operators
   {
-    uint32_t um = 0;
-    if (P.n_mh) { ps.item_offsets(); um = ps.item_units(); }
+    const uint32_t um = P.n_mh ? ps.item_units() : 0u;
     const uint32_t uo = ps.other_units(), un = ps.ngram_units();
     for (uint32_t u = grab_unit(&s_ctr[3]); u < um + uo + un; u = grab_unit(&s_ctr[3])) {
       if (FBX_SKIP(4u)) continue;
@@ -1141,6 +1144,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       const uint32_t delta = (uint32_t)(addr0 & 15u);
       // the pass takes records r0 .. r1-1: as many as fit the LDS section
       uint32_t lo = r0, hi = nrec;
+      if (off[nrec] - o0 + delta <= (uint64_t)P.raw_cap) lo = nrec;  // the usual case: all that is left fits
       while (lo < hi) {
         const uint32_t mid = (lo + hi + 1u) >> 1;
         if (off[mid] - o0 + delta <= (uint64_t)P.raw_cap) lo = mid; else hi = mid - 1u;
