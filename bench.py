@@ -1,11 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the feature-extraction hot path on one MI355X.
 
-A step is one pass of the whole path (validate, count, scan, allocate, every
-layer's tile kernel) over one batch of synthetic records that is already
-resident in HBM.  Prints ONE JSON line: records/s, signs/s, the roofline of the
-dominant kernel (HIP-event time on the call's stream, measured live), and the
-CPU oracle timed on a bounded sample of the same workload.
+A step is one fbx_extract call: the whole path (every kernel the call enqueues
+plus its one synchronisation) over one batch of synthetic records that is
+already resident in HBM.  Prints ONE JSON line: records/s, signs/s, the roofline
+of the dominant kernel (HIP-event time on the call's stream, measured live), and
+the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -20,6 +20,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+
+# HBM traffic of one launch of the dominant kernel as rocprofv3 counted it (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a device-to-device copy of known
+# size), for the workloads that were profiled: see profiles/.  Other runs report null.
+MEASURED_TRAFFIC = {
+    # (workload, records, launch sequence): bytes per launch; profiles/k_tile_config5_hbm_traffic.md
+    ("config5", 16000000, "one_launch"): 49179794882,
+}
 
 
 def log(*a):
@@ -167,8 +175,18 @@ def main():
     dom_ms = avg[dom]
     achieved = launches[dom] / (dom_ms * 1e-3) / 1e9
     names = {0: "validate", 1: "count", 2: "scan", 3: "alloc"}
-    kernels = {names.get(k, f"tile_layer{k - 100}" if not args.fused else "tile_fused"): round(v, 4)
+    kernels = {names.get(k, f"tile_layer{k - 100}" if not args.fused else "tile"): round(v, 4)
                for k, v in sorted(avg.items())}
+    if not args.fused:
+        launch, kname = "per_layer", f"fbx::k_walk, layer {dom - 100}"
+    elif res.tile_launches == 0:
+        launch, kname = "walk_fused", "fbx::k_walk"
+    elif res.tile_launches == 1:
+        # no ragged slot at all: the writing launch alone; else counting and writing in one launch
+        has_ragged = any(" multi=1" in ln or " ngram " in ln or " filter " in ln for ln in w.spec.split("\n"))
+        launch, kname = ("one_launch", "fbx::k_tile<2>") if has_ragged else ("write", "fbx::k_tile<1>")
+    else:
+        launch, kname = "count+write", "fbx::k_tile<1>"
 
     out = {
         "metric": "records/s", "value": R / (ms_per_step * 1e-3), "unit": "records/s",
@@ -176,16 +194,18 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": w.name, "records": R, "fields": w.n_fields, "ops": w.n_ops, "layers": w.n_layers,
-                   "raw_bytes": raw_len, "signs": int(n_signs), "launch": "fused" if args.fused else "per_layer"},
+                   "raw_bytes": raw_len, "signs": int(n_signs), "launch": launch},
         "signs_per_s": n_signs / (ms_per_step * 1e-3),
         "path_algorithmic_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "path_frac_of_hbm_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernel_ms": kernels,
-        "roofline": {"bound": "hbm", "kernel": "k_tile<write> " + ("fused" if args.fused else f"layer {dom - 100}"),
+        "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get((w.name, R, launch)),
                      "algorithmic_bytes_per_launch": int(launches[dom]), "avg_launch_ms": dom_ms},
     }
+    if res.note:
+        out["note"] = res.note
     if not args.no_cpu:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(w)

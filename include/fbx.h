@@ -122,11 +122,17 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
  * Inputs are borrowed until the call returns.  Results point into the workspace
  * and are overwritten by the next fbx_extract on this plan.  The call
  * synchronises the stream exactly once, at its end, to read back sizes.
- * Layer by layer: with the plan option "fused" = 0 one kernel launch per layer,
- * the stream order being the layer barrier (Section 4); by default all layers in
- * one launch, each wavefront taking its records through the layers in order;
- * the dynamic-memory pool is released in O(1) after each
- * layer as far as live intermediates allow (Section 5, "Reset GPU memory pool").
+ * Layer by layer: by default all layers run in one launch, each workgroup taking
+ * a tile of records through the layers in order with a barrier after each layer
+ * (Section 4, "Scheduling": the synchronisation after a layer, per tile); with
+ * the plan option "fused" = 0 one kernel launch per layer, the stream order being
+ * the layer barrier, and the dynamic-memory pool released in O(1) after each layer
+ * as far as live intermediates allow (Section 5, "Reset GPU memory pool").
+ * Ragged slots need their sizes before they can be placed: the first call on a
+ * plan counts in a launch of its own; later calls size the arrays from the call
+ * before (plus a margin), count and write in one launch, and repeat themselves
+ * with the counting launch if a batch does not fit (out->tile_launches tells).
+ * On an error the contents of the workspace are unspecified.
  * Errors: FBX_E_ARG, FBX_E_NOMEM, FBX_E_INPUT, FBX_E_HIP.
  */
 fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len,
@@ -149,8 +155,15 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
 
 /*
  * Tuning knobs, all optional.  Keys:
- *   "fused"        1: all layers in one launch, each wavefront running the layers in
- *                  order on its own 64 records (default); 0: one launch per layer
+ *   "fused"        1: all layers in one launch (tile kernel, default); 0: one launch per
+ *                  layer (walk kernels)
+ *   "one_launch"   1: later calls skip the counting launch as described at fbx_extract
+ *                  (default); 0: always count first
+ *   "tile_log2"    -1: records per tile chosen per call (default); 0..6: 2^value records
+ *   "raw_cap"      0: bytes of text a workgroup stages at a time chosen per call (default);
+ *                  64..65000: that many
+ *   "lds_budget"   LDS bytes per workgroup the tile size is chosen for (default 81920)
+ *   "grid_limit"   0: as many workgroups as run at the same time (default); else at most that
  *   "profile"      1: time every kernel of fbx_extract with HIP events
  * Errors: FBX_E_ARG for an unknown key or an out-of-range value.
  */
@@ -159,7 +172,8 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value);
 /*
  * Kernel timings of the last fbx_extract (needs option "profile" = 1).
  * which: 0 validate, 1 count, 2 scan, 3 alloc, 4 all tile launches together,
- *        100 + l : tile launch of layer l (1-based; 101 alone in fused mode).
+ *        100 + l : tile launch of layer l (1-based; 101 alone when all layers share a launch).
+ * A kernel the last call did not launch answers FBX_E_ARG.
  * ms receives the HIP-event duration on the call's stream.
  */
 fbx_status fbx_plan_kernel_ms(const fbx_plan* plan, uint32_t which, float* ms);

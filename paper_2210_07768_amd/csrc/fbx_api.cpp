@@ -264,8 +264,10 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "grid_limit") {
     if (value < 0 || value > 65536) { plan->error = "grid_limit must be in 0..65536"; return FBX_E_ARG; }
     plan->grid_limit = static_cast<uint32_t>(value);
-  } else if (k == "debug_skip") {
+#ifdef FBX_TILE_PROF
+  } else if (k == "debug_skip") {  // tuning builds: leave phases out (results are then wrong)
     plan->dbg = static_cast<uint32_t>(value);
+#endif
   } else if (k == "profile") {
     if (value != 0 && value != 1) { plan->error = "profile must be 0 or 1"; return FBX_E_ARG; }
     plan->profile = static_cast<int>(value);
