@@ -212,11 +212,35 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
       }
     }
   };
-  uint32_t cnt = 0;
-  for (uint32_t ci = c0; ci < c1; ++ci) {
-    uint32_t f[4];
-    chunk_flags(ci, f);
-    cnt += __popc(f[0]) + __popc(f[1]) + __popc(f[2]) + __popc(f[3]);
+  // A lane with at most four chunks (the usual case) keeps one bit per byte: bit i of (mhi:mlo)
+  // is set when byte i of its run is a tab.  The second walk then needs no memory at all.
+  const bool few = c <= 4u;
+  uint32_t mlo = 0, mhi = 0, cnt = 0;
+  if (few) {
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      if (c0 + q < c1) {
+        uint32_t f[4];
+        chunk_flags(c0 + q, f);
+        // flag bytes (0x80 or 0) -> bits, four dwords -> sixteen bits
+        uint32_t lo8 = __builtin_amdgcn_udot4(f[0] >> 7, 0x08040201u, 0u, false);
+        lo8 = __builtin_amdgcn_udot4(f[1] >> 7, 0x80402010u, lo8, false);
+        uint32_t hi8 = __builtin_amdgcn_udot4(f[2] >> 7, 0x08040201u, 0u, false);
+        hi8 = __builtin_amdgcn_udot4(f[3] >> 7, 0x80402010u, hi8, false);
+        const uint32_t m16 = lo8 | (hi8 << 8);
+        if (q == 0) mlo = m16;
+        else if (q == 1) mlo |= m16 << 16;
+        else if (q == 2) mhi = m16;
+        else mhi |= m16 << 16;
+      }
+    }
+    cnt = __popc(mlo) + __popc(mhi);
+  } else {
+    for (uint32_t ci = c0; ci < c1; ++ci) {
+      uint32_t f[4];
+      chunk_flags(ci, f);
+      cnt += __popc(f[0]) + __popc(f[1]) + __popc(f[2]) + __popc(f[3]);
+    }
   }
   uint32_t incl = cnt;
   for (uint32_t s = 1; s < gsz; s <<= 1) {
@@ -227,23 +251,39 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
   if (!act) return;
   uint32_t k = incl - cnt;
   uint16_t* row = sh.rows + r * P.row_stride;
-  // second walk: from tab to tab.  A window of eight bytes at the current position
-  // (any alignment) shows the next tab, so every lane places one tab per turn.
-  const uint32_t* raw32 = reinterpret_cast<const uint32_t*>(sh.raw);
-  const uint32_t be = min(re, ab + 16u * c1);
-  uint32_t p = max(rs, ab + 16u * c0);
-  while (p < be) {
-    const uint32_t a = p >> 2, sh8 = (p & 3u) * 8u;
-    const uint32_t w0 = raw32[a], w1 = raw32[a + 1], w2 = raw32[a + 2];
-    const uint32_t f0 = tab_flags(__builtin_amdgcn_alignbit(w1, w0, sh8));
-    const uint32_t f1 = tab_flags(__builtin_amdgcn_alignbit(w2, w1, sh8));
-    const uint32_t i0 = ((uint32_t)__ffs((int)f0) - 1u) >> 3, i1 = 4u + (((uint32_t)__ffs((int)f1) - 1u) >> 3);
-    const uint32_t idx = f0 ? i0 : (f1 ? i1 : 8u);
-    p += idx;
-    if (idx < 8u && p < be) {
-      if (k < F) row[1u + k] = (uint16_t)p;
-      ++k;
-      ++p;
+  if (few) {
+    uint32_t base = ab + 16u * c0;
+    uint32_t m = mlo;
+#pragma unroll
+    for (uint32_t half = 0; half < 2; ++half) {
+      while (m) {
+        const uint32_t i = (uint32_t)__ffs((int)m) - 1u;
+        if (k < F) row[1u + k] = (uint16_t)(base + i);
+        ++k;
+        m &= m - 1u;
+      }
+      m = mhi;
+      base += 32u;
+    }
+  } else {
+    // second walk of a long run: from tab to tab.  A window of eight bytes at the current
+    // position (any alignment) shows the next tab, so every lane places one tab per turn.
+    const uint32_t* raw32 = reinterpret_cast<const uint32_t*>(sh.raw);
+    const uint32_t be = min(re, ab + 16u * c1);
+    uint32_t p = max(rs, ab + 16u * c0);
+    while (p < be) {
+      const uint32_t a = p >> 2, sh8 = (p & 3u) * 8u;
+      const uint32_t w0 = raw32[a], w1 = raw32[a + 1], w2 = raw32[a + 2];
+      const uint32_t f0 = tab_flags(__builtin_amdgcn_alignbit(w1, w0, sh8));
+      const uint32_t f1 = tab_flags(__builtin_amdgcn_alignbit(w2, w1, sh8));
+      const uint32_t i0 = ((uint32_t)__ffs((int)f0) - 1u) >> 3, i1 = 4u + (((uint32_t)__ffs((int)f1) - 1u) >> 3);
+      const uint32_t idx = f0 ? i0 : (f1 ? i1 : 8u);
+      p += idx;
+      if (idx < 8u && p < be) {
+        if (k < F) row[1u + k] = (uint16_t)p;
+        ++k;
+        ++p;
+      }
     }
   }
   if (j == 0) row[0] = (uint16_t)(rs - 1u);
@@ -514,6 +554,7 @@ struct Pass {
   uint32_t& malformed;
   bool& overflow;
   uint32_t lb_tile;   // tile number when counts are to be published (one-launch mode), else kNoRow
+  bool need_table;    // the pass goes on to write: keep comma positions while counting
 
   __device__ __forceinline__ uint32_t units_of(uint32_t list) const {
     return (sh.list_begin[list + 1] - sh.list_begin[list] + G - 1u) / G;
@@ -537,6 +578,8 @@ struct Pass {
       src.span(r, d->field, s, e);
       if (d->kind == OP_NGRAM) {
         c = e - s >= d->aux_len ? e - s - d->aux_len + 1u : 0u;
+      } else if (d->kind == OP_HASH && !need_table) {
+        c = count_commas(src, s, e) + 1u;  // counting launch: nobody reads the comma table
       } else if (d->kind == OP_HASH) {
         // multi-valued hash: from comma to comma; the first item_cap positions are kept for the item lanes
         const uint32_t i = u * G + og;  // hashes lead the ragged root list
@@ -871,7 +914,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   constexpr bool WRITE = MODE != 0;
   const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
   const uint32_t T = 1u << P.log2T;
-  Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow, MODE == 2 ? tile : kNoRow};
+  Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow, MODE == 2 ? tile : kNoRow, WRITE};
   ps.live = ps.r < nb;
   ps.g = g_first + ps.r;
   // the single-valued hashes and buckets of layer 1 fill whatever phase has idle wavefronts
@@ -1115,12 +1158,16 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
               nx_hi - nx_lo + delta <= (uint64_t)min(P.raw_cap, kPre * kTileThreads * 16u)) {
             const uint32_t nchunks = (delta + (uint32_t)(nx_hi - nx_lo) + 15u) >> 4;
             const uintptr_t a0 = addr - delta;
+            // (whole chunks only: a tile at either end of the caller's buffer loads when its turn comes)
+            if (a0 >= ok_lo && a0 + 16ull * nchunks <= ok_hi) {
+              const FBX_GLOBAL u32x4* src = gptr<const u32x4>((uint64_t)a0);
 #pragma unroll
-            for (uint32_t k = 0; k < kPre; ++k) {
-              const uint32_t c = tid + k * kTileThreads;
-              if (c < nchunks) pre[k] = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
+              for (uint32_t k = 0; k < kPre; ++k) {
+                const uint32_t c = tid + k * kTileThreads;
+                if (c < nchunks) pre[k] = src[c];
+              }
+              next_pre = true;
             }
-            next_pre = true;
           }
         }
       }
