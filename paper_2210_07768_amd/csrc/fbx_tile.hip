@@ -190,7 +190,10 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
   const uint32_t F = P.n_fields;
   const bool act = r < nb;
   uint32_t rs = 0, re = 0;
-  if (act) { rs = sh.rs[r]; re = sh.re[r]; }
+  if (act) {
+    rs = sh.rs[r]; re = sh.re[r];
+    if (re > rs && sh.raw[re - 1u] == '\n') --re;  // one trailing newline is not part of the record
+  }
   const uint32_t ab = rs & ~15u;
   const uint32_t nc = (act && re > rs) ? (re - ab + 15u) >> 4 : 0u;  // 16-byte chunks that cover the record
   const uint32_t c = (nc + gsz - 1u) >> lg;                          // chunks per lane
@@ -929,7 +932,8 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
 
   // A phase whose few long units would leave most wavefronts idle: wavefronts that
   // find no unit left hash single-valued fields until the last unit is done.
-  auto critical_phase = [&](uint32_t total, uint32_t* ctr, uint32_t* done, auto&& unit) {
+  // With `vote` (one-launch mode) the closing barrier also tells whether any lane saw absurd counts.
+  auto critical_phase = [&](uint32_t total, uint32_t* ctr, uint32_t* done, bool vote, auto&& unit) -> bool {
     for (uint32_t u = grab_unit(ctr); u < total; u = grab_unit(ctr)) {
       unit(u);
       __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
@@ -938,25 +942,26 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     if (WRITE) {
       while (*reinterpret_cast<volatile uint32_t*>(done) < total && fill_one()) {}
     }
+    if (MODE == 2 && vote) return __syncthreads_or((int)overflow) != 0;
     __syncthreads();
+    return false;
   };
 
   // ---- phase A: counts of the ragged root operators
-  if (P.n_ragged) critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], [&](uint32_t u) { ps.count_unit(u); });
+  bool absurd = false;
+  if (P.n_ragged) absurd = critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], !P.n_rnr, [&](uint32_t u) { ps.count_unit(u); });
   else __syncthreads();
   FBX_MARK(4);
   hook();
   // ---- phase B: one wavefront derives the counts of later layers
   if (P.n_rnr) {
-    critical_phase(1u, &s_ctr[2], &s_done[1], [&](uint32_t) { ps.derive(); });
+    absurd = critical_phase(1u, &s_ctr[2], &s_done[1], true, [&](uint32_t) { ps.derive(); });
     FBX_MARK(5);
     hook();
   }
-  if (MODE == 2 && P.n_ragged) {
-    if (__syncthreads_or((int)overflow)) {  // absurd counts: nothing of this tile may be placed
-      lb_abort_tile(P, tile);
-      return;
-    }
+  if (MODE == 2 && absurd) {  // absurd counts: nothing of this tile may be placed
+    lb_abort_tile(P, tile);
+    return;
   }
   // ---- phase B2: counts become positions
   if (P.n_ragged) {
@@ -991,7 +996,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // ---- one-launch mode: the tile's bases come from the tiles before it.  This is as late as
   // it can be: the count went out long ago, so the tiles before this one have had time to count.
   if (MODE == 2) {
-    critical_phase(P.n_ragged, &s_ctr[6], &s_done[2], [&](uint32_t row) {
+    critical_phase(P.n_ragged, &s_ctr[6], &s_done[2], false, [&](uint32_t row) {
       if (!lb_place_row(P, sh, tile, row) && lane == 0) s_good = 0u;
     });
     FBX_MARK(9);
@@ -1051,8 +1056,6 @@ __device__ __forceinline__ u32x4 load_chunk(uintptr_t ca, uintptr_t ok_lo, uintp
   return v;
 }
 
-constexpr uint32_t kPre = 4;  // 16-byte chunks a lane may hold for the next tile (larger tiles load when their turn comes)
-
 // Workgroups are persistent: each copies the plan tables into LDS once and then
 // takes tiles off a shared counter until none is left.
 template <int MODE>
@@ -1096,10 +1099,8 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
 
   uint32_t malformed = 0;
   bool overflow = false;
-  u32x4 pre[kPre];      // the next tile's raw text on its way (this lane's chunks)
-  bool have_pre = false;
+  uint32_t tile = s_cur;
   for (;;) {
-    const uint32_t tile = s_cur;
     if (tile >= P.n_tiles) break;
     uint32_t my_ticket = 0;
     if (tid == 0) my_ticket = atomicAdd(ticket, 1u);  // the next tile; the answer is picked up a barrier later
@@ -1132,11 +1133,11 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
 
     // The next tile arrives in steps, one per barrier of this tile, so that no step waits for
     // memory: (0) its number, (1) its record offsets are requested, (2) they are parked in LDS
-    // and its text is requested into registers.  Only the two outer offsets decide what is
-    // read; the tile itself is checked when its turn comes.
-    uint32_t pf_stage = 0, nxt = 0xffffffffu, nrec2 = 0;
+    // and one byte of every 128-byte line of its text is requested, which brings the text into
+    // the L2 cache without holding registers for it.  Only the two outer offsets decide what is
+    // touched; the tile itself is checked when its turn comes.
+    uint32_t pf_stage = 0, nxt = 0xffffffffu, nrec2 = 0, touch = 0;
     uint64_t off_next = 0, nx_lo = 0, nx_hi = 0;
-    bool next_pre = false;
     auto next_tile_step = [&]() {  // every lane, right after a barrier
       if (pf_stage == 0) {
         if (tid == 0) s_nxt = my_ticket;
@@ -1152,22 +1153,10 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       } else if (pf_stage == 2) {
         if (nxt < P.n_tiles) {
           if (tid <= nrec2) off2[tid] = off_next;
-          const uintptr_t addr = ok_lo + nx_lo;
-          const uint32_t delta = (uint32_t)(addr & 15u);
-          if (nx_lo <= nx_hi && nx_hi <= P.raw_len &&
-              nx_hi - nx_lo + delta <= (uint64_t)min(P.raw_cap, kPre * kTileThreads * 16u)) {
-            const uint32_t nchunks = (delta + (uint32_t)(nx_hi - nx_lo) + 15u) >> 4;
-            const uintptr_t a0 = addr - delta;
-            // (whole chunks only: a tile at either end of the caller's buffer loads when its turn comes)
-            if (a0 >= ok_lo && a0 + 16ull * nchunks <= ok_hi) {
-              const FBX_GLOBAL u32x4* src = gptr<const u32x4>((uint64_t)a0);
-#pragma unroll
-              for (uint32_t k = 0; k < kPre; ++k) {
-                const uint32_t c = tid + k * kTileThreads;
-                if (c < nchunks) pre[k] = src[c];
-              }
-              next_pre = true;
-            }
+          if (nx_lo <= nx_hi && nx_hi <= P.raw_len) {
+            const uintptr_t first = ok_lo + nx_lo, end = ok_lo + nx_hi;
+            const uintptr_t line = (first & ~(uintptr_t)127) + 128u * tid;  // (tiles beyond 64 KiB of text: the first 64 KiB)
+            if (line < end) touch = *gptr<const uint8_t>((uint64_t)max(line, first));
           }
         }
       }
@@ -1200,26 +1189,12 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       if (r1 > r0) {
         const uint32_t nb = r1 - r0;
         const uint32_t nchunks = (delta + (uint32_t)(off[r1] - o0) + 15u) >> 4;
-        if (r0 == 0 && have_pre) {  // the whole tile was requested a turn ago
-#pragma unroll
-          for (uint32_t k = 0; k < kPre; ++k) {
-            const uint32_t c = tid + k * kTileThreads;
-            if (c < nchunks) *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = pre[k];
-          }
-        } else {
-          const uintptr_t a0 = addr0 - delta;
-          for (uint32_t c = tid; c < nchunks; c += kTileThreads)
-            *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
-        }
+        const uintptr_t a0 = addr0 - delta;
+        for (uint32_t c = tid; c < nchunks; c += kTileThreads)
+          *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
         if (tid < nb) {
           sh.rs[tid] = kRawPad + delta + (uint32_t)(off[r0 + tid] - o0);
           sh.re[tid] = kRawPad + delta + (uint32_t)(off[r0 + tid + 1] - o0);
-        }
-        __syncthreads();
-        // one trailing newline is not part of the record
-        if (tid < nb) {
-          const uint32_t e = sh.re[tid];
-          if (e > sh.rs[tid] && sh.raw[e - 1u] == '\n') sh.re[tid] = e - 1u;
         }
         __syncthreads();
         FBX_MARK(2);
@@ -1252,15 +1227,16 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       for (uint32_t row = tid; row < P.n_ragged; row += kTileThreads)
         gptr(P.tile_cnt)[(uint64_t)row * P.n_tiles + tile] = sh.run[row];
     }
-    while (pf_stage < 3) {  // (a tile with few barriers: the remaining steps each get their own)
-      __syncthreads();
-      next_tile_step();
+    if (pf_stage < 3) {  // (a tile with few barriers: the remaining steps each get their own)
+      do {
+        __syncthreads();
+        next_tile_step();
+      } while (pf_stage < 3);
+      __syncthreads();  // the parked offsets are read by other lanes
     }
-    have_pre = next_pre;
+    asm volatile("" ::"v"(touch));  // the touched byte itself is of no use
     par ^= 1u;
-    __syncthreads();
-    if (tid == 0) s_cur = s_nxt;
-    __syncthreads();
+    tile = nxt;  // every lane has read the ticket by now
     FBX_MARK(12);
   }
 
