@@ -85,7 +85,7 @@ struct fbx_plan {
     off_row_total = o; o = align_up(o + host.n_ragged * 8ull);
     off_tile_lists = o; o = align_up(o + host.tile_lists.size() * 4);
     off_tile_list_begin = o; o = align_up(o + host.tile_list_begin.size() * 4);
-    off_rnr = o; o = align_up(o + host.ragged_nonroot.size() * 4);
+    off_rnr = o; o = align_up(o + host.derive_tab.size() * 4);
     off_prof = o; o = align_up(o + 32 * 8);
     off_cap = o; o = align_up(o + host.n_ragged * 8ull);
     off_static_end = o;
@@ -130,7 +130,7 @@ void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParam
   tp.o_prog = o; o = round16(o + sizeof(OpProg) * h.ops.size());
   tp.o_lists = o; o = round16(o + 4ull * h.tile_lists.size());
   tp.o_lbeg = o; o = round16(o + 4ull * h.tile_list_begin.size());
-  tp.o_rnr = o; o = round16(o + 4ull * h.ragged_nonroot.size());
+  tp.o_rnr = o; o = round16(o + 4ull * h.derive_tab.size());
   tp.o_aux = o; o = round16(o + h.aux.size());
   tp.lds_bytes = o;
 }
@@ -317,8 +317,8 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
   if (!h.field_ops.empty()) std::memcpy(img.data() + plan->off_field_ops, h.field_ops.data(), h.field_ops.size() * 4);
   if (!h.tile_lists.empty()) std::memcpy(img.data() + plan->off_tile_lists, h.tile_lists.data(), h.tile_lists.size() * 4);
   std::memcpy(img.data() + plan->off_tile_list_begin, h.tile_list_begin.data(), h.tile_list_begin.size() * 4);
-  if (!h.ragged_nonroot.empty())
-    std::memcpy(img.data() + plan->off_rnr, h.ragged_nonroot.data(), h.ragged_nonroot.size() * 4);
+  if (!h.derive_tab.empty())
+    std::memcpy(img.data() + plan->off_rnr, h.derive_tab.data(), h.derive_tab.size() * 4);
   hipError_t e = hipMemcpy(d_workspace, img.data(), img.size(), hipMemcpyHostToDevice);
   if (e != hipSuccess) return hip_fail(plan, e, "copying plan tables");
   plan->ws = static_cast<uint8_t*>(d_workspace);
@@ -413,7 +413,8 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
       Q.tile_cnt = P.tile_cnt; Q.tile_base = P.tile_base;
       Q.lb_state = nullptr; Q.row_cap = nullptr; Q.row_actual = nullptr;
       Q.n_ops = n_ops; Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged;
-      Q.n_rnr = static_cast<uint32_t>(h.ragged_nonroot.size());
+      Q.n_rnr = h.n_derive;
+      Q.rnr_words = static_cast<uint32_t>(h.derive_tab.size());
       Q.n_lists = static_cast<uint32_t>(h.tile_list_begin.size()) - 1u;
       Q.aux_bytes = static_cast<uint32_t>(h.aux.size());
 
@@ -508,10 +509,12 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
       if (hipMemcpy(pc, ws + plan->off_prof, sizeof(pc), hipMemcpyDeviceToHost) == hipSuccess) {
         for (int k = 0; k < 2; ++k) {
           uint64_t sum = 0;
-          for (int i = 0; i < 16; ++i) sum += pc[16 * k + i];
+          for (int i = 0; i < 13; ++i) sum += pc[16 * k + i];
           fprintf(stderr, "[fbx prof] %s T=%u lds=%u grid-cycles=%llu :", k ? "write" : "count", 1u << g.tp.log2T,
                   g.tp.lds_bytes, (unsigned long long)sum);
           for (int i = 0; i < 13; ++i) fprintf(stderr, " p%d=%.1f%%", i, sum ? 100.0 * pc[16 * k + i] / sum : 0.0);
+          fprintf(stderr, " placements=%llu windows=%llu polls=%llu", (unsigned long long)pc[16 * k + 15],
+                  (unsigned long long)pc[16 * k + 13], (unsigned long long)pc[16 * k + 14]);
           fprintf(stderr, "\n");
         }
       }

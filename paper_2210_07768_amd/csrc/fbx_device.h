@@ -49,7 +49,7 @@ struct TileParams {
   const OpProg* prog;          // [n_ops], per call (absolute addresses)
   const uint32_t* lists;       // work lists (operator indices)
   const uint32_t* list_begin;  // TL_LAYER + 2 * (n_layers - 1) + 1 entries
-  const uint32_t* rnr;         // ragged operators of layers >= 2, spec order
+  const uint32_t* rnr;         // how the counts of the ragged operators of layers >= 2 follow (PlanHost::derive_tab)
   const uint8_t* aux;
   Ctrl* ctrl;
   uint32_t* tile_cnt;          // [n_ragged][n_tiles], written by the counting launch
@@ -57,7 +57,8 @@ struct TileParams {
   uint64_t* lb_state;          // [n_ragged][n_tiles] look-back words (mode 2; shares the tile_base storage)
   const uint64_t* row_cap;     // [n_ragged] signs the arrays were sized for (mode 2)
   uint64_t* row_actual;        // [n_ragged] signs actually produced (mode 2)
-  uint32_t n_ops, n_layers, n_ragged, n_rnr, n_lists, aux_bytes;
+  uint32_t n_ops, n_layers, n_ragged, n_rnr, n_lists, aux_bytes;  // (n_rnr: operators in rnr)
+  uint32_t rnr_words;   // 32-bit words of the rnr table
   uint32_t n_mh;        // multi-valued hashes: the first n_mh entries of the ragged root list
   uint32_t n_tiles, n_fields, n_stage;
   uint32_t grid;        // upper limit of workgroups to launch (0: as many as run at the same time)

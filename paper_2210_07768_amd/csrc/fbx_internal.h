@@ -126,7 +126,13 @@ struct PlanHost {
   std::vector<uint32_t> tile_lists;
   std::vector<uint32_t> tile_list_begin;  // n_tile_lists + 1 entries into tile_lists
   uint32_t n_stage = 0;                   // rows of the on-chip sign table
-  std::vector<uint32_t> ragged_nonroot;   // ragged operators of layers >= 2, spec order
+  // Counts of the ragged operators of layers >= 2 follow from their inputs' counts.  Table of
+  // 32-bit words: a header of 4 * ceil(n_layers / 4) words (word l - 2 = first entry of layer l,
+  // for l = 2 .. n_layers + 1), then four words per operator, layer after layer: row of the
+  // result, input a, input b (a row of the count table, or 0x80000000 | arity for an input
+  // of fixed arity), and 0 for a cross (counts multiply) or 1 for a concat (counts add).
+  std::vector<uint32_t> derive_tab;
+  uint32_t n_derive = 0;                  // operators in derive_tab
 };
 
 // Work lists of the tile kernel.  Layer 1 has four lists; every later layer l

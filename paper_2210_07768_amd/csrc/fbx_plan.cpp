@@ -352,8 +352,24 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
     plan.tile_lists.insert(plan.tile_lists.end(), l.begin(), l.end());
   }
   plan.tile_list_begin.push_back(static_cast<uint32_t>(plan.tile_lists.size()));
-  for (uint32_t i : plan.nonroot_ops)
-    if (plan.ops[i].d.arity == 0) plan.ragged_nonroot.push_back(i);
+  if (plan.n_layers > 1) {
+    const uint32_t hw = 4u * ((plan.n_layers + 3u) / 4u);
+    plan.derive_tab.assign(hw, 0u);
+    for (uint32_t layer = 2; layer <= plan.n_layers; ++layer) {
+      plan.derive_tab[layer - 2] = plan.n_derive;
+      for (uint32_t i : plan.nonroot_ops) {  // (spec order inside a layer)
+        const OpDesc& d = plan.ops[i].d;
+        if (d.arity != 0 || d.layer != layer) continue;
+        auto input = [&](uint32_t in) {
+          const OpDesc& di = plan.ops[in].d;
+          return di.arity ? (0x80000000u | di.arity) : di.rag_row;
+        };
+        plan.derive_tab.insert(plan.derive_tab.end(), {d.rag_row, input(d.a), input(d.b), d.kind == OP_CROSS ? 0u : 1u});
+        ++plan.n_derive;
+      }
+    }
+    plan.derive_tab[plan.n_layers - 1] = plan.n_derive;
+  }
   return FBX_OK;
 }
 

@@ -73,7 +73,12 @@ __shared__ unsigned long long s_prof_last;
     }                                                           \
   } while (0)
 #define FBX_SKIP(bit) (P.dbg & (bit))
+#define FBX_TALLY(n, v)                                         \
+  do {                                                          \
+    if (lane_id() == 0) atomicAdd(&s_prof[n], (unsigned long long)(v)); \
+  } while (0)
 #else
+#define FBX_TALLY(n, v) do {} while (0)
 #define FBX_MARK(n) do {} while (0)
 #define FBX_SKIP(bit) false
 #endif
@@ -169,40 +174,33 @@ struct GlobalSrc {
 };
 
 // ------------------------------------------------------------ splitting
-// 0x80 in exactly the bytes of w that are tabs.
-__device__ __forceinline__ uint32_t tab_flags(uint32_t w) {
-  const uint32_t x = w ^ 0x09090909u;
+// 0x80 in exactly the bytes of w that equal the byte repeated in pat.
+__device__ __forceinline__ uint32_t eq_flags(uint32_t w, uint32_t pat) {
+  const uint32_t x = w ^ pat;
   return ~(((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x | 0x7f7f7f7fu);
 }
+constexpr uint32_t kTabs = 0x09090909u, kCommas = 0x2c2c2c2cu;
 
-// Field table of the staged records.  kTileThreads / T lanes (at most 64) share a
-// record: each takes an equal run of its 16-byte chunks, counts its tabs, a
-// prefix sum over the group turns the counts into field numbers, and a second
-// walk writes the positions.  Entries from the record's tab count on hold the
-// record's end.
-__device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
-  const uint32_t tid = threadIdx.x;
-  constexpr uint32_t kLogThreads = kTileThreads == 1024 ? 10u : (kTileThreads == 512 ? 9u : 8u);
-  const uint32_t lg = kLogThreads - P.log2T < 6u ? kLogThreads - P.log2T : 6u;  // log2 of the lanes per record
+// 1 << lg neighbouring lanes of a wavefront (j = 0 .. (1 << lg) - 1) split the staged
+// bytes [rs, re) at every delimiter (pat: the delimiter in all four bytes).  Each lane
+// takes an equal run of the 16-byte chunks that cover the range and counts its
+// delimiters; a prefix sum over the group turns the counts into ordinals, and a second
+// walk calls emit(k, position) for the k-th delimiter.  Returns the number of delimiters
+// in the whole range.  Every lane of the wavefront calls it; those with act == false
+// (and, with positions == false, all of them) emit nothing.
+template <class Emit>
+__device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs, uint32_t re, bool act, uint32_t pat,
+                                                uint32_t lg, uint32_t j, bool positions, Emit&& emit) {
   const uint32_t gsz = 1u << lg;
-  const uint32_t j = tid & (gsz - 1u);
-  const uint32_t r = tid >> lg;
-  const uint32_t F = P.n_fields;
-  const bool act = r < nb;
-  uint32_t rs = 0, re = 0;
-  if (act) {
-    rs = sh.rs[r]; re = sh.re[r];
-    if (re > rs && sh.raw[re - 1u] == '\n') --re;  // one trailing newline is not part of the record
-  }
   const uint32_t ab = rs & ~15u;
-  const uint32_t nc = (act && re > rs) ? (re - ab + 15u) >> 4 : 0u;  // 16-byte chunks that cover the record
+  const uint32_t nc = (act && re > rs) ? (re - ab + 15u) >> 4 : 0u;  // 16-byte chunks that cover the range
   const uint32_t c = (nc + gsz - 1u) >> lg;                          // chunks per lane
   const uint32_t c0 = min(j * c, nc), c1 = min(c0 + c, nc);
-  // tab flags of the four dwords of chunk ci, bytes outside the record masked off
+  // delimiter flags of the four dwords of chunk ci, bytes outside the range masked off
   auto chunk_flags = [&](uint32_t ci, uint32_t (&f)[4]) {
     const uint32_t cp = ab + 16u * ci;
-    const u32x4 w = *reinterpret_cast<const u32x4*>(sh.raw + cp);
-    f[0] = tab_flags(w.x); f[1] = tab_flags(w.y); f[2] = tab_flags(w.z); f[3] = tab_flags(w.w);
+    const u32x4 w = *reinterpret_cast<const u32x4*>(raw + cp);
+    f[0] = eq_flags(w.x, pat); f[1] = eq_flags(w.y, pat); f[2] = eq_flags(w.z, pat); f[3] = eq_flags(w.w, pat);
     if (cp < rs || cp + 16u > re) {
 #pragma unroll
       for (uint32_t i = 0; i < 4; ++i) {
@@ -216,7 +214,7 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
     }
   };
   // A lane with at most four chunks (the usual case) keeps one bit per byte: bit i of (mhi:mlo)
-  // is set when byte i of its run is a tab.  The second walk then needs no memory at all.
+  // is set when byte i of its run is a delimiter.  The second walk then needs no memory at all.
   const bool few = c <= 4u;
   uint32_t mlo = 0, mhi = 0, cnt = 0;
   if (few) {
@@ -251,9 +249,8 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
     if (j >= s) incl += t;
   }
   const uint32_t total = __shfl(incl, (int)(lane_id() | (gsz - 1u)), 64);
-  if (!act) return;
+  if (!act || !positions) return total;
   uint32_t k = incl - cnt;
-  uint16_t* row = sh.rows + r * P.row_stride;
   if (few) {
     uint32_t base = ab + 16u * c0;
     uint32_t m = mlo;
@@ -261,7 +258,7 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
     for (uint32_t half = 0; half < 2; ++half) {
       while (m) {
         const uint32_t i = (uint32_t)__ffs((int)m) - 1u;
-        if (k < F) row[1u + k] = (uint16_t)(base + i);
+        emit(k, base + i);
         ++k;
         m &= m - 1u;
       }
@@ -269,26 +266,51 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
       base += 32u;
     }
   } else {
-    // second walk of a long run: from tab to tab.  A window of eight bytes at the current
-    // position (any alignment) shows the next tab, so every lane places one tab per turn.
-    const uint32_t* raw32 = reinterpret_cast<const uint32_t*>(sh.raw);
+    // second walk of a long run: from delimiter to delimiter.  A window of eight bytes at the
+    // current position (any alignment) shows the next one, so every lane places one per turn.
+    const uint32_t* raw32 = reinterpret_cast<const uint32_t*>(raw);
     const uint32_t be = min(re, ab + 16u * c1);
     uint32_t p = max(rs, ab + 16u * c0);
     while (p < be) {
       const uint32_t a = p >> 2, sh8 = (p & 3u) * 8u;
       const uint32_t w0 = raw32[a], w1 = raw32[a + 1], w2 = raw32[a + 2];
-      const uint32_t f0 = tab_flags(__builtin_amdgcn_alignbit(w1, w0, sh8));
-      const uint32_t f1 = tab_flags(__builtin_amdgcn_alignbit(w2, w1, sh8));
+      const uint32_t f0 = eq_flags(__builtin_amdgcn_alignbit(w1, w0, sh8), pat);
+      const uint32_t f1 = eq_flags(__builtin_amdgcn_alignbit(w2, w1, sh8), pat);
       const uint32_t i0 = ((uint32_t)__ffs((int)f0) - 1u) >> 3, i1 = 4u + (((uint32_t)__ffs((int)f1) - 1u) >> 3);
       const uint32_t idx = f0 ? i0 : (f1 ? i1 : 8u);
       p += idx;
       if (idx < 8u && p < be) {
-        if (k < F) row[1u + k] = (uint16_t)p;
+        emit(k, p);
         ++k;
         ++p;
       }
     }
   }
+  return total;
+}
+
+// Field table of the staged records.  kTileThreads / T lanes (at most 64) share a
+// record and place its tabs.  Entries from the record's tab count on hold the
+// record's end.
+__device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
+  const uint32_t tid = threadIdx.x;
+  constexpr uint32_t kLogThreads = kTileThreads == 1024 ? 10u : (kTileThreads == 512 ? 9u : 8u);
+  const uint32_t lg = kLogThreads - P.log2T < 6u ? kLogThreads - P.log2T : 6u;  // log2 of the lanes per record
+  const uint32_t gsz = 1u << lg;
+  const uint32_t j = tid & (gsz - 1u);
+  const uint32_t r = tid >> lg;
+  const uint32_t F = P.n_fields;
+  const bool act = r < nb;
+  uint32_t rs = 0, re = 0;
+  if (act) {
+    rs = sh.rs[r]; re = sh.re[r];
+    if (re > rs && sh.raw[re - 1u] == '\n') --re;  // one trailing newline is not part of the record
+  }
+  uint16_t* row = sh.rows + r * P.row_stride;
+  const uint32_t total = split_bytes(sh.raw, rs, re, act, kTabs, lg, j, true, [&](uint32_t k, uint32_t pos) {
+    if (k < F) row[1u + k] = (uint16_t)pos;
+  });
+  if (!act) return;
   if (j == 0) row[0] = (uint16_t)(rs - 1u);
   for (uint32_t kk = total + j; kk < F; kk += gsz) row[1u + kk] = (uint16_t)re;
 }
@@ -516,11 +538,11 @@ constexpr uint32_t kWaves = kTileThreads / 64;
 
 // Work counters of a pass (cleared between passes): s_ctr[0] hands out the
 // single-valued hash / bucket units of layer 1, which fill every phase that has
-// idle wavefronts; s_ctr[1] the counting units, s_ctr[2] the derivation,
-// s_ctr[3] the ragged root units, s_ctr[4 + (l & 1)] the single crosses of layer l,
-// s_ctr[6] the placement units, s_ctr[7 + (l & 1)] the list operators of layer l.  s_done[0..2]: finished units of the counting, the
-// derivation and the placement phase.
-__shared__ uint32_t s_ctr[9];
+// idle wavefronts; s_ctr[1] the counting units, s_ctr[3] the ragged root units,
+// s_ctr[4 + (l & 1)] the single crosses of layer l, s_ctr[7 + (l & 1)] its list operators,
+// s_ctr[9 + (l & 1)] the derivation of its counts.  s_done[0]: finished counting units,
+// s_done[1 + (l & 1)]: finished derivation units of layer l.
+__shared__ uint32_t s_ctr[11];
 __shared__ uint32_t s_done[3];
 __shared__ uint32_t s_good;   // MODE 2: the tile's bases are known and inside the arrays
 
@@ -569,11 +591,55 @@ struct Pass {
     return i < m ? &sh.prog[sh.lists[lb + i]] : nullptr;
   }
 
-  // ---- counts of the ragged root operators (lists TL_RAGROOT, TL_NGRAM, taken as one)
-  __device__ __forceinline__ uint32_t count_units() const { return units_of(TL_RAGROOT) + units_of(TL_NGRAM); }
+  // ---- counts of the ragged root operators
+  // Multi-valued hashes of staged records (the first P.n_mh entries of the ragged root list):
+  // every wavefront takes part.  A few neighbouring lanes share one (operator, record) and
+  // split the field at its commas: the item count, and the first item_cap comma positions
+  // for the lanes that later hash the items.
+  __device__ __forceinline__ void split_items() {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t np = P.n_mh * T;  // (operator, record slot) pairs
+    uint32_t lg = 0;                 // log2 of the lanes per pair
+    while (lg < 6u && (np << (lg + 1u)) <= kTileThreads) ++lg;
+    const uint32_t j = tid & ((1u << lg) - 1u);
+    for (uint32_t p0 = 0; p0 < np; p0 += kTileThreads >> lg) {
+      const uint32_t pr = p0 + (tid >> lg);
+      const uint32_t i = pr / T, rr = pr & (T - 1u);
+      const bool act = pr < np && rr < nb;
+      uint32_t s = 0, e = 0, row = 0;
+      if (act) {
+        const OpProg& d = sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]];
+        src.span(rr, d.field, s, e);
+        row = d.rag_row;
+      } else if (pr < np) {
+        row = sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]].rag_row;
+      }
+      uint16_t* tab = sh.ctab + pr * P.item_cap;
+      const uint32_t cap = P.item_cap;
+      const uint32_t commas = split_bytes(src.raw8, s, e, act, kCommas, lg, j, need_table, [&](uint32_t k, uint32_t pos) {
+        if (k < cap) tab[k] = (uint16_t)pos;
+      });
+      if (pr < np && j == 0) sh.cnt[row * T + rr] = act ? commas + 1u : 0u;  // items = commas + 1 (far below kMaxCount)
+    }
+  }
+  // The other ragged root operators and the n-grams (lists TL_RAGROOT and TL_NGRAM, taken as
+  // one), G operators per unit; records read in place count their multi-valued hashes here too.
+  __device__ __forceinline__ uint32_t count_skip() const { return Src::kTable ? P.n_mh : 0u; }
+  __device__ __forceinline__ uint32_t count_root_units() const {
+    return (sh.list_begin[TL_RAGROOT + 1] - sh.list_begin[TL_RAGROOT] - count_skip() + G - 1u) / G;
+  }
+  __device__ __forceinline__ uint32_t count_units() const { return count_root_units() + units_of(TL_NGRAM); }
   __device__ __forceinline__ void count_unit(uint32_t u) {
-    const uint32_t ur = units_of(TL_RAGROOT);
-    const OpProg* d = u < ur ? op_of(TL_RAGROOT, u) : op_of(TL_NGRAM, u - ur);
+    const uint32_t ur = count_root_units();
+    const OpProg* d;
+    uint32_t i = 0;  // position in the ragged root list
+    if (u < ur) {
+      const uint32_t lb = sh.list_begin[TL_RAGROOT], m = sh.list_begin[TL_RAGROOT + 1] - lb;
+      i = count_skip() + u * G + og;
+      d = i < m ? &sh.prog[sh.lists[lb + i]] : nullptr;
+    } else {
+      d = op_of(TL_NGRAM, u - ur);
+    }
     if (!d) return;
     uint32_t c = 0;
     if (live) {
@@ -585,7 +651,6 @@ struct Pass {
         c = count_commas(src, s, e) + 1u;  // counting launch: nobody reads the comma table
       } else if (d->kind == OP_HASH) {
         // multi-valued hash: from comma to comma; the first item_cap positions are kept for the item lanes
-        const uint32_t i = u * G + og;  // hashes lead the ragged root list
         uint16_t* tab = sh.ctab + (i * T + r) * P.item_cap;
         uint32_t p = s;
         for (;;) {
@@ -604,23 +669,21 @@ struct Pass {
     sh.cnt[d->rag_row * T + r] = c;
   }
 
-  // Counts of the later layers follow from the inputs' counts, record by record,
-  // in spec order.  One wavefront does it (its LDS traffic stays in order).
-  __device__ __forceinline__ void derive() {
-    const uint32_t lane = lane_id();
-    if (lane < T) {
-      for (uint32_t k = 0; k < P.n_rnr; ++k) {
-        const OpProg& d = sh.prog[sh.rnr[k]];
-        const OpProg& da = sh.prog[d.a];
-        const OpProg& db = sh.prog[d.b];
-        const uint64_t ca = da.arity ? da.arity : sh.cnt[da.rag_row * T + lane];
-        const uint64_t cb = db.arity ? db.arity : sh.cnt[db.rag_row * T + lane];
-        const uint64_t c = d.kind == OP_CROSS ? ca * cb : ca + cb;
-        if (c > kMaxCount) overflow = true;
-        sh.cnt[d.rag_row * T + lane] = lane < nb ? (uint32_t)c : 0u;
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-      }
-    }
+  // Counts of the later layers follow from the inputs' counts, record by record and layer
+  // by layer (the operators of one layer do not depend on each other): G operators per unit.
+  __device__ __forceinline__ uint32_t derive_units(uint32_t layer) const {
+    return (sh.rnr[layer - 1u] - sh.rnr[layer - 2u] + G - 1u) / G;
+  }
+  __device__ __forceinline__ void derive_unit(uint32_t layer, uint32_t u) {
+    const uint32_t i = sh.rnr[layer - 2u] + u * G + og;
+    if (i >= sh.rnr[layer - 1u]) return;
+    const uint32_t header = 4u * ((P.n_layers + 3u) >> 2);
+    const u32x4 d = *reinterpret_cast<const u32x4*>(sh.rnr + header + 4u * i);  // result row, a, b, cross or concat
+    const uint64_t ca = (d.y >> 31) ? (d.y & 0x7fffffffu) : sh.cnt[d.y * T + r];
+    const uint64_t cb = (d.z >> 31) ? (d.z & 0x7fffffffu) : sh.cnt[d.z * T + r];
+    const uint64_t c = d.w == 0u ? ca * cb : ca + cb;
+    if (c > kMaxCount) overflow = true;
+    sh.cnt[d.x * T + r] = live ? (uint32_t)c : 0u;
   }
   // Counts become positions inside the tile: a prefix sum over the records of G rows at a time.
   __device__ __forceinline__ uint32_t scan_units() const { return (P.n_ragged + G - 1u) / G; }
@@ -861,23 +924,33 @@ __device__ __forceinline__ void lb_abort_tile(const TileParams& P, uint32_t tile
     lb_store(P.lb_state + (uint64_t)row * P.n_tiles + tile, kLbAbort);
 }
 
+// The words of the 64 tiles below `upper` of one ragged operator, lane 0 the nearest;
+// in front of tile 0 lies a prefix of zero.
+__device__ __forceinline__ uint64_t lb_window(const TileParams& P, uint32_t row, uint32_t upper) {
+  const uint32_t lane = lane_id();
+  return upper > lane ? lb_load(P.lb_state + (uint64_t)row * P.n_tiles + (upper - 1u - lane)) : kLbPrefix;
+}
+
 // One wavefront finds the base of one ragged operator for this tile (whose count is
-// already published).  Returns false (in every lane) when the tile must not be written.
-__device__ __forceinline__ bool lb_place_row(const TileParams& P, const Sh& sh, uint32_t tile, uint32_t row) {
+// already published).  `v` is the window right below the tile, requested by the caller
+// (who requests those of several operators at once, so that their latencies overlap).
+// Returns false (in every lane) when the tile must not be written.
+__device__ __forceinline__ bool lb_place_row(const TileParams& P, const Sh& sh, uint32_t tile, uint32_t row, uint64_t v) {
   const uint32_t lane = lane_id();
   uint64_t* st = P.lb_state + (uint64_t)row * P.n_tiles;
   const uint64_t agg = sh.tot[row];
   uint64_t excl = 0;
   bool abort = false;
-  uint32_t upper = tile, spins = 0;  // the window is the 64 tiles below `upper`, lane 0 the nearest
-  for (;;) {
-    const bool inside = upper > lane;  // in front of tile 0 lies a prefix of zero
-    const uint64_t v = inside ? lb_load(st + (upper - 1u - lane)) : kLbPrefix;
+  uint32_t upper = tile, spins = 0;
+  FBX_TALLY(15, 1);  // (tuning builds: placements, windows read, polls of an unfinished tile)
+  for (;; v = lb_window(P, row, upper)) {
+    FBX_TALLY(13, 1);
     const uint64_t flag = v & ~kLbValue;
     const uint64_t stops = __ballot(flag == kLbPrefix || flag == kLbAbort);
     const uint32_t stop = stops ? (uint32_t)__ffsll((unsigned long long)stops) - 1u : 64u;
     const uint64_t below = stop == 64u ? ~0ull : ((1ull << stop) - 1ull);
     if (__ballot(flag == 0ull) & below) {  // a tile in between has not counted yet
+      FBX_TALLY(14, 1);
       if (++spins > kSpinLimit) {
         if (lane == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_STALL);
         abort = true;
@@ -949,15 +1022,25 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
 
   // ---- phase A: counts of the ragged root operators
   bool absurd = false;
+  if constexpr (Src::kTable) {
+    if (P.n_mh) ps.split_items();
+  }
   if (P.n_ragged) absurd = critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], !P.n_rnr, [&](uint32_t u) { ps.count_unit(u); });
   else __syncthreads();
   FBX_MARK(4);
   hook();
-  // ---- phase B: one wavefront derives the counts of later layers
+  // ---- phase B: the counts of later layers, layer by layer
   if (P.n_rnr) {
-    absurd = critical_phase(1u, &s_ctr[2], &s_done[1], true, [&](uint32_t) { ps.derive(); });
+    for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
+      if (tid == 0) {  // the next layer's counters (idle since the barrier before this one)
+        s_ctr[9u + ((layer + 1u) & 1u)] = 0;
+        s_done[1u + ((layer + 1u) & 1u)] = 0;
+      }
+      absurd = critical_phase(ps.derive_units(layer), &s_ctr[9u + (layer & 1u)], &s_done[1u + (layer & 1u)],
+                              layer == P.n_layers, [&](uint32_t u) { ps.derive_unit(layer, u); });
+      hook();
+    }
     FBX_MARK(5);
-    hook();
   }
   if (MODE == 2 && absurd) {  // absurd counts: nothing of this tile may be placed
     lb_abort_tile(P, tile);
@@ -996,9 +1079,21 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // ---- one-launch mode: the tile's bases come from the tiles before it.  This is as late as
   // it can be: the count went out long ago, so the tiles before this one have had time to count.
   if (MODE == 2) {
-    critical_phase(P.n_ragged, &s_ctr[6], &s_done[2], false, [&](uint32_t row) {
-      if (!lb_place_row(P, sh, tile, row) && lane == 0) s_good = 0u;
-    });
+    constexpr uint32_t kRows = 4;  // operators a wavefront looks back for at the same time
+    for (uint32_t row0 = wave; row0 < P.n_ragged; row0 += kRows * kWaves) {
+      uint64_t v[kRows];
+#pragma unroll
+      for (uint32_t k = 0; k < kRows; ++k) {
+        const uint32_t row = row0 + k * kWaves;
+        v[k] = row < P.n_ragged ? lb_window(P, row, tile) : kLbPrefix;
+      }
+#pragma unroll
+      for (uint32_t k = 0; k < kRows; ++k) {
+        const uint32_t row = row0 + k * kWaves;
+        if (row < P.n_ragged && !lb_place_row(P, sh, tile, row, v[k]) && lane == 0) s_good = 0u;
+      }
+    }
+    __syncthreads();
     FBX_MARK(9);
     if (!s_good) return;  // the call fails or falls back: leave the arrays alone
   } else if (P.n_mh) {
@@ -1079,7 +1174,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   copy_table(smem + P.o_prog, P.prog, P.n_ops * (uint32_t)sizeof(OpProg));
   copy_table(smem + P.o_lists, P.lists, P.n_ops * 4u);
   copy_table(smem + P.o_lbeg, P.list_begin, (P.n_lists + 1u) * 4u);
-  copy_table(smem + P.o_rnr, P.rnr, P.n_rnr * 4u);
+  copy_table(smem + P.o_rnr, P.rnr, P.rnr_words * 4u);
   copy_table(smem + P.o_aux, P.aux, P.aux_bytes);
 #ifdef FBX_TILE_PROF
   if (tid < 16) s_prof[tid] = 0;
@@ -1112,9 +1207,9 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       sh.run[row] = 0;
       if (MODE == 1) sh.base[row] = gptr(P.tile_base)[(uint64_t)row * P.n_tiles + tile];
     }
-    if (tid < 9) s_ctr[tid] = 0;
-    if (tid >= 9 && tid < 12) s_done[tid - 9] = 0;
-    if (tid == 12) s_good = 1u;
+    if (tid < 11) s_ctr[tid] = 0;
+    if (tid >= 11 && tid < 14) s_done[tid - 11] = 0;
+    if (tid == 14) s_good = 1u;
     bool nrec_ok = true;
     uint32_t bad = 0;
     if (tid < nrec) {
@@ -1218,9 +1313,9 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
         r0 += 1u;
       }
       __syncthreads();  // the sections are reused by the next pass
-      if (tid < 9) s_ctr[tid] = 0;
-      if (tid >= 9 && tid < 12) s_done[tid - 9] = 0;
-      if (tid == 12) s_good = 1u;
+      if (tid < 11) s_ctr[tid] = 0;
+      if (tid >= 11 && tid < 14) s_done[tid - 11] = 0;
+      if (tid == 14) s_good = 1u;
       FBX_MARK(11);
     }
     if (!WRITE) {
