@@ -196,22 +196,17 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
   const uint32_t nc = (act && re > rs) ? (re - ab + 15u) >> 4 : 0u;  // 16-byte chunks that cover the range
   const uint32_t c = (nc + gsz - 1u) >> lg;                          // chunks per lane
   const uint32_t c0 = min(j * c, nc), c1 = min(c0 + c, nc);
-  // delimiter flags of the four dwords of chunk ci, bytes outside the range masked off
-  auto chunk_flags = [&](uint32_t ci, uint32_t (&f)[4]) {
+  // one bit per byte of chunk ci: set where the byte is a delimiter inside the range
+  auto chunk_bits = [&](uint32_t ci) -> uint32_t {
     const uint32_t cp = ab + 16u * ci;
     const u32x4 w = *reinterpret_cast<const u32x4*>(raw + cp);
-    f[0] = eq_flags(w.x, pat); f[1] = eq_flags(w.y, pat); f[2] = eq_flags(w.z, pat); f[3] = eq_flags(w.w, pat);
-    if (cp < rs || cp + 16u > re) {
-#pragma unroll
-      for (uint32_t i = 0; i < 4; ++i) {
-        const uint32_t pos = cp + 4u * i;
-        const uint32_t lo = rs > pos ? rs - pos : 0u;  // valid bytes of the dword: [lo, hi)
-        const uint32_t hi = re > pos ? re - pos : 0u;
-        uint32_t m = (lo >= 4u || hi == 0u) ? 0u : (0xffffffffu << (8u * lo));
-        if (hi < 4u) m &= (1u << (8u * hi)) - 1u;
-        f[i] &= m;
-      }
-    }
+    // flag bytes (0x80 or 0) -> bits, four dwords -> sixteen bits
+    uint32_t lo8 = __builtin_amdgcn_udot4(eq_flags(w.x, pat) >> 7, 0x08040201u, 0u, false);
+    lo8 = __builtin_amdgcn_udot4(eq_flags(w.y, pat) >> 7, 0x80402010u, lo8, false);
+    uint32_t hi8 = __builtin_amdgcn_udot4(eq_flags(w.z, pat) >> 7, 0x08040201u, 0u, false);
+    hi8 = __builtin_amdgcn_udot4(eq_flags(w.w, pat) >> 7, 0x80402010u, hi8, false);
+    const uint32_t lo = rs > cp ? rs - cp : 0u, hi = min(re - cp, 16u);  // the chunk's bytes [lo, hi) are in the range
+    return (lo8 | (hi8 << 8)) & (((1u << (hi - lo)) - 1u) << lo);
   };
   // A lane with at most four chunks (the usual case) keeps one bit per byte: bit i of (mhi:mlo)
   // is set when byte i of its run is a delimiter.  The second walk then needs no memory at all.
@@ -221,14 +216,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
 #pragma unroll
     for (uint32_t q = 0; q < 4; ++q) {
       if (c0 + q < c1) {
-        uint32_t f[4];
-        chunk_flags(c0 + q, f);
-        // flag bytes (0x80 or 0) -> bits, four dwords -> sixteen bits
-        uint32_t lo8 = __builtin_amdgcn_udot4(f[0] >> 7, 0x08040201u, 0u, false);
-        lo8 = __builtin_amdgcn_udot4(f[1] >> 7, 0x80402010u, lo8, false);
-        uint32_t hi8 = __builtin_amdgcn_udot4(f[2] >> 7, 0x08040201u, 0u, false);
-        hi8 = __builtin_amdgcn_udot4(f[3] >> 7, 0x80402010u, hi8, false);
-        const uint32_t m16 = lo8 | (hi8 << 8);
+        const uint32_t m16 = chunk_bits(c0 + q);
         if (q == 0) mlo = m16;
         else if (q == 1) mlo |= m16 << 16;
         else if (q == 2) mhi = m16;
@@ -237,11 +225,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
     }
     cnt = __popc(mlo) + __popc(mhi);
   } else {
-    for (uint32_t ci = c0; ci < c1; ++ci) {
-      uint32_t f[4];
-      chunk_flags(ci, f);
-      cnt += __popc(f[0]) + __popc(f[1]) + __popc(f[2]) + __popc(f[3]);
-    }
+    for (uint32_t ci = c0; ci < c1; ++ci) cnt += __popc(chunk_bits(ci));
   }
   uint32_t incl = cnt;
   for (uint32_t s = 1; s < gsz; s <<= 1) {
@@ -1285,8 +1269,14 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
         const uint32_t nb = r1 - r0;
         const uint32_t nchunks = (delta + (uint32_t)(off[r1] - o0) + 15u) >> 4;
         const uintptr_t a0 = addr0 - delta;
-        for (uint32_t c = tid; c < nchunks; c += kTileThreads)
-          *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
+        if (a0 >= ok_lo && a0 + 16ull * nchunks <= ok_hi) {  // whole chunks (all but the ends of the caller's buffer)
+          const FBX_GLOBAL u32x4* from = gptr<const u32x4>((uint64_t)a0);
+          for (uint32_t c = tid; c < nchunks; c += kTileThreads)
+            *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = from[c];
+        } else {
+          for (uint32_t c = tid; c < nchunks; c += kTileThreads)
+            *reinterpret_cast<u32x4*>(sh.raw + kRawPad + 16u * c) = load_chunk(a0 + 16u * c, ok_lo, ok_hi);
+        }
         if (tid < nb) {
           sh.rs[tid] = kRawPad + delta + (uint32_t)(off[r0 + tid] - o0);
           sh.re[tid] = kRawPad + delta + (uint32_t)(off[r0 + tid + 1] - o0);
