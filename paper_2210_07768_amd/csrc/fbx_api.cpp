@@ -128,7 +128,6 @@ void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParam
   tp.item_cap = 16;
   tp.o_ctab = o; o = round16(o + 2ull * tp.n_mh * T * tp.item_cap);
   tp.o_prog = o; o = round16(o + sizeof(OpProg) * h.ops.size());
-  tp.o_lists = o; o = round16(o + 4ull * h.tile_lists.size());
   tp.o_lbeg = o; o = round16(o + 4ull * h.tile_list_begin.size());
   tp.o_rnr = o; o = round16(o + 4ull * h.derive_tab.size());
   tp.o_aux = o; o = round16(o + h.aux.size());

@@ -47,7 +47,7 @@ struct TileParams {
   const uint64_t* rec_off;
   uint64_t n_records;
   const OpProg* prog;          // [n_ops], per call (absolute addresses)
-  const uint32_t* lists;       // work lists (operator indices)
+  const uint32_t* lists;       // work lists (operator indices, n_ops in all), then each operator's position in them
   const uint32_t* list_begin;  // TL_LAYER + 2 * (n_layers - 1) + 1 entries
   const uint32_t* rnr;         // how the counts of the ragged operators of layers >= 2 follow (PlanHost::derive_tab)
   const uint8_t* aux;
@@ -67,7 +67,7 @@ struct TileParams {
   uint32_t row_stride;  // u16 entries per record in the field table (n_fields + 1, padded)
   // byte offsets of the LDS sections
   uint32_t o_off, o_rs, o_re, o_rows, o_raw, o_stage, o_cnt, o_start, o_run, o_base;
-  uint32_t o_prog, o_lists, o_lbeg, o_rnr, o_aux;  // plan tables
+  uint32_t o_prog, o_lbeg, o_rnr, o_aux;  // plan tables
   uint32_t o_tot, o_ioff, o_ctab;
   uint32_t item_cap;    // comma positions kept per record and multi-valued hash
   uint32_t lds_bytes;

@@ -123,7 +123,8 @@ struct PlanHost {
   uint32_t count_fields = 0;           // the counting pass may stop after this many fields
   // Work lists of the tile kernel: operator indices grouped by how a tile of
   // records runs them.  List ids: see TileList.
-  std::vector<uint32_t> tile_lists;
+  std::vector<uint32_t> tile_lists;       // the lists one after the other (n_ops entries), then for every
+                                          // operator its position in that sequence (n_ops entries)
   std::vector<uint32_t> tile_list_begin;  // n_tile_lists + 1 entries into tile_lists
   uint32_t n_stage = 0;                   // rows of the on-chip sign table
   // Counts of the ragged operators of layers >= 2 follow from their inputs' counts.  Table of

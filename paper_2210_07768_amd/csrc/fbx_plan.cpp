@@ -352,6 +352,11 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
     plan.tile_lists.insert(plan.tile_lists.end(), l.begin(), l.end());
   }
   plan.tile_list_begin.push_back(static_cast<uint32_t>(plan.tile_lists.size()));
+  {  // every operator is in exactly one list: append where each one went
+    const size_t n = plan.ops.size();
+    plan.tile_lists.resize(2 * n);
+    for (uint32_t pos = 0; pos < n; ++pos) plan.tile_lists[n + plan.tile_lists[pos]] = pos;
+  }
   if (plan.n_layers > 1) {
     const uint32_t hw = 4u * ((plan.n_layers + 3u) / 4u);
     plan.derive_tab.assign(hw, 0u);

@@ -107,10 +107,9 @@ struct Sh {
   uint32_t* ioff;   // [n_mh + 1] first item of every multi-valued hash among the pass's items
   uint16_t* ctab;   // [n_mh][T][item_cap] comma positions of the multi-valued hash fields
   // plan tables, copied once per workgroup so that no lane waits on memory for a descriptor
-  const OpProg* prog;          // [n_ops]
-  const uint32_t* lists;       // work lists (operator indices)
+  const OpProg* prog;          // [n_ops], in the order of the work lists
   const uint32_t* list_begin;
-  const uint32_t* rnr;         // ragged operators of layers >= 2, spec order
+  const uint32_t* rnr;         // how the counts of the ragged operators of layers >= 2 follow from their inputs'
   const uint8_t* aux;          // bucket boundaries and filter prefixes
 };
 
@@ -130,7 +129,6 @@ __device__ __forceinline__ Sh views(const TileParams& P) {
   s.ioff = reinterpret_cast<uint32_t*>(smem + P.o_ioff);
   s.ctab = reinterpret_cast<uint16_t*>(smem + P.o_ctab);
   s.prog = reinterpret_cast<const OpProg*>(smem + P.o_prog);
-  s.lists = reinterpret_cast<const uint32_t*>(smem + P.o_lists);
   s.list_begin = reinterpret_cast<const uint32_t*>(smem + P.o_lbeg);
   s.rnr = reinterpret_cast<const uint32_t*>(smem + P.o_rnr);
   s.aux = smem + P.o_aux;
@@ -536,6 +534,18 @@ __device__ __forceinline__ uint32_t grab_unit(uint32_t* ctr) {
   if (lane_id() == 0) u = atomicAdd(ctr, 1u);
   return __builtin_amdgcn_readfirstlane(u);
 }
+// Runs unit(u) for the units a wavefront gets of a phase with `total` units.  The next
+// unit is asked for before the current one runs, so that the answer is there when needed.
+template <class F>
+__device__ __forceinline__ void for_units(uint32_t* ctr, uint32_t total, F&& unit) {
+  uint32_t u = grab_unit(ctr);
+  while (u < total) {
+    uint32_t next = 0;
+    if (lane_id() == 0) next = atomicAdd(ctr, 1u);
+    unit(u);
+    u = __builtin_amdgcn_readfirstlane(next);
+  }
+}
 
 // flag bits and helpers of the one-launch placement (see lb_place_row)
 constexpr uint64_t kLbAggregate = 1ull << 62, kLbPrefix = 2ull << 62, kLbAbort = 3ull << 62;
@@ -572,7 +582,7 @@ struct Pass {
   __device__ __forceinline__ const OpProg* op_of(uint32_t list, uint32_t u) const {
     const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
     const uint32_t i = u * G + og;
-    return i < m ? &sh.prog[sh.lists[lb + i]] : nullptr;
+    return i < m ? &sh.prog[lb + i] : nullptr;
   }
 
   // ---- counts of the ragged root operators
@@ -592,11 +602,11 @@ struct Pass {
       const bool act = pr < np && rr < nb;
       uint32_t s = 0, e = 0, row = 0;
       if (act) {
-        const OpProg& d = sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]];
+        const OpProg& d = sh.prog[sh.list_begin[TL_RAGROOT] + i];
         src.span(rr, d.field, s, e);
         row = d.rag_row;
       } else if (pr < np) {
-        row = sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]].rag_row;
+        row = sh.prog[sh.list_begin[TL_RAGROOT] + i].rag_row;
       }
       uint16_t* tab = sh.ctab + pr * P.item_cap;
       const uint32_t cap = P.item_cap;
@@ -620,7 +630,7 @@ struct Pass {
     if (u < ur) {
       const uint32_t lb = sh.list_begin[TL_RAGROOT], m = sh.list_begin[TL_RAGROOT + 1] - lb;
       i = count_skip() + u * G + og;
-      d = i < m ? &sh.prog[sh.lists[lb + i]] : nullptr;
+      d = i < m ? &sh.prog[lb + i] : nullptr;
     } else {
       d = op_of(TL_NGRAM, u - ur);
     }
@@ -726,7 +736,7 @@ struct Pass {
   __device__ __forceinline__ void other_unit(uint32_t u) {
     const uint32_t lb = sh.list_begin[TL_RAGROOT] + P.n_mh, m = sh.list_begin[TL_RAGROOT + 1] - lb;
     const uint32_t i = u * G + og;
-    const OpProg* d = i < m ? &sh.prog[sh.lists[lb + i]] : nullptr;
+    const OpProg* d = i < m ? &sh.prog[lb + i] : nullptr;
     if (!d || !live) return;
     const uint64_t first = place(*d, r, g);
     uint32_t s, e;
@@ -744,7 +754,7 @@ struct Pass {
     for (uint32_t i0 = 0; i0 < P.n_mh; i0 += 64u) {
       const uint32_t i = i0 + lane;
       uint32_t v = 0;
-      if (i < P.n_mh) v = sh.tot[sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]].rag_row];
+      if (i < P.n_mh) v = sh.tot[sh.prog[sh.list_begin[TL_RAGROOT] + i].rag_row];
       uint32_t incl = v;
       for (uint32_t d = 1; d < 64u; d <<= 1) {
         const uint32_t t = __shfl_up(incl, d, 64);
@@ -767,7 +777,7 @@ struct Pass {
       if (sh.ioff[mid] <= q) lo = mid; else hi = mid - 1u;
     }
     const uint32_t i = lo;
-    const OpProg& d = sh.prog[sh.lists[sh.list_begin[TL_RAGROOT] + i]];
+    const OpProg& d = sh.prog[sh.list_begin[TL_RAGROOT] + i];
     const uint32_t row = d.rag_row;
     const uint32_t before = sh.run[row] - sh.tot[row];     // signs of the tile's earlier passes
     const uint32_t pos = before + (q - sh.ioff[i]);         // the item's position inside the tile
@@ -811,7 +821,7 @@ struct Pass {
   }
   __device__ __forceinline__ void ngram_unit(uint32_t u) {
     const uint32_t lane = lane_id();
-    const OpProg& d = sh.prog[sh.lists[sh.list_begin[TL_NGRAM] + u / nb]];
+    const OpProg& d = sh.prog[sh.list_begin[TL_NGRAM] + u / nb];
     const uint32_t rr = u % nb;
     uint32_t s, e;
     src.span(rr, d.field, s, e);
@@ -1043,7 +1053,10 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // ---- phase C: the rest of layer 1's single signs; one wavefront first lays out the item
   // index space of the multi-valued hashes (needed after at least one more barrier)
   if (P.n_mh && wave == kWaves - 1) ps.item_offsets();
-  while (fill_one()) {}
+  for_units(&s_ctr[0], uh + ub, [&](uint32_t u) {
+    if (FBX_SKIP(1u)) return;
+    if (u < uh) ps.hash1_unit(u); else ps.bucket1_unit(u - uh);
+  });
   FBX_MARK(7);
   // ---- the single crosses of every later layer: they only read signs kept on chip
   for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
@@ -1052,10 +1065,9 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     uint32_t* ctr = &s_ctr[4u + (layer & 1u)];
     if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
     const uint32_t ux = ps.units_of(TL_LAYER + 2u * (layer - 2u));
-    for (uint32_t u = grab_unit(ctr); u < ux; u = grab_unit(ctr)) {
-      if (FBX_SKIP(2u)) continue;
-      ps.x11_unit(layer, u);
-    }
+    for_units(ctr, ux, [&](uint32_t u) {
+      if (!FBX_SKIP(2u)) ps.x11_unit(layer, u);
+    });
   }
   FBX_MARK(8);
   if (!P.n_ragged) return;  // (list operators need a ragged input somewhere below them)
@@ -1087,12 +1099,12 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   {
     const uint32_t um = P.n_mh ? ps.item_units() : 0u;
     const uint32_t uo = ps.other_units(), un = ps.ngram_units();
-    for (uint32_t u = grab_unit(&s_ctr[3]); u < um + uo + un; u = grab_unit(&s_ctr[3])) {
-      if (FBX_SKIP(4u)) continue;
+    for_units(&s_ctr[3], um + uo + un, [&](uint32_t u) {
+      if (FBX_SKIP(4u)) return;
       if (u < uo) ps.other_unit(u);
       else if (u < uo + um) ps.item_unit(u - uo);
       else ps.ngram_unit(u - uo - um);
-    }
+    });
   }
   FBX_MARK(10);
   // ---- the list crosses / concats, layer by layer
@@ -1101,10 +1113,9 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     uint32_t* ctr = &s_ctr[7u + (layer & 1u)];
     if (tid == 0) s_ctr[7u + ((layer + 1u) & 1u)] = 0;
     const uint32_t ug = ps.units_of(TL_LAYER + 2u * (layer - 2u) + 1u);
-    for (uint32_t u = grab_unit(ctr); u < ug; u = grab_unit(ctr)) {
-      if (FBX_SKIP(2u)) continue;
-      ps.gen_unit(layer, u);
-    }
+    for_units(ctr, ug, [&](uint32_t u) {
+      if (!FBX_SKIP(2u)) ps.gen_unit(layer, u);
+    });
   }
 }
 
@@ -1155,8 +1166,18 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
     s_err = P.ctrl->err;  // set by an earlier kernel of this call: nothing may be written
     s_cur = atomicAdd(ticket, 1u);
   }
-  copy_table(smem + P.o_prog, P.prog, P.n_ops * (uint32_t)sizeof(OpProg));
-  copy_table(smem + P.o_lists, P.lists, P.n_ops * 4u);
+  {  // the operators' programs in the order of the work lists, their inputs a and b renumbered alike
+    static_assert(sizeof(OpProg) == 64 && offsetof(OpProg, a) == 24 && offsetof(OpProg, b) == 28, "OpProg layout");
+    const FBX_GLOBAL uint32_t* from = gptr(reinterpret_cast<const uint32_t*>(P.prog));
+    const FBX_GLOBAL uint32_t* lists = gptr(P.lists);
+    uint32_t* to = reinterpret_cast<uint32_t*>(smem + P.o_prog);
+    for (uint32_t i = tid; i < P.n_ops * 16u; i += kTileThreads) {
+      const uint32_t w = i & 15u;
+      uint32_t v = from[lists[i >> 4] * 16u + w];
+      if ((w == 6u || w == 7u) && v < P.n_ops) v = lists[P.n_ops + v];
+      to[i] = v;
+    }
+  }
   copy_table(smem + P.o_lbeg, P.list_begin, (P.n_lists + 1u) * 4u);
   copy_table(smem + P.o_rnr, P.rnr, P.rnr_words * 4u);
   copy_table(smem + P.o_aux, P.aux, P.aux_bytes);
