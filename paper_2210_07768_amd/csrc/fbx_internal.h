@@ -32,7 +32,11 @@ struct OpDesc {
   uint32_t death;    // last layer that reads this operator's output (>= layer)
   uint32_t stage;    // row of the on-chip sign table (single-sign operators that feed a later
                      // operator), 0xffffffff if none
-  uint32_t pad;
+  uint32_t fuse;     // tile kernel.  A cross of a multi-valued hash with a single sign is computed
+                     // by the lane that hashes the item: 1 when the hash is input a, 2 when it is
+                     // input b, 0 for every other cross.  For the multi-valued hash itself: first
+                     // entry (low 16 bits) and number (high 16 bits) of such crosses in
+                     // PlanHost::derive_tab's list of them.
 };
 static_assert(sizeof(OpDesc) == 64, "OpDesc must stay 64 bytes");
 
@@ -132,14 +136,17 @@ struct PlanHost {
   // for l = 2 .. n_layers + 1), then four words per operator, layer after layer: row of the
   // result, input a, input b (a row of the count table, or 0x80000000 | arity for an input
   // of fixed arity), and 0 for a cross (counts multiply) or 1 for a concat (counts add).
+  // After these, one word per cross that is computed along with its multi-valued hash (see
+  // OpDesc::fuse): its position in tile_lists, grouped by hash.
   std::vector<uint32_t> derive_tab;
   uint32_t n_derive = 0;                  // operators in derive_tab
 };
 
-// Work lists of the tile kernel.  Layer 1 has four lists; every later layer l
+// Work lists of the tile kernel.  Layer 1 has four lists; TL_FUSED holds the crosses that
+// the lanes of a multi-valued hash compute along with its items; every later layer l
 // has two, TL_LAYER + 2 * (l - 2) (crosses of two single signs) and the next
 // one (every other cross or concat).
-enum TileList : uint32_t { TL_HASH1 = 0, TL_BUCKET1 = 1, TL_RAGROOT = 2, TL_NGRAM = 3, TL_LAYER = 4 };
+enum TileList : uint32_t { TL_HASH1 = 0, TL_BUCKET1 = 1, TL_RAGROOT = 2, TL_NGRAM = 3, TL_FUSED = 4, TL_LAYER = 5 };
 
 // Returns FBX_OK or FBX_E_SPEC (message in err).
 fbx_status parse_plan(const char* spec, size_t len, PlanHost& out, std::string& err);

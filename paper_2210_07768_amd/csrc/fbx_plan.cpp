@@ -321,7 +321,7 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
   // Tile kernel: single-sign operators that feed a later operator keep their
   // signs on chip (one table row each); work lists group operators by the code
   // that runs them, layer by layer.
-  for (HostOp& op : plan.ops) op.d.stage = 0xffffffffu;
+  for (HostOp& op : plan.ops) { op.d.stage = 0xffffffffu; op.d.fuse = 0; }
   for (const HostOp& op : plan.ops) {
     if (op.d.kind != OP_CROSS && op.d.kind != OP_CONCAT) continue;
     for (uint32_t in : {op.d.a, op.d.b}) {
@@ -340,7 +340,16 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
       else lists[TL_BUCKET1].push_back(i);
     } else {
       const bool single = d.kind == OP_CROSS && plan.ops[d.a].d.arity == 1 && plan.ops[d.b].d.arity == 1;
-      lists[TL_LAYER + 2 * (d.layer - 2) + (single ? 0 : 1)].push_back(i);
+      auto multi_hash = [&](uint32_t in) {
+        const OpDesc& di = plan.ops[in].d;
+        return di.layer == 1 && di.kind == OP_HASH && di.arity == 0;
+      };
+      uint32_t fuse = 0;
+      if (d.kind == OP_CROSS && multi_hash(d.a) && plan.ops[d.b].d.arity == 1) fuse = 1;
+      if (d.kind == OP_CROSS && multi_hash(d.b) && plan.ops[d.a].d.arity == 1) fuse = 2;
+      plan.ops[i].d.fuse = fuse;
+      if (fuse) lists[TL_FUSED].push_back(i);
+      else lists[TL_LAYER + 2 * (d.layer - 2) + (single ? 0 : 1)].push_back(i);
     }
   }
   // neighbouring lanes run neighbouring list entries: keep like with like
@@ -374,6 +383,26 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
       }
     }
     plan.derive_tab[plan.n_layers - 1] = plan.n_derive;
+    // the crosses computed along with a multi-valued hash, grouped by hash
+    const size_t n = plan.ops.size();
+    uint32_t n_fused = 0;
+    for (uint32_t h = 0; h < n; ++h) {
+      OpDesc& dh = plan.ops[h].d;
+      if (!(dh.layer == 1 && dh.kind == OP_HASH && dh.arity == 0)) continue;
+      const uint32_t first = n_fused;
+      for (uint32_t i : plan.nonroot_ops) {
+        const OpDesc& d = plan.ops[i].d;
+        if ((d.fuse == 1 && d.a == h) || (d.fuse == 2 && d.b == h)) {
+          plan.derive_tab.push_back(plan.tile_lists[n + i]);
+          ++n_fused;
+        }
+      }
+      if (n_fused > 0xffffu) {
+        err = "more than 65535 crosses of a multi-valued hash with a single sign";
+        return FBX_E_SPEC;
+      }
+      dh.fuse = first | ((n_fused - first) << 16);
+    }
   }
   return FBX_OK;
 }

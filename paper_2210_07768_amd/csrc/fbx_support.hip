@@ -132,6 +132,15 @@ __device__ void write_programs(const WalkParams& P, bool placed) {
       g.aux_off = ops[d.a].stage;
       g.aux_len = ops[d.b].stage;
     }
+    if (d.kind == OP_CROSS && d.fuse) {
+      // a cross computed along with its multi-valued hash: the other input's row, and which side the hash is on
+      g.aux_off = ops[d.fuse == 1 ? d.b : d.a].stage;
+      g.aux_len = d.fuse == 1 ? 1u : 0u;
+    }
+    if (d.kind == OP_HASH && !d.arity) {  // a multi-valued hash: its crosses of that kind (first, number)
+      g.a = d.fuse & 0xffffu;
+      g.b = d.fuse >> 16;
+    }
     P.prog_ops[i] = g;
   }
   for (uint32_t k = tid; k < P.n_fields; k += kBlock) {

@@ -812,7 +812,22 @@ struct Pass {
       off[gg] = first;
       if (gg + 1 == P.n_records) off[gg + 1] = first + cnt;
     }
-    gptr<uint64_t>(d.values)[first] = hash_span(src, is, ie, d.key);
+    const uint64_t v = hash_span(src, is, ie, d.key);
+    gptr<uint64_t>(d.values)[first] = v;
+    // crosses of this hash with a single sign: one sign per item, in the items' order
+    const uint32_t* fused = sh.rnr + 4u * ((P.n_layers + 3u) >> 2) + 4u * P.n_rnr + d.a;
+    for (uint32_t k = 0; k < d.b; ++k) {
+      const OpProg& c = sh.prog[fused[k]];
+      const uint64_t other = sh.stage[c.aux_off * T + rr];
+      const uint64_t at = sh.base[c.rag_row] + sh.start[c.rag_row * T + rr] + j;
+      if (j == 0 && (c.flags & F_EMIT)) {
+        G64 off = gptr<uint64_t>(c.offsets);
+        const uint64_t gg = g_first + rr;
+        off[gg] = at;
+        if (gg + 1 == P.n_records) off[gg + 1] = at + cnt;
+      }
+      gptr<uint64_t>(c.values)[at] = c.aux_len ? mix64(mix64(v + c.key) + other) : mix64(mix64(other + c.key) + v);
+    }
   }
 
   // n-grams: the lanes of a wavefront run over the grams of one record; unit = (operator, record)
@@ -844,55 +859,87 @@ struct Pass {
     gptr<uint64_t>(d->values)[g] = v;
     if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
   }
-  // this lane's list of an earlier operator (in the arrays this workgroup wrote)
-  __device__ __forceinline__ void input_list(const OpProg& d, CG64& ptr, uint32_t& n) const {
-    if (d.arity) {
-      n = d.arity;
-      ptr = gptr<const uint64_t>(d.values) + g * d.arity;
-    } else {
-      n = sh.cnt[d.rag_row * T + r];
-      ptr = gptr<const uint64_t>(d.values) + sh.base[d.rag_row] + sh.start[d.rag_row * T + r];
-    }
+  // Every other cross or concat: lanes are output signs.  A unit is 64 consecutive outputs
+  // of one operator in this pass (operator after operator, record after record); a lane
+  // finds its record by a search over the records' first positions, its place in the
+  // record's list tells which input signs it combines, and neighbouring lanes write
+  // neighbouring signs.
+  __device__ __forceinline__ uint32_t gen_total(const OpProg& d) const { return d.arity ? d.arity * nb : sh.tot[d.rag_row]; }
+  // sign x of record rr of an earlier operator (single signs from the on-chip table, lists
+  // from the arrays this workgroup wrote before the layer barrier)
+  __device__ __forceinline__ uint64_t input_sign(const OpProg& d, uint32_t rr, uint32_t x) const {
+    if (d.arity == 1u && d.stage != kNoRow) return sh.stage[d.stage * T + rr];
+    const uint64_t at = d.arity ? (g_first + rr) * d.arity : sh.base[d.rag_row] + sh.start[d.rag_row * T + rr];
+    return gptr<const uint64_t>(d.values)[at + x];
   }
-  // every other cross or concat; inputs are read four at a time so that their
-  // loads overlap instead of queueing behind the stores
-  __device__ __forceinline__ void gen_unit(uint32_t layer, uint32_t u) {
-    const OpProg* dp = op_of(TL_LAYER + 2u * (layer - 2u) + 1u, u);
-    if (!dp || !live) return;
-    const OpProg& d = *dp;
+  __device__ __forceinline__ void gen_items(const OpProg& d, uint32_t chunk) {
+    const uint32_t lane = lane_id();
+    const uint32_t row = d.rag_row;
+    if (chunk == 0 && !d.arity && lane < nb) place(d, lane, g_first + lane);  // the offsets entries (T <= 64 records)
+    const uint32_t q = chunk * 64u + lane;
+    if (q >= gen_total(d)) return;
+    uint32_t rr, j;
+    uint64_t at;  // where the sign goes
+    if (d.arity) {
+      rr = q / d.arity;
+      j = q - rr * d.arity;
+      at = (g_first + rr) * d.arity + j;
+    } else {
+      const uint32_t pos = sh.run[row] - sh.tot[row] + q;  // position inside the tile (earlier passes come first)
+      const uint32_t* st = sh.start + row * T;
+      uint32_t lo = 0, hi = nb - 1u;  // the last record whose first position is <= pos (it is the one that has the sign)
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1u) >> 1;
+        if (st[mid] <= pos) lo = mid; else hi = mid - 1u;
+      }
+      rr = lo;
+      j = pos - st[rr];
+      at = sh.base[row] + pos;
+    }
     const OpProg& da = sh.prog[d.a];
     const OpProg& db = sh.prog[d.b];
-    CG64 pa, pb;
-    uint32_t na, nbv;
-    input_list(da, pa, na);
-    input_list(db, pb, nbv);
-    G64 dst = gptr<uint64_t>(d.values) + (d.arity ? g * d.arity : place(d, r, g));
-    const uint64_t key = d.key;
-    if (d.kind == OP_CROSS) {
-      for (uint32_t x = 0; x < na; ++x) {
-        const uint64_t ma = mix64((da.arity == 1 && da.stage != kNoRow ? sh.stage[da.stage * T + r] : pa[x]) + key);
-        for (uint32_t y0 = 0; y0 < nbv; y0 += 4) {
-          uint64_t bv[4];
-#pragma unroll
-          for (uint32_t t = 0; t < 4; ++t) bv[t] = y0 + t < nbv ? pb[y0 + t] : 0;
-#pragma unroll
-          for (uint32_t t = 0; t < 4; ++t) if (y0 + t < nbv) dst[t] = mix64(ma + bv[t]);
-          dst += min(4u, nbv - y0);
-        }
-      }
+    const uint32_t na = da.arity ? da.arity : sh.cnt[da.rag_row * T + rr];
+    const uint32_t nbv = db.arity ? db.arity : sh.cnt[db.rag_row * T + rr];
+    uint64_t v;
+    if (d.kind == OP_CROSS) {  // A outer, B inner
+      const uint32_t x = j / nbv, y = j - x * nbv;
+      v = mix64(mix64(input_sign(da, rr, x) + d.key) + input_sign(db, rr, y));
     } else {
-      for (uint32_t pass = 0; pass < 2; ++pass) {
-        CG64 p = pass ? pb : pa;
-        const uint32_t n = pass ? nbv : na;
-        for (uint32_t y0 = 0; y0 < n; y0 += 4) {
-          uint64_t bv[4];
-#pragma unroll
-          for (uint32_t t = 0; t < 4; ++t) bv[t] = y0 + t < n ? p[y0 + t] : 0;
-#pragma unroll
-          for (uint32_t t = 0; t < 4; ++t) if (y0 + t < n) dst[t] = bv[t];
-          dst += min(4u, n - y0);
-        }
+      v = j < na ? input_sign(da, rr, j) : input_sign(db, rr, j - na);
+    }
+    gptr<uint64_t>(d.values)[at] = v;
+  }
+  // all list operators of one layer; `ctr` numbers the layer's units from zero
+  template <class Skip>
+  __device__ __forceinline__ void gen_layer(uint32_t layer, uint32_t* ctr, Skip&& skip) {
+    const uint32_t lane = lane_id();
+    const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
+    const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
+    uint32_t u = grab_unit(ctr), units_before = 0;
+    for (uint32_t i0 = 0; i0 < m; i0 += 64u) {  // 64 operators at a time: lane l knows the units of operator i0 + l
+      uint32_t chunks = 0;
+      if (i0 + lane < m) {  // (a ragged operator without a sign in this pass still has offsets to write)
+        const OpProg& d = sh.prog[lb + i0 + lane];
+        chunks = max((gen_total(d) + 63u) >> 6, d.arity ? 0u : 1u);
       }
+      uint32_t incl = chunks;
+      for (uint32_t d = 1; d < 64u; d <<= 1) {
+        const uint32_t t = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += t;
+      }
+      const uint32_t first = units_before + incl - chunks;
+      const uint32_t end = units_before + __shfl(incl, 63, 64);
+      while (u < end) {
+        uint32_t next = 0;
+        if (lane == 0) next = atomicAdd(ctr, 1u);
+        // the unit's operator: the last lane that has units and whose first unit is <= u
+        const uint64_t owners = __ballot(chunks != 0u && first <= u);
+        const uint32_t l = 63u - (uint32_t)__clzll((unsigned long long)owners);
+        const uint32_t c = u - (uint32_t)__shfl(first, (int)l, 64);
+        if (!skip()) gen_items(sh.prog[lb + i0 + l], c);
+        u = __builtin_amdgcn_readfirstlane(next);
+      }
+      units_before = end;
     }
   }
 };
@@ -1112,10 +1159,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     __syncthreads();  // the layer barrier
     uint32_t* ctr = &s_ctr[7u + (layer & 1u)];
     if (tid == 0) s_ctr[7u + ((layer + 1u) & 1u)] = 0;
-    const uint32_t ug = ps.units_of(TL_LAYER + 2u * (layer - 2u) + 1u);
-    for_units(ctr, ug, [&](uint32_t u) {
-      if (!FBX_SKIP(2u)) ps.gen_unit(layer, u);
-    });
+    ps.gen_layer(layer, ctr, [&]() { return (bool)FBX_SKIP(2u); });
   }
 }
 
@@ -1174,7 +1218,10 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
     for (uint32_t i = tid; i < P.n_ops * 16u; i += kTileThreads) {
       const uint32_t w = i & 15u;
       uint32_t v = from[lists[i >> 4] * 16u + w];
-      if ((w == 6u || w == 7u) && v < P.n_ops) v = lists[P.n_ops + v];
+      if (w == 6u || w == 7u) {  // a, b
+        const uint32_t kind = from[lists[i >> 4] * 16u];
+        if ((kind == OP_CROSS || kind == OP_CONCAT) && v < P.n_ops) v = lists[P.n_ops + v];
+      }
       to[i] = v;
     }
   }
