@@ -54,6 +54,42 @@ def test_tile_sizes_passes_and_in_place_records(mode):
         check(w.spec, raw, off, mode, label=f"{w.name} {mode}")
 
 
+# crosses of a multi-valued hash with a single sign, which the tile kernel computes along with
+# the hash's items: the hash on either side, emitted or not, the single sign from layer 1 or from
+# a cross of layer 2, and later operators that read such a cross's list
+MULTI_CROSS_SPEC = ("fbx 1\nfields 4\n"
+                    "op s hash slot=0 seed=1 emit=1 field=0 multi=0\n"
+                    "op m hash slot=1 seed=2 emit=1 field=1 multi=1\n"
+                    "op n hash slot=2 seed=3 emit=0 field=3 multi=1\n"
+                    "op u bucket slot=3 seed=4 emit=1 field=2 multi=0 bounds=0,1000000\n"
+                    "op x1 cross slot=4 seed=5 emit=1 a=s b=m\n"
+                    "op x2 cross slot=5 seed=6 emit=1 a=m b=s\n"
+                    "op x3 cross slot=6 seed=7 emit=0 a=u b=n\n"
+                    "op x4 cross slot=7 seed=8 emit=1 a=s b=u\n"
+                    "op x5 cross slot=8 seed=9 emit=1 a=x4 b=m\n"
+                    "op x6 cross slot=9 seed=10 emit=1 a=x3 b=m\n"
+                    "op x7 concat slot=10 emit=1 a=x1 b=x2\n"
+                    "op x8 cross slot=11 seed=11 emit=1 a=m b=m\n"
+                    "op x9 cross slot=12 seed=12 emit=1 a=n b=x4\n")
+
+
+@pytest.mark.parametrize("mode", [{}, {"one_launch": 0}, {"fused": 0}] + TILE_MODES,
+                         ids=["default", "two_launches", "per_layer"] + TILE_IDS)
+def test_crosses_of_multi_valued_hashes_with_single_signs(mode):
+    rng = random.Random(77)
+    word = lambda: "".join(rng.choice("abcxyz0189") for _ in range(rng.randint(0, 9)))
+    recs = []
+    for i in range(333):
+        items = lambda k: ",".join(word() for _ in range(k))
+        k1 = rng.choice([1, 1, 2, 3, 5, 8, 16, 17, 21, 40])  # beyond the sixteen kept comma positions too
+        k3 = rng.choice([1, 2, 4, 19])
+        rec = f"{word()}\t{items(k1)}\t{rng.randint(-5, 5)}.{rng.randint(0, 999)}\t{items(k3)}"
+        if i % 7 == 3:
+            rec = word()  # the list fields are missing: one empty item each
+        recs.append((rec + ("\n" if i % 3 else "")).encode())
+    check(MULTI_CROSS_SPEC, *_cat(recs), mode, label=f"multi-valued crosses {mode}")
+
+
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 777])
 def test_tile_boundaries(n):
     for cfg in (5, 2):
