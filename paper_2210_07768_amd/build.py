@@ -25,6 +25,9 @@ def command() -> list:
         hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
         # keep the compiler from forming packed-FP32 instructions anywhere
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        # atomics whose one lane asks for a work item stay plain: rewritten as a wavefront-wide
+        # reduction they would wait for the answer at once instead of where it is used
+        "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
         "-x", "hip",
     ] + (["-DFBX_TILE_PROF"] if os.environ.get("FBX_TILE_PROF") else []) + [
         "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
