@@ -521,9 +521,8 @@ constexpr uint32_t kWaves = kTileThreads / 64;
 // Work counters of a pass (cleared between passes): s_ctr[0] hands out the
 // single-valued hash / bucket units of layer 1, which fill every phase that has
 // idle wavefronts; s_ctr[1] the counting units, s_ctr[3] the ragged root units,
-// s_ctr[4 + (l & 1)] the single crosses of layer l, s_ctr[7 + (l & 1)] its list operators,
-// s_ctr[9 + (l & 1)] the derivation of its counts.  s_done[0]: finished counting units,
-// s_done[1 + (l & 1)]: finished derivation units of layer l.
+// s_ctr[4 + (l & 1)] the single crosses of layer l, s_ctr[7 + (l & 1)] its list operators.
+// s_done[0]: finished counting units.
 __shared__ uint32_t s_ctr[11];
 __shared__ uint32_t s_done[3];
 __shared__ uint32_t s_good;   // MODE 2: the tile's bases are known and inside the arrays
@@ -557,6 +556,12 @@ __device__ __forceinline__ void lb_store(uint64_t* p, uint64_t v) {
 }
 __device__ __forceinline__ uint64_t lb_load(uint64_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A single sign goes to memory for the caller only (later layers read it from the on-chip
+// table): it bypasses the caches' keep-for-reuse policy, so that the text requested ahead stays cached.
+__device__ __forceinline__ void store_single(uint64_t values, uint64_t g, uint64_t v) {
+  __builtin_nontemporal_store(v, gptr<uint64_t>(values) + g);
 }
 
 template <class Src>
@@ -705,7 +710,7 @@ struct Pass {
     uint32_t s, e;
     src.span(r, d->field, s, e);
     const uint64_t v = hash_span(src, s, e, d->key);
-    gptr<uint64_t>(d->values)[g] = v;
+    store_single(d->values, g, v);
     if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
   }
   __device__ __forceinline__ void bucket1_unit(uint32_t u) {
@@ -716,7 +721,7 @@ struct Pass {
     NumState ns;
     for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
     const uint64_t v = bucket_sign(*d, sh.aux, ns, malformed);
-    gptr<uint64_t>(d->values)[g] = v;
+    store_single(d->values, g, v);
     if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
   }
   // where this lane's list of a ragged operator starts; writes its offsets entry
@@ -856,7 +861,7 @@ struct Pass {
     if (!d || !live) return;
     const uint64_t a = sh.stage[d->aux_off * T + r], b = sh.stage[d->aux_len * T + r];
     const uint64_t v = mix64(mix64(a + d->key) + b);
-    gptr<uint64_t>(d->values)[g] = v;
+    store_single(d->values, g, v);
     if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
   }
   // Every other cross or concat: lanes are output signs.  A unit is 64 consecutive outputs
@@ -1072,13 +1077,11 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   hook();
   // ---- phase B: the counts of later layers, layer by layer
   if (P.n_rnr) {
-    for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
-      if (tid == 0) {  // the next layer's counters (idle since the barrier before this one)
-        s_ctr[9u + ((layer + 1u) & 1u)] = 0;
-        s_done[1u + ((layer + 1u) & 1u)] = 0;
-      }
-      absurd = critical_phase(ps.derive_units(layer), &s_ctr[9u + (layer & 1u)], &s_done[1u + (layer & 1u)],
-                              layer == P.n_layers, [&](uint32_t u) { ps.derive_unit(layer, u); });
+    for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {  // (short: the wavefronts just share the units out)
+      const uint32_t ud = ps.derive_units(layer);
+      for (uint32_t u = wave; u < ud; u += kWaves) ps.derive_unit(layer, u);
+      if (MODE == 2 && layer == P.n_layers) absurd = __syncthreads_or((int)overflow) != 0;
+      else __syncthreads();
       hook();
     }
     FBX_MARK(5);
