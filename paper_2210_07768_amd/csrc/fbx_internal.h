@@ -13,7 +13,11 @@ namespace fbx {
 
 enum OpKind : uint32_t { OP_HASH = 1, OP_NGRAM = 2, OP_BUCKET = 3, OP_FILTER = 4, OP_CROSS = 5, OP_CONCAT = 6 };
 
-enum OpFlags : uint32_t { F_MULTI = 1u, F_EMIT = 2u };
+enum OpFlags : uint32_t {
+  F_MULTI = 1u,
+  F_EMIT = 2u,
+  F_STREAM = 4u  // tile kernel: no later operator reads the signs from memory (they are only the caller's)
+};
 
 // Device-visible operator descriptor (64 bytes).  Filled once at plan time.
 struct OpDesc {

@@ -361,6 +361,14 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
     plan.tile_lists.insert(plan.tile_lists.end(), l.begin(), l.end());
   }
   plan.tile_list_begin.push_back(static_cast<uint32_t>(plan.tile_lists.size()));
+  // whose signs does a later operator of the tile kernel read from memory?  (single signs are
+  // read from the on-chip table, a multi-valued hash's items by the lanes that compute them)
+  for (HostOp& op : plan.ops) op.d.flags |= F_STREAM;
+  for (const HostOp& op : plan.ops) {
+    if (op.d.kind != OP_CROSS && op.d.kind != OP_CONCAT) continue;
+    if (plan.ops[op.d.a].d.arity != 1 && op.d.fuse != 1) plan.ops[op.d.a].d.flags &= ~(uint32_t)F_STREAM;
+    if (plan.ops[op.d.b].d.arity != 1 && op.d.fuse != 2) plan.ops[op.d.b].d.flags &= ~(uint32_t)F_STREAM;
+  }
   {  // every operator is in exactly one list: append where each one went
     const size_t n = plan.ops.size();
     plan.tile_lists.resize(2 * n);

@@ -563,6 +563,11 @@ __device__ __forceinline__ uint64_t lb_load(uint64_t* p) {
 __device__ __forceinline__ void store_single(uint64_t values, uint64_t g, uint64_t v) {
   __builtin_nontemporal_store(v, gptr<uint64_t>(values) + g);
 }
+// The same for any array entry that nothing on the device reads again (stream == true).
+__device__ __forceinline__ void store_sign(G64 at, uint64_t v, bool stream) {
+  if (stream) __builtin_nontemporal_store(v, at);
+  else *at = v;
+}
 
 template <class Src>
 struct Pass {
@@ -729,7 +734,7 @@ struct Pass {
     const uint64_t first = sh.base[d.rag_row] + sh.start[d.rag_row * T + rr];
     if (d.flags & F_EMIT) {
       G64 off = gptr<uint64_t>(d.offsets);
-      off[gg] = first;
+      __builtin_nontemporal_store(first, off + gg);
       if (gg + 1 == P.n_records) off[gg + 1] = first + sh.cnt[d.rag_row * T + rr];
     }
     return first;
@@ -814,11 +819,11 @@ struct Pass {
     if (j == 0 && (d.flags & F_EMIT)) {
       G64 off = gptr<uint64_t>(d.offsets);
       const uint64_t gg = g_first + rr;
-      off[gg] = first;
+      __builtin_nontemporal_store(first, off + gg);
       if (gg + 1 == P.n_records) off[gg + 1] = first + cnt;
     }
     const uint64_t v = hash_span(src, is, ie, d.key);
-    gptr<uint64_t>(d.values)[first] = v;
+    store_sign(gptr<uint64_t>(d.values) + first, v, d.flags & F_STREAM);
     // crosses of this hash with a single sign: one sign per item, in the items' order
     const uint32_t* fused = sh.rnr + 4u * ((P.n_layers + 3u) >> 2) + 4u * P.n_rnr + d.a;
     for (uint32_t k = 0; k < d.b; ++k) {
@@ -828,10 +833,11 @@ struct Pass {
       if (j == 0 && (c.flags & F_EMIT)) {
         G64 off = gptr<uint64_t>(c.offsets);
         const uint64_t gg = g_first + rr;
-        off[gg] = at;
+        __builtin_nontemporal_store(at, off + gg);
         if (gg + 1 == P.n_records) off[gg + 1] = at + cnt;
       }
-      gptr<uint64_t>(c.values)[at] = c.aux_len ? mix64(mix64(v + c.key) + other) : mix64(mix64(other + c.key) + v);
+      store_sign(gptr<uint64_t>(c.values) + at, c.aux_len ? mix64(mix64(v + c.key) + other) : mix64(mix64(other + c.key) + v),
+                 c.flags & F_STREAM);
     }
   }
 
@@ -912,7 +918,7 @@ struct Pass {
     } else {
       v = j < na ? input_sign(da, rr, j) : input_sign(db, rr, j - na);
     }
-    gptr<uint64_t>(d.values)[at] = v;
+    store_sign(gptr<uint64_t>(d.values) + at, v, d.flags & F_STREAM);
   }
   // all list operators of one layer; `ctr` numbers the layer's units from zero
   template <class Skip>
