@@ -183,28 +183,31 @@ constexpr uint32_t kTabs = 0x09090909u, kCommas = 0x2c2c2c2cu;
 // bytes [rs, re) at every delimiter (pat: the delimiter in all four bytes).  Each lane
 // takes an equal run of the 16-byte chunks that cover the range and counts its
 // delimiters; a prefix sum over the group turns the counts into ordinals, and a second
-// walk calls emit(k, position) for the k-th delimiter.  Returns the number of delimiters
-// in the whole range.  Every lane of the wavefront calls it; those with act == false
-// (and, with positions == false, all of them) emit nothing.
+// walk calls emit(k, position) for the k-th delimiter, k < limit.  Returns the number of
+// delimiters in the whole range.  Every lane of the wavefront calls it; those with
+// act == false (and, with limit == 0, all of them) emit nothing.
 template <class Emit>
 __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs, uint32_t re, bool act, uint32_t pat,
-                                                uint32_t lg, uint32_t j, bool positions, Emit&& emit) {
+                                                uint32_t lg, uint32_t j, uint32_t limit, Emit&& emit) {
   const uint32_t gsz = 1u << lg;
   const uint32_t ab = rs & ~15u;
   const uint32_t nc = (act && re > rs) ? (re - ab + 15u) >> 4 : 0u;  // 16-byte chunks that cover the range
   const uint32_t c = (nc + gsz - 1u) >> lg;                          // chunks per lane
   const uint32_t c0 = min(j * c, nc), c1 = min(c0 + c, nc);
-  // one bit per byte of chunk ci: set where the byte is a delimiter inside the range
+  // one bit per byte of chunk ci: set where the byte is a delimiter (bytes outside the range included)
   auto chunk_bits = [&](uint32_t ci) -> uint32_t {
-    const uint32_t cp = ab + 16u * ci;
-    const u32x4 w = *reinterpret_cast<const u32x4*>(raw + cp);
-    // flag bytes (0x80 or 0) -> bits, four dwords -> sixteen bits
-    uint32_t lo8 = __builtin_amdgcn_udot4(eq_flags(w.x, pat) >> 7, 0x08040201u, 0u, false);
-    lo8 = __builtin_amdgcn_udot4(eq_flags(w.y, pat) >> 7, 0x80402010u, lo8, false);
-    uint32_t hi8 = __builtin_amdgcn_udot4(eq_flags(w.z, pat) >> 7, 0x08040201u, 0u, false);
-    hi8 = __builtin_amdgcn_udot4(eq_flags(w.w, pat) >> 7, 0x80402010u, hi8, false);
-    const uint32_t lo = rs > cp ? rs - cp : 0u, hi = min(re - cp, 16u);  // the chunk's bytes [lo, hi) are in the range
-    return (lo8 | (hi8 << 8)) & (((1u << (hi - lo)) - 1u) << lo);
+    const u32x4 w = *reinterpret_cast<const u32x4*>(raw + ab + 16u * ci);
+    // flag bytes (0x80 or 0) times weights 1, 2, 4 ...: every sum is 128 times the wanted bits
+    uint32_t lo8 = __builtin_amdgcn_udot4(eq_flags(w.x, pat), 0x08040201u, 0u, false);
+    lo8 = __builtin_amdgcn_udot4(eq_flags(w.y, pat), 0x80402010u, lo8, false);
+    uint32_t hi8 = __builtin_amdgcn_udot4(eq_flags(w.z, pat), 0x08040201u, 0u, false);
+    hi8 = __builtin_amdgcn_udot4(eq_flags(w.w, pat), 0x80402010u, hi8, false);
+    return (lo8 | (hi8 << 8)) >> 7;
+  };
+  // the bits [lo, hi) of a mask of n bits that starts at staged position p: those inside the range
+  auto inside = [&](uint32_t p, uint32_t n) -> uint64_t {
+    const uint32_t lo = rs > p ? rs - p : 0u, hi = min(re - p, n);
+    return (hi >= 64u ? ~0ull : (1ull << hi) - 1ull) & (~0ull << lo);
   };
   // A lane with at most four chunks (the usual case) keeps one bit per byte: bit i of (mhi:mlo)
   // is set when byte i of its run is a delimiter.  The second walk then needs no memory at all.
@@ -221,9 +224,14 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
         else mhi |= m16 << 16;
       }
     }
+    if (c0 < c1) {  // (the lane's run starts before re)
+      const uint64_t in = inside(ab + 16u * c0, 64u);
+      mlo &= (uint32_t)in;
+      mhi &= (uint32_t)(in >> 32);
+    }
     cnt = __popc(mlo) + __popc(mhi);
   } else {
-    for (uint32_t ci = c0; ci < c1; ++ci) cnt += __popc(chunk_bits(ci));
+    for (uint32_t ci = c0; ci < c1; ++ci) cnt += __popc(chunk_bits(ci) & (uint32_t)inside(ab + 16u * ci, 16u));
   }
   uint32_t incl = cnt;
   for (uint32_t s = 1; s < gsz; s <<= 1) {
@@ -231,14 +239,17 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
     if (j >= s) incl += t;
   }
   const uint32_t total = __shfl(incl, (int)(lane_id() | (gsz - 1u)), 64);
-  if (!act || !positions) return total;
+  if (!act || !limit) return total;
   uint32_t k = incl - cnt;
   if (few) {
     uint32_t base = ab + 16u * c0;
     uint32_t m = mlo;
+    uint32_t room = k < limit ? limit - k : 0u;  // delimiters this lane may still report
 #pragma unroll
     for (uint32_t half = 0; half < 2; ++half) {
-      while (m) {
+      uint32_t n = min((uint32_t)__popc(m), room);
+      room -= n;
+      for (; n; --n) {
         const uint32_t i = (uint32_t)__ffs((int)m) - 1u;
         emit(k, base + i);
         ++k;
@@ -262,7 +273,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
       const uint32_t idx = f0 ? i0 : (f1 ? i1 : 8u);
       p += idx;
       if (idx < 8u && p < be) {
-        emit(k, p);
+        if (k < limit) emit(k, p);
         ++k;
         ++p;
       }
@@ -289,8 +300,8 @@ __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint
     if (re > rs && sh.raw[re - 1u] == '\n') --re;  // one trailing newline is not part of the record
   }
   uint16_t* row = sh.rows + r * P.row_stride;
-  const uint32_t total = split_bytes(sh.raw, rs, re, act, kTabs, lg, j, true, [&](uint32_t k, uint32_t pos) {
-    if (k < F) row[1u + k] = (uint16_t)pos;
+  const uint32_t total = split_bytes(sh.raw, rs, re, act, kTabs, lg, j, F, [&](uint32_t k, uint32_t pos) {
+    row[1u + k] = (uint16_t)pos;
   });
   if (!act) return;
   if (j == 0) row[0] = (uint16_t)(rs - 1u);
@@ -620,8 +631,8 @@ struct Pass {
       }
       uint16_t* tab = sh.ctab + pr * P.item_cap;
       const uint32_t cap = P.item_cap;
-      const uint32_t commas = split_bytes(src.raw8, s, e, act, kCommas, lg, j, need_table, [&](uint32_t k, uint32_t pos) {
-        if (k < cap) tab[k] = (uint16_t)pos;
+      const uint32_t commas = split_bytes(src.raw8, s, e, act, kCommas, lg, j, need_table ? cap : 0u, [&](uint32_t k, uint32_t pos) {
+        tab[k] = (uint16_t)pos;
       });
       if (pr < np && j == 0) sh.cnt[row * T + rr] = act ? commas + 1u : 0u;  // items = commas + 1 (far below kMaxCount)
     }
@@ -1076,6 +1087,10 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   bool absurd = false;
   if constexpr (Src::kTable) {
     if (P.n_mh) ps.split_items();
+    if (P.n_mh && FBX_SKIP(0x200u)) {  // (tuning builds: once more, to weigh it)
+      __syncthreads();
+      ps.split_items();
+    }
   }
   if (P.n_ragged) absurd = critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], !P.n_rnr, [&](uint32_t u) { ps.count_unit(u); });
   else __syncthreads();
@@ -1361,6 +1376,10 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
         __syncthreads();
         FBX_MARK(2);
         if (!FBX_SKIP(8u)) tokenize(P, sh, nb);
+        if (FBX_SKIP(0x100u)) {  // (tuning builds: once more, to weigh it)
+          __syncthreads();
+          tokenize(P, sh, nb);
+        }
         __syncthreads();
         FBX_MARK(3);
         LdsSrc src{sh.raw, sh.rows, P.row_stride};
