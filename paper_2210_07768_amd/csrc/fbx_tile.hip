@@ -1129,6 +1129,10 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     if (u < uh) ps.hash1_unit(u); else ps.bucket1_unit(u - uh);
   });
   FBX_MARK(7);
+  // One-launch mode: the words of the tiles before this one (for the wavefront's first ragged
+  // operator) are requested now, so that they arrive while the single crosses run.
+  uint64_t early = kLbPrefix;
+  if (MODE == 2 && wave < P.n_ragged) early = lb_window(P, wave, tile);
   // ---- the single crosses of every later layer: they only read signs kept on chip
   for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
     __syncthreads();  // the layer barrier: every sign this layer reads is in place
@@ -1143,11 +1147,12 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   FBX_MARK(8);
   if (!P.n_ragged) return;  // (list operators need a ragged input somewhere below them)
 
-  // ---- one-launch mode: the tile's bases come from the tiles before it.  This is as late as
-  // it can be: the count went out long ago, so the tiles before this one have had time to count.
+  // ---- one-launch mode: the tile's bases come from the tiles before it.  The count went out
+  // long ago, so the tiles before this one have had time to count.
   if (MODE == 2) {
-    constexpr uint32_t kRows = 4;  // operators a wavefront looks back for at the same time
-    for (uint32_t row0 = wave; row0 < P.n_ragged; row0 += kRows * kWaves) {
+    if (wave < P.n_ragged && !lb_place_row(P, sh, tile, wave, early) && lane == 0) s_good = 0u;
+    constexpr uint32_t kRows = 4;  // further operators: a wavefront looks back for several at the same time
+    for (uint32_t row0 = wave + kWaves; row0 < P.n_ragged; row0 += kRows * kWaves) {
       uint64_t v[kRows];
 #pragma unroll
       for (uint32_t k = 0; k < kRows; ++k) {
