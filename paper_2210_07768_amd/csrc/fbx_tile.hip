@@ -11,23 +11,27 @@
 //     16-byte loads that every lane of the workgroup takes part in: each raw
 //     byte leaves HBM once, fully coalesced.
 //  2. Splitting at the delimiter (Section 5, first paragraph): groups of lanes
-//     share a record, find its tabs four bytes at a time and write a table of
+//     share a record, find its tabs sixteen bytes at a time and write a table of
 //     field ends (16-bit LDS positions).  No per-thread array is allocated; the
-//     table has one entry per (record, field).
+//     table has one entry per (record, field).  The same routine splits the item
+//     lists of multi-valued fields at their commas.
 //  3. Layer 1: lanes are (record, operator) pairs.  A lane looks up its field in
 //     the table and hashes / parses it out of LDS; T neighbouring lanes hold T
 //     consecutive records of one operator, so a slot is written in runs of 8 T
 //     bytes.  Signs that a later operator needs stay in an LDS table as well.
-//  4. Later layers read their inputs from that table (or, for lists, from the
-//     arrays this workgroup wrote) after the barrier.
+//  4. Later layers run after the barrier: crosses of two single signs out of that
+//     table; list operators with one lane per output sign, reading lists from
+//     the arrays this workgroup wrote.  A cross of a multi-valued hash with a
+//     single sign is computed by the lane that hashes the item.
 //  5. Ragged slots: the per-record counts of the tile are found first, then
 //     turned into positions by a prefix sum over the tile's records on top of
-//     the tile's base (a counting launch of this same kernel and a scan over
-//     tiles provide it).
+//     the tile's base.  The base comes from a counting launch of this same
+//     kernel and a scan over tiles, or, in the one-launch mode, from the words
+//     that the tiles before this one have published (see lb_place_row).
 //  6. Workgroups are persistent and software-pipelined: while a tile is worked
-//     on, the ticket of the tile after the next, the record offsets of the next
-//     tile and then its raw text are already on their way (the text waits in
-//     registers until the LDS section is free).
+//     on, the ticket and the record offsets of the next tile are fetched and one
+//     byte of every line of its text is touched, so that the text is on its way
+//     into the cache when the tile's turn comes.
 //
 // A tile whose text does not fit the LDS section is worked off in several
 // passes of fewer records; a single record that does not fit alone is walked
