@@ -124,6 +124,7 @@ void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParam
   tp.o_run = o; o = round16(o + 4ull * h.n_ragged);
   tp.o_base = o; o = round16(o + 8ull * h.n_ragged);
   tp.o_tot = o; o = round16(o + 4ull * h.n_ragged);
+  tp.o_cap = o; o = round16(o + 8ull * h.n_ragged);
   tp.o_ioff = o; o = round16(o + 4ull * (tp.n_mh + 1));
   tp.item_cap = 16;
   tp.o_ctab = o; o = round16(o + 2ull * tp.n_mh * T * tp.item_cap);

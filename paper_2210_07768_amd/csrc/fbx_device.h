@@ -68,7 +68,7 @@ struct TileParams {
   // byte offsets of the LDS sections
   uint32_t o_off, o_rs, o_re, o_rows, o_raw, o_stage, o_cnt, o_start, o_run, o_base;
   uint32_t o_prog, o_lbeg, o_rnr, o_aux;  // plan tables
-  uint32_t o_tot, o_ioff, o_ctab;
+  uint32_t o_tot, o_ioff, o_ctab, o_cap;
   uint32_t item_cap;    // comma positions kept per record and multi-valued hash
   uint32_t lds_bytes;
   uint64_t* prof;  // 32 phase counters (tuning builds only), else NULL

@@ -108,6 +108,7 @@ struct Sh {
   uint32_t* run;    // [n_ragged] signs of the tile's earlier passes
   uint64_t* base;   // [n_ragged] the tile's base in the operator's values array
   uint32_t* tot;    // [n_ragged] signs of this pass
+  uint64_t* cap;    // [n_ragged] signs the operator's array has room for (one-launch mode)
   uint32_t* ioff;   // [n_mh + 1] first item of every multi-valued hash among the pass's items
   uint16_t* ctab;   // [n_mh][T][item_cap] comma positions of the multi-valued hash fields
   // plan tables, copied once per workgroup so that no lane waits on memory for a descriptor
@@ -130,6 +131,7 @@ __device__ __forceinline__ Sh views(const TileParams& P) {
   s.run = reinterpret_cast<uint32_t*>(smem + P.o_run);
   s.base = reinterpret_cast<uint64_t*>(smem + P.o_base);
   s.tot = reinterpret_cast<uint32_t*>(smem + P.o_tot);
+  s.cap = reinterpret_cast<uint64_t*>(smem + P.o_cap);
   s.ioff = reinterpret_cast<uint32_t*>(smem + P.o_ioff);
   s.ctab = reinterpret_cast<uint16_t*>(smem + P.o_ctab);
   s.prog = reinterpret_cast<const OpProg*>(smem + P.o_prog);
@@ -1036,7 +1038,7 @@ __device__ __forceinline__ bool lb_place_row(const TileParams& P, const Sh& sh, 
     upper -= 64u;  // all counts: look further back (upper >= 64 here, else lane `upper` had stopped the window)
     spins = 0;
   }
-  if (!abort && excl + agg > gptr(P.row_cap)[row]) {  // the array was sized too small: nothing may be written
+  if (!abort && excl + agg > sh.cap[row]) {  // the array was sized too small: nothing may be written
     if (lane == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
     abort = true;
   }
@@ -1261,6 +1263,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   copy_table(smem + P.o_lbeg, P.list_begin, (P.n_lists + 1u) * 4u);
   copy_table(smem + P.o_rnr, P.rnr, P.rnr_words * 4u);
   copy_table(smem + P.o_aux, P.aux, P.aux_bytes);
+  if (MODE == 2) copy_table(smem + P.o_cap, P.row_cap, P.n_ragged * 8u);
 #ifdef FBX_TILE_PROF
   if (tid < 16) s_prof[tid] = 0;
   if (tid == 0) s_prof_last = clock64();
