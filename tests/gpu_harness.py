@@ -66,3 +66,49 @@ def check(spec, raw, off, options=None, misalign=0, label=""):
     assert_same(out, res, want, label)
     plan.close()
     return res, want
+
+
+def device_workload(w, chunk_records=500_000):
+    """A whole synthetic workload assembled in device memory chunk by chunk: (raw bytes, record offsets)."""
+    import torch
+
+    n = w.n_records
+    probe, _ = w.generate(0, min(n, 2048))
+    est = int(probe.size / min(n, 2048) * n * 1.03) + (1 << 20)
+    d_raw = torch.empty(est, dtype=torch.uint8, device="cuda")
+    d_off = torch.empty(n + 1, dtype=torch.int64, device="cuda")
+    pos = r = 0
+    while r < n:
+        m = min(chunk_records, n - r)
+        raw, off = w.generate(r, m)
+        if pos + raw.size > d_raw.numel():
+            grown = torch.empty(int((pos + raw.size) * 1.1), dtype=torch.uint8, device="cuda")
+            grown[:pos].copy_(d_raw[:pos])
+            d_raw = grown
+        d_raw[pos:pos + raw.size].copy_(torch.from_numpy(raw))
+        d_off[r:r + m].copy_(torch.from_numpy((off[:-1] + np.uint64(pos)).astype(np.int64)))
+        pos += raw.size
+        r += m
+    d_off[n:].fill_(pos)
+    torch.cuda.synchronize()
+    return d_raw[:pos], d_off
+
+
+def check_window(spec, res, d_raw, d_off, first, count, label=""):
+    """Records [first, first + count) of a large result against the oracle run on just those records."""
+    off = d_off[first:first + count + 1].cpu().numpy().astype(np.uint64)
+    raw = d_raw[int(off[0]):int(off[-1])].cpu().numpy()
+    want = O.extract(spec, raw, off - off[0])
+    assert sorted(res.slot_ids) == sorted(want.slots), label
+    for s in want.slot_ids:
+        ov, oo, arity = want.slots[s]
+        slot = res.slots[s]
+        assert slot.fixed_arity == arity, f"{label} slot {s} arity"
+        if slot.offsets is None:
+            lo, hi = first * arity, (first + count) * arity
+        else:
+            go = slot.offsets[first:first + count + 1].cpu().numpy().view(np.uint64)
+            assert np.array_equal(go - go[0], oo), f"{label} slot {s}: offsets of records {first}.. differ"
+            lo, hi = int(go[0]), int(go[-1])
+        gv = slot.values[lo:hi].cpu().numpy().view(np.uint64)
+        assert np.array_equal(gv, ov), f"{label} slot {s}: signs of records {first}..{first + count} differ"

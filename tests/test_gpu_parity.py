@@ -9,7 +9,7 @@ from oracle import fbx_oracle as O
 from paper_2210_07768_amd import binding as B
 from paper_2210_07768_amd import workloads as W
 from helpers import FRAMING_RECORDS, FRAMING_SPEC
-from gpu_harness import assert_same, check, run_gpu, to_device
+from gpu_harness import assert_same, check, check_window, device_workload, run_gpu, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -88,6 +88,41 @@ def test_crosses_of_multi_valued_hashes_with_single_signs(mode):
             rec = word()  # the list fields are missing: one empty item each
         recs.append((rec + ("\n" if i % 3 else "")).encode())
     check(MULTI_CROSS_SPEC, *_cat(recs), mode, label=f"multi-valued crosses {mode}")
+
+
+@pytest.mark.parametrize("cfg,one_launch", [(5, True), (2, False), (3, True), (4, False)])
+def test_full_size_workloads_on_sampled_records(cfg, one_launch):
+    """The benchmark configurations at their full sizes, run the way bench.py times them (a first
+    call that sizes the workspace, then a call that knows the ragged sizes): properties that hold
+    for the whole result, and windows of records against the oracle."""
+    import torch
+
+    w = W.get(cfg)
+    d_raw, d_off = device_workload(w)
+    R = w.n_records
+    plan = B.Plan(w.spec)
+    first_res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.03)
+    res = plan.extract(d_raw, d_off)
+    assert res.tile_launches == (1 if one_launch else 2), res.note
+    assert res.n_records == R and res.n_values_total == first_res.n_values_total
+    total = 0
+    for s in res.slot_ids:
+        slot = res.slots[s]
+        total += slot.n_values
+        if slot.offsets is None:
+            assert slot.n_values == R * slot.fixed_arity
+            continue
+        offs = slot.offsets
+        assert offs.numel() == R + 1 and int(offs[0]) == 0 and int(offs[R]) == slot.n_values, f"slot {s}"
+        assert bool((offs[1:] >= offs[:-1]).all()), f"slot {s}: offsets decrease"
+    assert total == res.n_values_total
+    rng = np.random.default_rng(1000 + cfg)
+    starts = [0, R - 5, 31, 63, R // 2 - 2] + [int(x) for x in rng.integers(0, R - 5, size=35)]
+    for first in starts:
+        check_window(w.spec, res, d_raw, d_off, first, 5, label=f"{w.name} full size")
+    plan.close()
+    del ws
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 777])
