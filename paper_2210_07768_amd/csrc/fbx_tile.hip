@@ -39,6 +39,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "fbx_device.h"
 
@@ -327,14 +328,16 @@ __device__ __forceinline__ void window8(const LdsSrc& src, uint32_t p, uint32_t&
 // Calls f(byte) for every byte of [s, e), in order.  Staged text is read eight
 // bytes per window; the steps of a window nest, so a lane that is done leaves
 // the execution mask once.
+// Calls f(word, K) for the bytes [s, e) in order: the byte is byte K (a compile-time constant,
+// passed as std::integral_constant) of the 32-bit word.
 template <class F>
-__device__ __forceinline__ void for_each_byte(const LdsSrc& src, uint32_t s, uint32_t e, F&& f) {
+__device__ __forceinline__ void for_each_byte_of_word(const LdsSrc& src, uint32_t s, uint32_t e, F&& f) {
   uint32_t p = s;
   while (p < e) {
     uint32_t x0, x1;
     window8(src, p, x0, x1);
     const uint32_t n = e - p < 8u ? e - p : 8u;
-#define FBX_STEP(J, X) if (n > (uint32_t)J) { f(((X) >> (8 * (J & 3))) & 0xffu);
+#define FBX_STEP(J, X) if (n > (uint32_t)J) { f(X, std::integral_constant<int, (J & 3)>());
     FBX_STEP(0, x0) FBX_STEP(1, x0) FBX_STEP(2, x0) FBX_STEP(3, x0)
     FBX_STEP(4, x1) FBX_STEP(5, x1) FBX_STEP(6, x1) FBX_STEP(7, x1)
     }}}}}}}}
@@ -342,17 +345,47 @@ __device__ __forceinline__ void for_each_byte(const LdsSrc& src, uint32_t s, uin
     p += n;
   }
 }
+template <class F>
+__device__ __forceinline__ void for_each_byte(const LdsSrc& src, uint32_t s, uint32_t e, F&& f) {
+  for_each_byte_of_word(src, s, e, [&](uint32_t w, auto k) { f((w >> (8 * decltype(k)::value)) & 0xffu); });
+}
 
 template <class F>
 __device__ __forceinline__ void for_each_byte(const GlobalSrc& src, uint32_t s, uint32_t e, F&& f) {
   for (uint32_t p = s; p < e; ++p) f(src.byte(p));
 }
+template <class F>
+__device__ __forceinline__ void for_each_byte_of_word(const GlobalSrc& src, uint32_t s, uint32_t e, F&& f) {
+  for (uint32_t p = s; p < e; ++p) f(src.byte(p), std::integral_constant<int, 0>());
+}
 
-// FNV-1a over the bytes [s, e) from state h.
+// a ^ (byte K of w), in one instruction (sub-dword operand selection)
+template <int K>
+__device__ __forceinline__ uint32_t xor_byte(uint32_t a, uint32_t w) {
+  uint32_t r;
+  if (K == 0) asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(a), "v"(w));
+  else if (K == 1) asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(a), "v"(w));
+  else if (K == 2) asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(a), "v"(w));
+  else asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(a), "v"(w));
+  return r;
+}
+
+// FNV-1a over the bytes [s, e) from state h: h = (h ^ b) * (2^40 + 435) per byte.  Only the low
+// word's product needs the wide multiply-add; the high word's own terms, 435 hi + (lo << 8), go
+// in as its addend.
 template <class Src>
 __device__ __forceinline__ uint64_t hash_span(const Src& src, uint32_t s, uint32_t e, uint64_t h) {
-  for_each_byte(src, s, e, [&](uint32_t b) { h = (h ^ b) * kPrime; });
-  return h;
+  static_assert(kPrime == ((1ull << 40) | 435ull), "FNV-1a prime");
+  uint32_t lo = (uint32_t)h, hi = (uint32_t)(h >> 32);
+  for_each_byte_of_word(src, s, e, [&](uint32_t w, auto k) {
+    lo = xor_byte<decltype(k)::value>(lo, w);
+    const uint32_t top = hi * 435u + (lo << 8);
+    uint64_t r, carry;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(r), "=s"(carry) : "v"(lo), "s"(435u), "v"((uint64_t)top << 32));
+    lo = (uint32_t)r;
+    hi = (uint32_t)(r >> 32);
+  });
+  return ((uint64_t)hi << 32) | lo;
 }
 
 // 0x80 in exactly the zero bytes of x.
