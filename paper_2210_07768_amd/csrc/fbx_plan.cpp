@@ -281,9 +281,13 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
     plan.layer_ops.insert(plan.layer_ops.end(), ids.begin(), ids.end());
   }
   plan.layer_begin[plan.n_layers] = static_cast<uint32_t>(plan.layer_ops.size());
+  // Rows of the ragged operators: those of the last layer (if it is not the first) come last, in
+  // spec order, because the tile kernel derives their counts in the same step that scans them.
+  for (int last = 0; last < 2; ++last)
+    for (HostOp& op : plan.ops)
+      if (op.d.arity == 0 && (op.d.layer > 1 && op.d.layer == plan.n_layers) == (last == 1)) op.d.rag_row = plan.n_ragged++;
   for (uint32_t i = 0; i < plan.ops.size(); ++i) {
     OpDesc& d = plan.ops[i].d;
-    if (d.arity == 0) d.rag_row = plan.n_ragged++;
     if (d.layer > 1) plan.nonroot_ops.push_back(i);
     if (d.kind == OP_BUCKET) {
       while (plan.aux.size() % 8) plan.aux.push_back(0);
@@ -391,6 +395,14 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
       }
     }
     plan.derive_tab[plan.n_layers - 1] = plan.n_derive;
+    {  // the last layer's operators hold the last rows, in the table's order
+      const uint32_t first = plan.derive_tab[plan.n_layers - 2], n_last = plan.n_derive - first;
+      for (uint32_t i = 0; i < n_last; ++i)
+        if (plan.derive_tab[hw + 4 * (first + i)] != plan.n_ragged - n_last + i) {
+          err = "internal: rows of the last layer's ragged operators are out of order";
+          return FBX_E_SPEC;
+        }
+    }
     // the crosses computed along with a multi-valued hash, grouped by hash
     const size_t n = plan.ops.size();
     uint32_t n_fused = 0;

@@ -740,11 +740,38 @@ struct Pass {
     sh.cnt[d.x * T + r] = live ? (uint32_t)c : 0u;
   }
   // Counts become positions inside the tile: a prefix sum over the records of G rows at a time.
-  __device__ __forceinline__ uint32_t scan_units() const { return (P.n_ragged + G - 1u) / G; }
+  // The ragged operators of the last layer (if it is not the first) hold the last rows, in the
+  // order of their table entries: their counts are derived here, right before they are summed.
+  __device__ __forceinline__ uint32_t last_layer_rows() const {
+    return P.n_rnr ? sh.rnr[P.n_layers - 1u] - sh.rnr[P.n_layers - 2u] : 0u;
+  }
+  __device__ __forceinline__ uint32_t scan_units() const {
+    const uint32_t nl = last_layer_rows();
+    return (P.n_ragged - nl + G - 1u) / G + (nl + G - 1u) / G;
+  }
   __device__ __forceinline__ void scan_unit(uint32_t u) {
-    const uint32_t row = u * G + og;
-    const bool ok = row < P.n_ragged;
-    const uint32_t v = ok ? sh.cnt[row * T + r] : 0u;
+    const uint32_t nl = last_layer_rows(), plain = P.n_ragged - nl, up = (plain + G - 1u) / G;
+    uint32_t row, v = 0;
+    bool ok;
+    if (u < up) {
+      row = u * G + og;
+      ok = row < plain;
+      if (ok) v = sh.cnt[row * T + r];
+    } else {
+      const uint32_t i = (u - up) * G + og;
+      row = plain + i;
+      ok = i < nl;
+      if (ok) {
+        const uint32_t header = 4u * ((P.n_layers + 3u) >> 2);
+        const u32x4 d = *reinterpret_cast<const u32x4*>(sh.rnr + header + 4u * (sh.rnr[P.n_layers - 2u] + i));
+        const uint64_t ca = (d.y >> 31) ? (d.y & 0x7fffffffu) : sh.cnt[d.y * T + r];
+        const uint64_t cb = (d.z >> 31) ? (d.z & 0x7fffffffu) : sh.cnt[d.z * T + r];
+        const uint64_t c = d.w == 0u ? ca * cb : ca + cb;
+        if (c > kMaxCount) overflow = true;
+        v = live && c <= kMaxCount ? (uint32_t)c : 0u;
+        sh.cnt[row * T + r] = v;
+      }
+    }
     const uint32_t incl = group_incl_scan(v, T);
     if (ok) {
       const uint32_t before = sh.run[row];
@@ -1131,32 +1158,33 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
       ps.split_items();
     }
   }
-  if (P.n_ragged) absurd = critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], !P.n_rnr, [&](uint32_t u) { ps.count_unit(u); });
+  if (P.n_ragged) critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], false, [&](uint32_t u) { ps.count_unit(u); });
   else __syncthreads();
   FBX_MARK(4);
   hook();
   // ---- phase B: the counts of later layers, layer by layer
   if (P.n_rnr) {
-    for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {  // (short: the wavefronts just share the units out)
+    // (short: the wavefronts just share the units out; the last layer's counts are left to the next phase)
+    for (uint32_t layer = 2; layer < P.n_layers; ++layer) {
       const uint32_t ud = ps.derive_units(layer);
       for (uint32_t u = wave; u < ud; u += kWaves) ps.derive_unit(layer, u);
-      if (MODE == 2 && layer == P.n_layers) absurd = __syncthreads_or((int)overflow) != 0;
-      else __syncthreads();
+      __syncthreads();
       hook();
     }
     FBX_MARK(5);
-  }
-  if (MODE == 2 && absurd) {  // absurd counts: nothing of this tile may be placed
-    lb_abort_tile(P, tile);
-    return;
   }
   // ---- phase B2: counts become positions
   if (P.n_ragged) {
     const uint32_t us = ps.scan_units();
     for (uint32_t u = wave; u < us; u += kWaves) ps.scan_unit(u);
-    __syncthreads();
+    if (MODE == 2) absurd = __syncthreads_or((int)overflow) != 0;
+    else __syncthreads();
     FBX_MARK(6);
     hook();
+  }
+  if (MODE == 2 && absurd) {  // absurd counts: nothing of this tile may be placed (whatever it published is overwritten)
+    lb_abort_tile(P, tile);
+    return;
   }
   if (!WRITE) return;
 
@@ -1223,10 +1251,13 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   }
   FBX_MARK(10);
   // ---- the list crosses / concats, layer by layer
-  for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
+  for (uint32_t layer = 2, turn = 0; layer <= P.n_layers; ++layer) {
+    const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
+    if (sh.list_begin[list + 1] == sh.list_begin[list]) continue;  // (no such operator in this layer: no barrier either)
     __syncthreads();  // the layer barrier
-    uint32_t* ctr = &s_ctr[7u + (layer & 1u)];
-    if (tid == 0) s_ctr[7u + ((layer + 1u) & 1u)] = 0;
+    uint32_t* ctr = &s_ctr[7u + (turn & 1u)];
+    if (tid == 0) s_ctr[7u + ((turn + 1u) & 1u)] = 0;  // the counter of the next layer that has any (idle since the barrier before this one)
+    ++turn;
     ps.gen_layer(layer, ctr, [&]() { return (bool)FBX_SKIP(2u); });
   }
 }
