@@ -1295,6 +1295,7 @@ template <int MODE>
 __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   constexpr bool WRITE = MODE != 0;
   __shared__ uint32_t s_err, s_len, s_cur, s_nxt;
+  __shared__ uint32_t s_bad[2];  // what is wrong with the offsets of the current and of the next tile (CE_ bits)
   const Sh sh = views(P);
   const uint32_t tid = threadIdx.x;
   const uint32_t T = 1u << P.log2T;
@@ -1308,6 +1309,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   if (tid == 0) {
     s_err = P.ctrl->err;  // set by an earlier kernel of this call: nothing may be written
     s_cur = atomicAdd(ticket, 1u);
+    s_bad[0] = s_bad[1] = 0;
   }
   {  // the operators' programs in the order of the work lists, their inputs a and b renumbered alike
     static_assert(sizeof(OpProg) == 64 && offsetof(OpProg, a) == 24 && offsetof(OpProg, b) == 28, "OpProg layout");
@@ -1334,12 +1336,21 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
 #endif
   __syncthreads();
   if (s_err) return;
+  // Offsets are checked before a tile touches the text: non-decreasing, inside the text, a record shorter than 2 GiB.
+  auto offsets_fault = [&](uint64_t a, uint64_t b) -> uint32_t {
+    if (a > b || b > P.raw_len) return CE_OFFSETS;
+    return b - a >= (1ull << 31) ? CE_TILE : 0u;
+  };
   // the first tile's offsets arrive the plain way
   uint32_t par = 0;
   if (s_cur < P.n_tiles) {
     const uint64_t g0 = (uint64_t)s_cur << P.log2T;
     const uint32_t nrec = (uint32_t)min((uint64_t)T, P.n_records - g0);
     if (tid <= nrec) sh.off[tid] = rec_off[g0 + tid];
+    if (tid < nrec) {
+      const uint32_t bad = offsets_fault(rec_off[g0 + tid], rec_off[g0 + tid + 1]);
+      if (bad) atomicOr(&s_bad[0], bad);
+    }
   }
   __syncthreads();
   FBX_MARK(0);
@@ -1363,14 +1374,10 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
     if (tid >= 11 && tid < 14) s_done[tid - 11] = 0;
     if (tid == 14) s_good = 1u;
     bool nrec_ok = true;
-    uint32_t bad = 0;
-    if (tid < nrec) {
-      const uint64_t a = off[tid], b = off[tid + 1];
-      if (a > b || b > P.raw_len) bad = CE_OFFSETS;
-      else if (b - a >= (1ull << 31)) bad = CE_TILE;
-    }
-    if (__syncthreads_or((int)bad)) {
-      if (bad) atomicOr(&P.ctrl->err, bad);
+    const uint32_t bad = s_bad[par];  // (found while the tile before this one was worked on)
+    if (tid == 0) s_bad[par ^ 1u] = 0;
+    if (bad) {
+      if (tid == 0) atomicOr(&P.ctrl->err, bad);
       if (MODE != 2) break;  // the call fails: no point in working off the other tiles
       // without a counting launch later tiles wait for this one: tell them, then go on
       lb_abort_tile(P, tile);
@@ -1384,7 +1391,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
     // the L2 cache without holding registers for it.  Only the two outer offsets decide what is
     // touched; the tile itself is checked when its turn comes.
     uint32_t pf_stage = 0, nxt = 0xffffffffu, nrec2 = 0, touch = 0;
-    uint64_t off_next = 0, nx_lo = 0, nx_hi = 0;
+    uint64_t off_next = 0, off_next1 = 0, nx_lo = 0, nx_hi = 0;
     auto next_tile_step = [&]() {  // every lane, right after a barrier
       if (pf_stage == 0) {
         if (tid == 0) s_nxt = my_ticket;
@@ -1394,12 +1401,17 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
           const uint64_t g1 = (uint64_t)nxt << P.log2T;
           nrec2 = (uint32_t)min((uint64_t)T, P.n_records - g1);
           if (tid <= nrec2) off_next = rec_off[g1 + tid];
+          if (tid < nrec2) off_next1 = rec_off[g1 + tid + 1u];
           nx_lo = rec_off[g1];
           nx_hi = rec_off[g1 + nrec2];
         }
       } else if (pf_stage == 2) {
         if (nxt < P.n_tiles) {
           if (tid <= nrec2) off2[tid] = off_next;
+          if (tid < nrec2) {
+            const uint32_t fault = offsets_fault(off_next, off_next1);
+            if (fault) atomicOr(&s_bad[par ^ 1u], fault);
+          }
           if (nx_lo <= nx_hi && nx_hi <= P.raw_len) {
             const uintptr_t first = ok_lo + nx_lo, end = ok_lo + nx_hi;
             const uintptr_t line = (first & ~(uintptr_t)127) + 128u * tid;  // (tiles beyond 64 KiB of text: the first 64 KiB)
