@@ -94,7 +94,15 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
   return x ^ (x >> 31);
 }
 
-__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+// The thread's number, hidden from the optimiser's view of the loops around the caller: what
+// follows from it (lane masks, per-lane addresses) is then worked out where it is used instead
+// of once per kernel, where each such value would hold a register for good.
+__device__ __forceinline__ uint32_t thread_id() {
+  uint32_t t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+__device__ __forceinline__ uint32_t lane_id() { return thread_id() & 63u; }
 
 // Views of the LDS sections of one workgroup.
 struct Sh {
@@ -293,7 +301,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
 // record and place its tabs.  Entries from the record's tab count on hold the
 // record's end.
 __device__ __forceinline__ void tokenize(const TileParams& P, const Sh& sh, uint32_t nb) {
-  const uint32_t tid = threadIdx.x;
+  const uint32_t tid = thread_id();
   constexpr uint32_t kLogThreads = kTileThreads == 1024 ? 10u : (kTileThreads == 512 ? 9u : 8u);
   const uint32_t lg = kLogThreads - P.log2T < 6u ? kLogThreads - P.log2T : 6u;  // log2 of the lanes per record
   const uint32_t gsz = 1u << lg;
@@ -635,6 +643,16 @@ struct Pass {
   uint32_t lb_tile;   // tile number when counts are to be published (one-launch mode), else kNoRow
   bool need_table;    // the pass goes on to write: keep comma positions while counting
 
+  // This lane's place in a unit, worked out anew (and hidden from the optimiser's view of the
+  // tile loop): otherwise every address that follows from it is computed once per kernel and
+  // kept in a register of its own for good, and the hot loops run out of registers.
+  __device__ __forceinline__ void refresh() {
+    const uint32_t lane = lane_id();
+    r = lane & (T - 1u);
+    og = lane >> P.log2T;
+    live = r < nb;
+    g = g_first + r;
+  }
   __device__ __forceinline__ uint32_t units_of(uint32_t list) const {
     return (sh.list_begin[list + 1] - sh.list_begin[list] + G - 1u) / G;
   }
@@ -651,7 +669,7 @@ struct Pass {
   // split the field at its commas: the item count, and the first item_cap comma positions
   // for the lanes that later hash the items.
   __device__ __forceinline__ void split_items() {
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = thread_id();
     const uint32_t np = P.n_mh * T;  // (operator, record slot) pairs
     uint32_t lg = 0;                 // log2 of the lanes per pair
     while (lg < 6u && (np << (lg + 1u)) <= kTileThreads) ++lg;
@@ -684,6 +702,7 @@ struct Pass {
   }
   __device__ __forceinline__ uint32_t count_units() const { return count_root_units() + units_of(TL_NGRAM); }
   __device__ __forceinline__ void count_unit(uint32_t u) {
+    refresh();
     const uint32_t ur = count_root_units();
     const OpProg* d;
     uint32_t i = 0;  // position in the ragged root list
@@ -729,6 +748,7 @@ struct Pass {
     return (sh.rnr[layer - 1u] - sh.rnr[layer - 2u] + G - 1u) / G;
   }
   __device__ __forceinline__ void derive_unit(uint32_t layer, uint32_t u) {
+    refresh();
     const uint32_t i = sh.rnr[layer - 2u] + u * G + og;
     if (i >= sh.rnr[layer - 1u]) return;
     const uint32_t header = 4u * ((P.n_layers + 3u) >> 2);
@@ -750,6 +770,7 @@ struct Pass {
     return (P.n_ragged - nl + G - 1u) / G + (nl + G - 1u) / G;
   }
   __device__ __forceinline__ void scan_unit(uint32_t u) {
+    refresh();
     const uint32_t nl = last_layer_rows(), plain = P.n_ragged - nl, up = (plain + G - 1u) / G;
     uint32_t row, v = 0;
     bool ok;
@@ -787,6 +808,7 @@ struct Pass {
 
   // ---- layer 1
   __device__ __forceinline__ void hash1_unit(uint32_t u) {
+    refresh();
     const OpProg* d = op_of(TL_HASH1, u);
     if (!d || !live) return;
     uint32_t s, e;
@@ -796,6 +818,7 @@ struct Pass {
     if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
   }
   __device__ __forceinline__ void bucket1_unit(uint32_t u) {
+    refresh();
     const OpProg* d = op_of(TL_BUCKET1, u);
     if (!d || !live) return;
     uint32_t s, e;
@@ -821,6 +844,7 @@ struct Pass {
     return (sh.list_begin[TL_RAGROOT + 1] - sh.list_begin[TL_RAGROOT] - P.n_mh + G - 1u) / G;
   }
   __device__ __forceinline__ void other_unit(uint32_t u) {
+    refresh();
     const uint32_t lb = sh.list_begin[TL_RAGROOT] + P.n_mh, m = sh.list_begin[TL_RAGROOT + 1] - lb;
     const uint32_t i = u * G + og;
     const OpProg* d = i < m ? &sh.prog[lb + i] : nullptr;
@@ -940,6 +964,7 @@ struct Pass {
   // ---- later layers
   // crosses of two single signs, both on chip
   __device__ __forceinline__ void x11_unit(uint32_t layer, uint32_t u) {
+    refresh();
     const OpProg* d = op_of(TL_LAYER + 2u * (layer - 2u), u);
     if (!d || !live) return;
     const uint64_t a = sh.stage[d->aux_off * T + r], b = sh.stage[d->aux_len * T + r];
@@ -1117,7 +1142,7 @@ template <int MODE, class Src, class Hook>
 __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, const Src& src, uint32_t nb, uint64_t g_first,
                                          uint32_t tile, uint32_t& malformed, bool& overflow, Hook&& hook) {
   constexpr bool WRITE = MODE != 0;
-  const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+  const uint32_t tid = thread_id(), lane = tid & 63u, wave = tid >> 6;
   const uint32_t T = 1u << P.log2T;
   Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow, MODE == 2 ? tile : kNoRow, WRITE};
   ps.live = ps.r < nb;
