@@ -487,16 +487,6 @@ __device__ __forceinline__ uint64_t bucket_sign(const OpProg& d, const uint8_t* 
   return mix64(d.key + lo);
 }
 
-// The one sign of a single-valued hash or bucket operator on [s, e).
-template <class Src>
-__device__ __forceinline__ uint64_t single_sign(const Src& src, const OpProg& d, const uint8_t* aux, uint32_t s,
-                                                uint32_t e, uint32_t& malformed) {
-  if (d.kind == OP_HASH) return hash_span(src, s, e, d.key);
-  NumState ns;
-  for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
-  return bucket_sign(d, aux, ns, malformed);
-}
-
 // Number of signs a ragged root operator (not n-gram) produces on [s, e).
 template <class Src>
 __device__ __forceinline__ uint32_t ragged_root_count(const Src& src, const OpProg& d, const uint8_t* aux, uint32_t s,
@@ -580,9 +570,9 @@ constexpr uint32_t kWaves = kTileThreads / 64;
 // single-valued hash / bucket units of layer 1, which fill every phase that has
 // idle wavefronts; s_ctr[1] the counting units, s_ctr[3] the ragged root units,
 // s_ctr[4 + (l & 1)] the single crosses of layer l, s_ctr[7 + (l & 1)] its list operators.
-// s_done[0]: finished counting units.
-__shared__ uint32_t s_ctr[11];
-__shared__ uint32_t s_done[3];
+// s_done: finished counting units.
+__shared__ uint32_t s_ctr[9];
+__shared__ uint32_t s_done;
 __shared__ uint32_t s_good;   // MODE 2: the tile's bases are known and inside the arrays
 
 // Next unit of a phase, the same for every lane of the wavefront.
@@ -1159,8 +1149,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
 
   // A phase whose few long units would leave most wavefronts idle: wavefronts that
   // find no unit left hash single-valued fields until the last unit is done.
-  // With `vote` (one-launch mode) the closing barrier also tells whether any lane saw absurd counts.
-  auto critical_phase = [&](uint32_t total, uint32_t* ctr, uint32_t* done, bool vote, auto&& unit) -> bool {
+  auto critical_phase = [&](uint32_t total, uint32_t* ctr, uint32_t* done, auto&& unit) {
     for (uint32_t u = grab_unit(ctr); u < total; u = grab_unit(ctr)) {
       unit(u);
       __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
@@ -1169,9 +1158,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     if (WRITE) {
       while (*reinterpret_cast<volatile uint32_t*>(done) < total && fill_one()) {}
     }
-    if (MODE == 2 && vote) return __syncthreads_or((int)overflow) != 0;
     __syncthreads();
-    return false;
   };
 
   // ---- phase A: counts of the ragged root operators
@@ -1183,7 +1170,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
       ps.split_items();
     }
   }
-  if (P.n_ragged) critical_phase(ps.count_units(), &s_ctr[1], &s_done[0], false, [&](uint32_t u) { ps.count_unit(u); });
+  if (P.n_ragged) critical_phase(ps.count_units(), &s_ctr[1], &s_done, [&](uint32_t u) { ps.count_unit(u); });
   else __syncthreads();
   FBX_MARK(4);
   hook();
@@ -1395,9 +1382,9 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       sh.run[row] = 0;
       if (MODE == 1) sh.base[row] = gptr(P.tile_base)[(uint64_t)row * P.n_tiles + tile];
     }
-    if (tid < 11) s_ctr[tid] = 0;
-    if (tid >= 11 && tid < 14) s_done[tid - 11] = 0;
-    if (tid == 14) s_good = 1u;
+    if (tid < 9) s_ctr[tid] = 0;
+    if (tid == 9) s_done = 0;
+    if (tid == 10) s_good = 1u;
     bool nrec_ok = true;
     const uint32_t bad = s_bad[par];  // (found while the tile before this one was worked on)
     if (tid == 0) s_bad[par ^ 1u] = 0;
@@ -1512,9 +1499,9 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
         r0 += 1u;
       }
       __syncthreads();  // the sections are reused by the next pass
-      if (tid < 11) s_ctr[tid] = 0;
-      if (tid >= 11 && tid < 14) s_done[tid - 11] = 0;
-      if (tid == 14) s_good = 1u;
+      if (tid < 9) s_ctr[tid] = 0;
+      if (tid == 9) s_done = 0;
+      if (tid == 10) s_good = 1u;
       FBX_MARK(11);
     }
     if (!WRITE) {
