@@ -574,6 +574,7 @@ constexpr uint32_t kWaves = kTileThreads / 64;
 __shared__ uint32_t s_ctr[9];
 __shared__ uint32_t s_done;
 __shared__ uint32_t s_good;   // MODE 2: the tile's bases are known and inside the arrays
+__shared__ uint32_t s_absurd; // MODE 2: some lane saw a count beyond kMaxCount in this tile
 
 // Next unit of a phase, the same for every lane of the wavefront.
 __device__ __forceinline__ uint32_t grab_unit(uint32_t* ctr) {
@@ -1189,8 +1190,9 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   if (P.n_ragged) {
     const uint32_t us = ps.scan_units();
     for (uint32_t u = wave; u < us; u += kWaves) ps.scan_unit(u);
-    if (MODE == 2) absurd = __syncthreads_or((int)overflow) != 0;
-    else __syncthreads();
+    if (MODE == 2 && overflow) s_absurd = 1u;  // (rare: a plain flag is cheaper than a vote in every tile)
+    __syncthreads();
+    if (MODE == 2) absurd = s_absurd != 0u;
     FBX_MARK(6);
     hook();
   }
@@ -1385,6 +1387,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
     if (tid < 9) s_ctr[tid] = 0;
     if (tid == 9) s_done = 0;
     if (tid == 10) s_good = 1u;
+    if (tid == 11) s_absurd = 0u;
     bool nrec_ok = true;
     const uint32_t bad = s_bad[par];  // (found while the tile before this one was worked on)
     if (tid == 0) s_bad[par ^ 1u] = 0;
@@ -1502,6 +1505,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
       if (tid < 9) s_ctr[tid] = 0;
       if (tid == 9) s_done = 0;
       if (tid == 10) s_good = 1u;
+      if (tid == 11) s_absurd = 0u;
       FBX_MARK(11);
     }
     if (!WRITE) {
