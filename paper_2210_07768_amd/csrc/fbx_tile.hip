@@ -226,8 +226,9 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
   };
   // A lane with at most four chunks (the usual case) keeps one bit per byte: bit i of (mhi:mlo)
   // is set when byte i of its run is a delimiter.  The second walk then needs no memory at all.
-  const bool few = c <= 4u;
-  uint32_t mlo = 0, mhi = 0, cnt = 0;
+  // With five to eight chunks (long records) two more words (m2, m3) hold the second 64 bytes.
+  const bool few = c <= 4u, some = c > 4u && c <= 8u;
+  uint32_t mlo = 0, mhi = 0, m2 = 0, m3 = 0, cnt = 0;
   if (few) {
 #pragma unroll
     for (uint32_t q = 0; q < 4; ++q) {
@@ -245,6 +246,28 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
       mhi &= (uint32_t)(in >> 32);
     }
     cnt = __popc(mlo) + __popc(mhi);
+  } else if (some) {
+#pragma unroll
+    for (uint32_t q = 0; q < 8; ++q) {
+      if (c0 + q < c1) {
+        const uint32_t m16 = chunk_bits(c0 + q) << (16u * (q & 1u));
+        if (q < 2) mlo |= m16;
+        else if (q < 4) mhi |= m16;
+        else if (q < 6) m2 |= m16;
+        else m3 |= m16;
+      }
+    }
+    if (c0 < c1) {
+      const uint64_t in = inside(ab + 16u * c0, 64u);
+      mlo &= (uint32_t)in;
+      mhi &= (uint32_t)(in >> 32);
+    }
+    if (c0 + 4u < c1) {  // (the second 64 bytes start before re)
+      const uint64_t in = inside(ab + 16u * c0 + 64u, 64u);
+      m2 &= (uint32_t)in;
+      m3 &= (uint32_t)(in >> 32);
+    }
+    cnt = __popc(mlo) + __popc(mhi) + __popc(m2) + __popc(m3);
   } else {
     for (uint32_t ci = c0; ci < c1; ++ci) cnt += __popc(chunk_bits(ci) & (uint32_t)inside(ab + 16u * ci, 16u));
   }
@@ -261,7 +284,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
     uint32_t m = mlo;
     uint32_t room = k < limit ? limit - k : 0u;  // delimiters this lane may still report
 #pragma unroll
-    for (uint32_t half = 0; half < 2; ++half) {
+    for (uint32_t word = 0; word < 2; ++word) {
       uint32_t n = min((uint32_t)__popc(m), room);
       room -= n;
       for (; n; --n) {
@@ -271,6 +294,23 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
         m &= m - 1u;
       }
       m = mhi;
+      base += 32u;
+    }
+  } else if (some) {
+    uint32_t base = ab + 16u * c0;
+    uint32_t m = mlo;
+    uint32_t room = k < limit ? limit - k : 0u;
+#pragma unroll
+    for (uint32_t word = 0; word < 4; ++word) {
+      uint32_t n = min((uint32_t)__popc(m), room);
+      room -= n;
+      for (; n; --n) {
+        const uint32_t i = (uint32_t)__ffs((int)m) - 1u;
+        emit(k, base + i);
+        ++k;
+        m &= m - 1u;
+      }
+      m = word == 0 ? mhi : (word == 1 ? m2 : m3);
       base += 32u;
     }
   } else {
