@@ -838,15 +838,22 @@ struct Pass {
   }
 
   // ---- layer 1
+  // (a unit is 2 G operators, each lane taking two of them one after the other: half the hand-outs and set-ups)
+  __device__ __forceinline__ uint32_t hash1_units() const {
+    return (sh.list_begin[TL_HASH1 + 1] - sh.list_begin[TL_HASH1] + 2u * G - 1u) / (2u * G);
+  }
   __device__ __forceinline__ void hash1_unit(uint32_t u) {
     refresh();
-    const OpProg* d = op_of(TL_HASH1, u);
-    if (!d || !live) return;
-    uint32_t s, e;
-    src.span(r, d->field, s, e);
-    const uint64_t v = hash_span(src, s, e, d->key);
-    store_single(d->values, g, v);
-    if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
+    if (!live) return;
+    const uint32_t lb = sh.list_begin[TL_HASH1], m = sh.list_begin[TL_HASH1 + 1] - lb;
+    for (uint32_t i = 2u * u * G + og; i < min(m, 2u * (u + 1u) * G); i += G) {
+      const OpProg& d = sh.prog[lb + i];
+      uint32_t s, e;
+      src.span(r, d.field, s, e);
+      const uint64_t v = hash_span(src, s, e, d.key);
+      store_single(d.values, g, v);
+      if (d.stage != kNoRow) sh.stage[d.stage * T + r] = v;
+    }
   }
   __device__ __forceinline__ void bucket1_unit(uint32_t u) {
     refresh();
@@ -1179,7 +1186,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   ps.live = ps.r < nb;
   ps.g = g_first + ps.r;
   // the single-valued hashes and buckets of layer 1 fill whatever phase has idle wavefronts
-  const uint32_t uh = WRITE ? ps.units_of(TL_HASH1) : 0u, ub = WRITE ? ps.units_of(TL_BUCKET1) : 0u;
+  const uint32_t uh = WRITE ? ps.hash1_units() : 0u, ub = WRITE ? ps.units_of(TL_BUCKET1) : 0u;
   auto fill_one = [&]() -> bool {
     const uint32_t u = grab_unit(&s_ctr[0]);
     if (u >= uh + ub) return false;
