@@ -189,6 +189,42 @@ def test_bad_offsets_are_rejected():
         assert e.value.status == B.E_INPUT
 
 
+def test_more_signs_per_record_than_the_limit_is_an_input_error():
+    """A cross of a list of 8200 items with itself would make 2^26 or more signs for one record:
+    both launch sequences refuse the batch (and write nothing) instead of sizing arrays for it."""
+    import torch
+    spec = ("fbx 1\nfields 1\n"
+            "op m hash slot=0 seed=1 emit=1 field=0 multi=1\n"
+            "op x cross slot=1 seed=2 emit=1 a=m b=m\n")
+    pad = b"0123456789abcdefghijklmnopqrstuvwxyz"  # (records long enough for the one-launch sequence to be chosen)
+    small = [b"a" + pad + b",b,c" + pad + b"\n", b"d" + pad + pad + b"\n", pad + b"," + pad + b"\n", b"e,f" + pad + pad + b"\n"] * 30
+    big = small[:50] + [b",".join([b"t"] * 8200) + b"\n"] + small[50:]
+    def arrays(records):
+        raw, off = _cat(records)
+        return np.frombuffer(raw, np.uint8), off
+
+    # first call on a plan: the counting launch sees it
+    with pytest.raises(B.FbxError) as e:
+        run_gpu(spec, *arrays(big))
+    assert e.value.status == B.E_INPUT
+    # a plan that knows its sizes from a good batch tries the one-launch sequence
+    plan = B.Plan(spec)
+    d_raw, d_off = to_device(*arrays(small))
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    plan.set_workspace(ws)
+    plan.extract(d_raw, d_off)
+    assert plan.extract(d_raw, d_off).tile_launches == 1
+    d_raw2, d_off2 = to_device(*arrays(big))
+    with pytest.raises(B.FbxError) as e:
+        plan.extract(d_raw2, d_off2)
+    assert e.value.status == B.E_INPUT
+    # and the plan still works
+    res = plan.extract(d_raw, d_off)
+    want = O.extract(spec, *arrays(small))
+    assert res.n_values_total == want.n_values_total
+    plan.close()
+
+
 def test_small_workspace_reports_requirement_then_succeeds():
     import torch
     w = W.get(2, 200)
