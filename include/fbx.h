@@ -34,7 +34,8 @@ typedef enum {
   FBX_E_ARG = -1,   /* NULL or inconsistent argument                         */
   FBX_E_SPEC = -2,  /* operator-DAG spec rejected (see fbx_last_error)        */
   FBX_E_NOMEM = -3, /* workspace too small; required size reported            */
-  FBX_E_INPUT = -4, /* record offsets decreasing / outside raw_len / too long */
+  FBX_E_INPUT = -4, /* record offsets decreasing / outside raw_len / a record of 2 GiB or more /
+                       an operator with 2^26 or more signs for one record */
   FBX_E_HIP = -5    /* a HIP runtime call failed                              */
 } fbx_status;
 

@@ -570,7 +570,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     return FBX_E_INPUT;
   }
   if (c->err & CE_OVERFLOW) {
-    plan->error = "an operator produces 2^31 or more signs for one tile of records";
+    plan->error = "an operator produces 2^26 or more signs for one record";
     return FBX_E_INPUT;
   }
   if (c->err & CE_NOMEM) {
