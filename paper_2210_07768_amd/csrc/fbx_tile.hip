@@ -1361,7 +1361,7 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   const uint32_t tid = threadIdx.x;
   const uint32_t T = 1u << P.log2T;
   const FBX_GLOBAL uint64_t* rec_off = gptr(P.rec_off);
-  uint32_t* ticket = &P.ctrl->ticket[WRITE ? 1 : 0];  // (MODE 2 needs the order the counter gives: see lb_place_tile)
+  uint32_t* ticket = &P.ctrl->ticket[WRITE ? 1 : 0];  // (MODE 2 needs the order the counter gives: see lb_place_row)
   const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(P.raw), ok_hi = ok_lo + P.raw_len;
   // Tiles are taken off a counter.  A workgroup takes its next tile when it starts on the
   // current one (that early, so that the next tile's offsets and text can be on their way),
