@@ -87,14 +87,34 @@ def lib():
 
 
 class Slot:
-    """One emitted slot of a result; ``values`` / ``offsets`` are torch views of the workspace."""
+    """One emitted slot of a result; ``values`` / ``offsets`` are torch views of the workspace
+    (made when first asked for: a result with hundreds of slots costs nothing to hand over)."""
 
-    def __init__(self, slot_id, fixed_arity, n_values, values, offsets):
+    def __init__(self, slot_id, fixed_arity, n_values, ws64, values_at, offsets_at, n_offsets):
         self.slot_id, self.fixed_arity, self.n_values = slot_id, fixed_arity, n_values
-        self.values, self.offsets = values, offsets
+        self._ws64, self._values_at, self._offsets_at, self._n_offsets = ws64, values_at, offsets_at, n_offsets
+        self._values = self._offsets = None
+
+    @property
+    def values(self):
+        if self._values is None:
+            self._values = self._ws64[self._values_at:self._values_at + self.n_values]
+        return self._values
+
+    @property
+    def offsets(self):
+        """None for a slot of fixed arity (offsets are implicit)."""
+        if self._offsets_at is None:
+            return None
+        if self._offsets is None:
+            self._offsets = self._ws64[self._offsets_at:self._offsets_at + self._n_offsets]
+        return self._offsets
 
 
 class ExtractResult:
+    """What fbx_extract reported.  ``slots`` (slot id -> Slot) and ``slot_ids`` (in emission order)
+    are built from the library's slot table when first asked for."""
+
     def __init__(self):
         self.n_records = 0
         self.n_values_total = 0
@@ -103,8 +123,31 @@ class ExtractResult:
         self.n_layers = 0
         self.tile_launches = 0
         self.note = ""
-        self.slots: Dict[int, Slot] = {}
-        self.slot_ids: List[int] = []
+        self._table = None   # (bytes of the library's slot table, workspace as int64, its base address, offsets per slot)
+        self._slots = None
+        self._slot_ids = None
+
+    def _build(self):
+        table, ws64, base, n_offsets = self._table
+        n = len(table) // ctypes.sizeof(SlotView)
+        self._slots, self._slot_ids = {}, []
+        for sv in ((SlotView * n).from_buffer_copy(table) if n else ()):
+            v0 = ((sv.values or base) - base) // 8
+            o0 = (sv.offsets - base) // 8 if sv.offsets else None
+            self._slots[sv.slot_id] = Slot(sv.slot_id, sv.fixed_arity, sv.n_values, ws64, v0, o0, n_offsets)
+            self._slot_ids.append(sv.slot_id)
+
+    @property
+    def slots(self) -> Dict[int, Slot]:
+        if self._slots is None:
+            self._build()
+        return self._slots
+
+    @property
+    def slot_ids(self) -> List[int]:
+        if self._slot_ids is None:
+            self._build()
+        return self._slot_ids
 
 
 class Plan:
@@ -181,18 +224,10 @@ class Plan:
         out.n_layers = res.n_layers
         out.tile_launches = res.tile_launches
         out.note = lib().fbx_last_error(self._h).decode()
-        base = self._ws.data_ptr()
+        # the library's slot table is overwritten by the next call: copy the plain numbers out now
         ws64 = self._ws[: self._ws.numel() // 8 * 8].view(torch.int64)
-        for i in range(res.n_slots):
-            sv = res.slots[i]
-            v0 = (sv.values - base) // 8
-            vals = ws64[v0:v0 + sv.n_values]
-            offs = None
-            if sv.offsets:
-                o0 = (sv.offsets - base) // 8
-                offs = ws64[o0:o0 + n_records + 1]
-            out.slots[sv.slot_id] = Slot(sv.slot_id, sv.fixed_arity, sv.n_values, vals, offs)
-            out.slot_ids.append(sv.slot_id)
+        table = ctypes.string_at(res.slots, res.n_slots * ctypes.sizeof(SlotView)) if res.n_slots else b""
+        out._table = (table, ws64, self._ws.data_ptr(), n_records + 1)
         return out
 
 
