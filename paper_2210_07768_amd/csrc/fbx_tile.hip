@@ -527,14 +527,35 @@ __device__ __forceinline__ uint64_t bucket_sign(const OpProg& d, const uint8_t* 
   return mix64(d.key + lo);
 }
 
+// The prefix of a filter: its first eight bytes are fetched once and kept in registers, so that
+// the byte-by-byte comparison does not wait on a table lookup per byte; longer prefixes (rare)
+// go on in the table.
+struct Prefix {
+  const uint8_t* pre;
+  uint32_t plen, lo, hi;
+  __device__ __forceinline__ Prefix(const uint8_t* aux, const OpProg& d) : pre(aux + d.aux_off), plen(d.aux_len), lo(0), hi(0) {
+#pragma unroll
+    for (uint32_t k = 0; k < 8u; ++k) {
+      const uint32_t b = k < plen ? pre[k] : 0u;
+      if (k < 4u) lo |= b << (8u * k);
+      else hi |= b << (8u * (k - 4u));
+    }
+  }
+  __device__ __forceinline__ uint32_t at(uint32_t k) const {  // byte k of the prefix, k < plen
+    if (k < 4u) return (lo >> (8u * k)) & 0xffu;
+    if (k < 8u) return (hi >> (8u * (k - 4u))) & 0xffu;
+    return pre[k];
+  }
+};
+
 // Number of signs a ragged root operator (not n-gram) produces on [s, e).
 template <class Src>
 __device__ __forceinline__ uint32_t ragged_root_count(const Src& src, const OpProg& d, const uint8_t* aux, uint32_t s,
                                                       uint32_t e) {
   const bool multi = d.flags & F_MULTI;
   if (d.kind != OP_FILTER) return count_commas(src, s, e) + 1u;  // multi-valued hash / bucket
-  const uint8_t* pre = aux + d.aux_off;
-  const uint32_t plen = d.aux_len;
+  const Prefix pre(aux, d);
+  const uint32_t plen = pre.plen;
   uint32_t cnt = 0, k = 0;
   bool match = true;
   for_each_byte(src, s, e, [&](uint32_t b) {
@@ -542,7 +563,7 @@ __device__ __forceinline__ uint32_t ragged_root_count(const Src& src, const OpPr
       cnt += (match && k >= plen) ? 1u : 0u;
       k = 0; match = true;
     } else {
-      if (k < plen && b != pre[k]) match = false;
+      if (k < plen && b != pre.at(k)) match = false;
       ++k;
     }
   });
@@ -564,8 +585,8 @@ __device__ __forceinline__ void ragged_root_emit(const Src& src, const OpProg& d
     });
     *dst = h;
   } else if (d.kind == OP_FILTER) {
-    const uint8_t* pre = aux + d.aux_off;
-    const uint32_t plen = d.aux_len;
+    const Prefix pre(aux, d);
+    const uint32_t plen = pre.plen;
     const uint64_t key = d.key;
     uint64_t h = key;
     uint32_t k = 0;
@@ -575,7 +596,7 @@ __device__ __forceinline__ void ragged_root_emit(const Src& src, const OpProg& d
         if (match && k >= plen) *dst++ = h;
         h = key; k = 0; match = true;
       } else {
-        if (k < plen && b != pre[k]) match = false;
+        if (k < plen && b != pre.at(k)) match = false;
         h = (h ^ b) * kPrime;
         ++k;
       }
