@@ -527,12 +527,12 @@ __device__ __forceinline__ uint64_t bucket_sign(const OpProg& d, const uint8_t* 
   return mix64(d.key + lo);
 }
 
-// The prefix of a filter: its first eight bytes are fetched once and kept in registers, so that
-// the byte-by-byte comparison does not wait on a table lookup per byte; longer prefixes (rare)
-// go on in the table.
+// The prefix of a filter.  Its first eight bytes are fetched once and kept in two registers, with
+// the masks of the bytes that count, so that a token is tested by comparing words; longer
+// prefixes (rare) go on byte by byte in the table.
 struct Prefix {
   const uint8_t* pre;
-  uint32_t plen, lo, hi;
+  uint32_t plen, lo, hi, mlo, mhi;
   __device__ __forceinline__ Prefix(const uint8_t* aux, const OpProg& d) : pre(aux + d.aux_off), plen(d.aux_len), lo(0), hi(0) {
 #pragma unroll
     for (uint32_t k = 0; k < 8u; ++k) {
@@ -540,34 +540,49 @@ struct Prefix {
       if (k < 4u) lo |= b << (8u * k);
       else hi |= b << (8u * (k - 4u));
     }
-  }
-  __device__ __forceinline__ uint32_t at(uint32_t k) const {  // byte k of the prefix, k < plen
-    if (k < 4u) return (lo >> (8u * k)) & 0xffu;
-    if (k < 8u) return (hi >> (8u * (k - 4u))) & 0xffu;
-    return pre[k];
+    mlo = plen >= 4u ? ~0u : (1u << (8u * plen)) - 1u;
+    mhi = plen <= 4u ? 0u : (plen >= 8u ? ~0u : (1u << (8u * (plen - 4u))) - 1u);
   }
 };
+
+// Whether the token [t, te) begins with the prefix.
+__device__ __forceinline__ bool starts_with(const LdsSrc& src, uint32_t t, uint32_t te, const Prefix& pre) {
+  if (te - t < pre.plen) return false;
+  if (pre.plen == 0u) return true;
+  uint32_t x0, x1;
+  window8(src, t, x0, x1);
+  bool ok = (((x0 ^ pre.lo) & pre.mlo) | ((x1 ^ pre.hi) & pre.mhi)) == 0u;
+  for (uint32_t k = 8u; k < pre.plen && ok; ++k) ok = src.byte(t + k) == pre.pre[k];
+  return ok;
+}
+__device__ __forceinline__ bool starts_with(const GlobalSrc& src, uint32_t t, uint32_t te, const Prefix& pre) {
+  if (te - t < pre.plen) return false;
+  bool ok = true;
+  for (uint32_t k = 0; k < pre.plen && ok; ++k) ok = src.byte(t + k) == pre.pre[k];
+  return ok;
+}
+
+// Calls f(t, te) for every token [t, te) of the field [s, e), in order: the field itself, or with
+// multi its comma-separated parts (one more than it has commas, empty ones included).
+template <class Src, class F>
+__device__ __forceinline__ void for_each_token(const Src& src, uint32_t s, uint32_t e, bool multi, F&& f) {
+  uint32_t t = s;
+  for (;;) {
+    const uint32_t te = multi ? next_comma(src, t, e) : e;
+    f(t, te);
+    if (te >= e) break;
+    t = te + 1u;
+  }
+}
 
 // Number of signs a ragged root operator (not n-gram) produces on [s, e).
 template <class Src>
 __device__ __forceinline__ uint32_t ragged_root_count(const Src& src, const OpProg& d, const uint8_t* aux, uint32_t s,
                                                       uint32_t e) {
-  const bool multi = d.flags & F_MULTI;
   if (d.kind != OP_FILTER) return count_commas(src, s, e) + 1u;  // multi-valued hash / bucket
   const Prefix pre(aux, d);
-  const uint32_t plen = pre.plen;
-  uint32_t cnt = 0, k = 0;
-  bool match = true;
-  for_each_byte(src, s, e, [&](uint32_t b) {
-    if (multi && b == ',') {
-      cnt += (match && k >= plen) ? 1u : 0u;
-      k = 0; match = true;
-    } else {
-      if (k < plen && b != pre.at(k)) match = false;
-      ++k;
-    }
-  });
-  cnt += (match && k >= plen) ? 1u : 0u;
+  uint32_t cnt = 0;
+  for_each_token(src, s, e, d.flags & F_MULTI, [&](uint32_t t, uint32_t te) { cnt += starts_with(src, t, te, pre) ? 1u : 0u; });
   return cnt;
 }
 
@@ -584,24 +599,12 @@ __device__ __forceinline__ void ragged_root_emit(const Src& src, const OpProg& d
       else h = (h ^ b) * kPrime;
     });
     *dst = h;
-  } else if (d.kind == OP_FILTER) {
+  } else if (d.kind == OP_FILTER) {  // only the tokens that pass are hashed
     const Prefix pre(aux, d);
-    const uint32_t plen = pre.plen;
     const uint64_t key = d.key;
-    uint64_t h = key;
-    uint32_t k = 0;
-    bool match = true;
-    for_each_byte(src, s, e, [&](uint32_t b) {
-      if (multi && b == ',') {
-        if (match && k >= plen) *dst++ = h;
-        h = key; k = 0; match = true;
-      } else {
-        if (k < plen && b != pre.at(k)) match = false;
-        h = (h ^ b) * kPrime;
-        ++k;
-      }
+    for_each_token(src, s, e, multi, [&](uint32_t t, uint32_t te) {
+      if (starts_with(src, t, te, pre)) *dst++ = hash_span(src, t, te, key);
     });
-    if (match && k >= plen) *dst = h;
   } else {  // OP_BUCKET, multi-valued
     NumState ns;
     for_each_byte(src, s, e, [&](uint32_t b) {
@@ -1241,6 +1244,10 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   }
   if (P.n_ragged) critical_phase(ps.count_units(), &s_ctr[1], &s_done, [&](uint32_t u) { ps.count_unit(u); });
   else __syncthreads();
+  if (P.n_ragged && FBX_SKIP(0x800u)) {  // (tuning builds: the counting units once more, to weigh them)
+    for (uint32_t u = wave; u < ps.count_units(); u += kWaves) ps.count_unit(u);
+    __syncthreads();
+  }
   FBX_MARK(4);
   hook();
   // ---- phase B: the counts of later layers, layer by layer

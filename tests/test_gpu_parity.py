@@ -90,6 +90,52 @@ def test_crosses_of_multi_valued_hashes_with_single_signs(mode):
     check(MULTI_CROSS_SPEC, *_cat(recs), mode, label=f"multi-valued crosses {mode}")
 
 
+# prefixes of every length up to eight bytes, the limit of what the kernel keeps in registers, and
+# beyond it; a comma inside the prefix (an ordinary byte for a single-valued filter, never matched
+# by a token of a multi-valued one); filters that feed later layers
+def _filter_spec():
+    lines = ["fbx 1", "fields 3"]
+    slot = 0
+    for plen in (0, 1, 2, 3, 4, 5, 7, 8, 9, 12):
+        for multi, field in ((0, 0), (1, 1)):
+            lines.append(f"op f{plen}_{multi} filter slot={slot} seed={100 + slot} emit=1 field={field} "
+                         f"multi={multi} prefix={(b'abababababab'[:plen]).hex()}")
+            slot += 1
+    lines.append(f"op c0 filter slot={slot} seed=50 emit=1 field=0 multi=0 prefix={b'a,b'.hex()}")
+    lines.append(f"op c1 filter slot={slot + 1} seed=51 emit=0 field=1 multi=1 prefix={b'a,b'.hex()}")
+    lines.append(f"op h hash slot={slot + 2} seed=52 emit=1 field=2 multi=0")
+    lines.append(f"op x cross slot={slot + 3} seed=53 emit=1 a=f2_1 b=h")
+    lines.append(f"op y concat slot={slot + 4} emit=1 a=c1 b=f1_0")
+    lines.append(f"op z cross slot={slot + 5} seed=54 emit=1 a=x b=f0_0")
+    return "\n".join(lines) + "\n"
+
+
+@pytest.mark.parametrize("mode", [{}, {"one_launch": 0}, {"fused": 0}] + TILE_MODES,
+                         ids=["default", "two_launches", "per_layer"] + TILE_IDS)
+def test_filters_with_short_and_long_prefixes(mode):
+    rng = random.Random(4242)
+
+    def token():
+        n = rng.choice([0, 1, 2, 3, 4, 5, 7, 8, 9, 11, 12, 13, 20])
+        t = "abababababababababababab"[:n]
+        if n and rng.random() < 0.4:   # a mismatch at a random position, the last one included
+            k = rng.randrange(n)
+            t = t[:k] + rng.choice("bax") + t[k + 1:]
+        return t + (rng.choice(["", "b", "zz"]) if rng.random() < 0.3 else "")
+
+    recs = []
+    for i in range(300):
+        single = rng.choice([token(), "a,b" + token(), "a," + token(), token() + "," + token()])
+        items = ",".join(token() for _ in range(rng.choice([1, 1, 2, 3, 6, 18, 30])))
+        rec = f"{single}\t{items}\tk{i % 5}"
+        if i % 11 == 5:
+            rec = single  # the list field is missing: one empty token
+        recs.append((rec + ("\n" if i % 4 else "")).encode())
+    # a record that does not fit the staged text is read in place
+    recs.append(b"abab\t" + ",".join(token() for _ in range(9000)).encode() + b"\tk1\n")
+    check(_filter_spec(), *_cat(recs), mode, label=f"filters {mode}")
+
+
 @pytest.mark.parametrize("cfg,one_launch", [(5, True), (2, False), (3, True), (4, False)])
 def test_full_size_workloads_on_sampled_records(cfg, one_launch):
     """The benchmark configurations at their full sizes, run the way bench.py times them (a first
