@@ -106,9 +106,12 @@ uint32_t round16(uint64_t x) { return static_cast<uint32_t>((x + 15u) & ~uint64_
 // LDS layout of the tile kernel for tiles of 2^lt records and raw_cap staged bytes.
 void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParams& tp) {
   const uint32_t T = 1u << lt;
-  tp.n_mh = 0;
-  for (uint32_t i = h.tile_list_begin[TL_RAGROOT]; i < h.tile_list_begin[TL_RAGROOT + 1]; ++i)
-    if (h.ops[h.tile_lists[i]].d.kind == OP_HASH) ++tp.n_mh;  // the list is sorted by kind, hashes first
+  tp.n_mh = tp.n_split = 0;  // (the list is sorted: multi-valued hashes, other multi-valued operators, the rest)
+  for (uint32_t i = h.tile_list_begin[TL_RAGROOT]; i < h.tile_list_begin[TL_RAGROOT + 1]; ++i) {
+    const OpDesc& d = h.ops[h.tile_lists[i]].d;
+    if (d.kind == OP_HASH) ++tp.n_mh;
+    if (d.flags & F_MULTI) ++tp.n_split;
+  }
   tp.log2T = lt;
   tp.raw_cap = raw_cap;
   tp.row_stride = (h.n_fields + 1u) | 1u;  // odd: neighbouring records start in different banks

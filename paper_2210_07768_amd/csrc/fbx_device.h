@@ -60,6 +60,7 @@ struct TileParams {
   uint32_t n_ops, n_layers, n_ragged, n_rnr, n_lists, aux_bytes;  // (n_rnr: operators in rnr)
   uint32_t rnr_words;   // 32-bit words of the rnr table
   uint32_t n_mh;        // multi-valued hashes: the first n_mh entries of the ragged root list
+  uint32_t n_split;     // multi-valued root operators of any kind: the first n_split entries of that list
   uint32_t n_tiles, n_fields, n_stage;
   uint32_t grid;        // upper limit of workgroups to launch (0: as many as run at the same time)
   uint32_t log2T;       // records per tile = 1 << log2T (at most 64)

@@ -16,7 +16,8 @@ enum OpKind : uint32_t { OP_HASH = 1, OP_NGRAM = 2, OP_BUCKET = 3, OP_FILTER = 4
 enum OpFlags : uint32_t {
   F_MULTI = 1u,
   F_EMIT = 2u,
-  F_STREAM = 4u  // tile kernel: no later operator reads the signs from memory (they are only the caller's)
+  F_STREAM = 4u,  // tile kernel: no later operator reads the signs from memory (they are only the caller's)
+  F_NEVER = 8u    // a multi-valued filter whose prefix holds a comma: no token can begin with it
 };
 
 // Device-visible operator descriptor (64 bytes).  Filled once at plan time.

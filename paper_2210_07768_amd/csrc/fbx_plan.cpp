@@ -356,10 +356,21 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
       else lists[TL_LAYER + 2 * (d.layer - 2) + (single ? 0 : 1)].push_back(i);
     }
   }
-  // neighbouring lanes run neighbouring list entries: keep like with like
+  // neighbouring lanes run neighbouring list entries: keep like with like.  Multi-valued hashes
+  // come first, then the other multi-valued operators, then the single-valued filters.
+  auto root_class = [&](uint32_t x) {
+    const OpDesc& d = plan.ops[x].d;
+    return d.kind == OP_HASH ? 0u : ((d.flags & F_MULTI) ? 1u : 2u);
+  };
   std::stable_sort(lists[TL_RAGROOT].begin(), lists[TL_RAGROOT].end(), [&](uint32_t x, uint32_t y) {
-    return plan.ops[x].d.kind < plan.ops[y].d.kind;
+    return root_class(x) != root_class(y) ? root_class(x) < root_class(y) : plan.ops[x].d.kind < plan.ops[y].d.kind;
   });
+  for (HostOp& op : plan.ops) {
+    OpDesc& d = op.d;
+    if (d.kind == OP_FILTER && (d.flags & F_MULTI) && d.aux_len &&
+        std::memchr(plan.aux.data() + d.aux_off, ',', d.aux_len))
+      d.flags |= F_NEVER;
+  }
   for (const std::vector<uint32_t>& l : lists) {
     plan.tile_list_begin.push_back(static_cast<uint32_t>(plan.tile_lists.size()));
     plan.tile_lists.insert(plan.tile_lists.end(), l.begin(), l.end());

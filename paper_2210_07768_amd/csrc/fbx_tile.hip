@@ -199,7 +199,7 @@ constexpr uint32_t kTabs = 0x09090909u, kCommas = 0x2c2c2c2cu;
 // takes an equal run of the 16-byte chunks that cover the range and counts its
 // delimiters; a prefix sum over the group turns the counts into ordinals, and a second
 // walk calls emit(k, position) for the k-th delimiter, k < limit.  Returns the number of
-// delimiters in the whole range.  Every lane of the wavefront calls it; those with
+// delimiters in the whole range.  Every lane of a group calls it; those with
 // act == false (and, with limit == 0, all of them) emit nothing.
 template <class Emit>
 __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs, uint32_t re, bool act, uint32_t pat,
@@ -697,6 +697,7 @@ struct Pass {
   bool& overflow;
   uint32_t lb_tile;   // tile number when counts are to be published (one-launch mode), else kNoRow
   bool need_table;    // the pass goes on to write: keep comma positions while counting
+  bool split_all;     // filters and buckets with lists are counted a few lanes a field, like the hashes (counting launch)
 
   // This lane's place in a unit, worked out anew (and hidden from the optimiser's view of the
   // tile loop): otherwise every address that follows from it is computed once per kernel and
@@ -749,9 +750,43 @@ struct Pass {
       if (pr < np && j == 0) sh.cnt[row * T + rr] = act ? commas + 1u : 0u;  // items = commas + 1 (far below kMaxCount)
     }
   }
-  // The other ragged root operators and the n-grams (lists TL_RAGROOT and TL_NGRAM, taken as
-  // one), G operators per unit; records read in place count their multi-valued hashes here too.
-  __device__ __forceinline__ uint32_t count_skip() const { return Src::kTable ? P.n_mh : 0u; }
+  // The other multi-valued root operators of staged records (filters and buckets: entries n_mh ..
+  // n_split - 1 of the ragged root list) are counted the same way, a few lanes a field: a bucket
+  // list has one sign per item; a filter tests the token that starts the field and the one after
+  // every comma.  (A token is as long as the prefix or longer exactly when the prefix's bytes
+  // follow its start and hold no comma: a prefix with a comma passes nothing, F_NEVER.)
+  __device__ __forceinline__ void split_others() {
+    const uint32_t tid = thread_id();
+    const uint32_t np = (P.n_split - P.n_mh) * T;
+    uint32_t lg = 0;
+    while (lg < 6u && (np << (lg + 1u)) <= kTileThreads) ++lg;
+    const uint32_t j = tid & ((1u << lg) - 1u);
+    for (uint32_t p0 = 0; p0 < np; p0 += kTileThreads >> lg) {
+      const uint32_t pr = p0 + (tid >> lg);
+      const uint32_t i = pr / T, rr = pr & (T - 1u);
+      const bool in = pr < np, act = in && rr < nb;
+      const OpProg& d = sh.prog[sh.list_begin[TL_RAGROOT] + P.n_mh + (in ? i : 0u)];
+      const bool filter = d.kind == OP_FILTER;
+      uint32_t s = 0, e = 0;
+      if (act) src.span(rr, d.field, s, e);
+      uint32_t c;
+      if (filter) {  // (uniform over the lanes of a field)
+        const Prefix pre(sh.aux, d);
+        uint32_t hits = (act && j == 0 && starts_with(src, s, e, pre)) ? 1u : 0u;
+        split_bytes(src.raw8, s, e, act, kCommas, lg, j, ~0u, [&](uint32_t, uint32_t pos) {
+          hits += starts_with(src, pos + 1u, e, pre) ? 1u : 0u;
+        });
+        for (uint32_t w = 1; w < (1u << lg); w <<= 1) hits += __shfl_xor(hits, (int)w, 64);
+        c = (d.flags & F_NEVER) ? 0u : hits;
+      } else {
+        c = split_bytes(src.raw8, s, e, act, kCommas, lg, j, 0u, [](uint32_t, uint32_t) {}) + 1u;
+      }
+      if (in && j == 0) sh.cnt[d.rag_row * T + rr] = act ? c : 0u;
+    }
+  }
+  // The single-valued filters and the n-grams (lists TL_RAGROOT and TL_NGRAM, taken as one), G
+  // operators per unit; records read in place count all their ragged root operators here.
+  __device__ __forceinline__ uint32_t count_skip() const { return !Src::kTable ? 0u : (split_all ? P.n_split : P.n_mh); }
   __device__ __forceinline__ uint32_t count_root_units() const {
     return (sh.list_begin[TL_RAGROOT + 1] - sh.list_begin[TL_RAGROOT] - count_skip() + G - 1u) / G;
   }
@@ -1206,7 +1241,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   constexpr bool WRITE = MODE != 0;
   const uint32_t tid = thread_id(), lane = tid & 63u, wave = tid >> 6;
   const uint32_t T = 1u << P.log2T;
-  Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow, MODE == 2 ? tile : kNoRow, WRITE};
+  Pass<Src> ps{P, sh, src, nb, g_first, T, 64u >> P.log2T, lane & (T - 1u), lane >> P.log2T, false, 0, malformed, overflow, MODE == 2 ? tile : kNoRow, WRITE, MODE == 0};
   ps.live = ps.r < nb;
   ps.g = g_first + ps.r;
   // the single-valued hashes and buckets of layer 1 fill whatever phase has idle wavefronts
@@ -1241,6 +1276,9 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
       __syncthreads();
       ps.split_items();
     }
+    // (the counting launch only: a launch that writes has single-valued fields to hash while a few
+    // wavefronts count these operators unit by unit, below)
+    if (MODE == 0 && P.n_split > P.n_mh) ps.split_others();
   }
   if (P.n_ragged) critical_phase(ps.count_units(), &s_ctr[1], &s_done, [&](uint32_t u) { ps.count_unit(u); });
   else __syncthreads();
