@@ -25,8 +25,8 @@ HBM_PEAK_GBPS = 8000.0
 # WRITE_SIZE, each scaled by what the same counter reads for a device-to-device copy of known
 # size), for the workloads that were profiled: see profiles/.  Other runs report null.
 MEASURED_TRAFFIC = {
-    # (workload, records, launch sequence): bytes per launch; profiles/k_tile_config5_hbm_traffic.md
-    ("config5", 16000000, "one_launch"): 42386037351,
+    # (workload, records, launch sequence, compiled for the plan): bytes per launch; profiles/k_tile_config5_hbm_traffic.md
+    ("config5", 16000000, "one_launch", 0): 42386037351,
 }
 
 
@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--records", type=int, default=None, help="override the record count (debugging)")
     ap.add_argument("--fused", type=int, default=1)
     ap.add_argument("--lds-pad", type=int, default=0)
+    ap.add_argument("--compile", type=int, default=1,
+                    help="1: the tile kernel is compiled for the plan at run time, during the warm-up calls "
+                         "(plan option compile, default); 0: the generic kernel")
     ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
                     help="extra plan option (tuning), e.g. --opt tile_log2=4")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -125,6 +128,7 @@ def main():
     plan = B.Plan(w.spec)
     plan.set_option("profile", 1)
     plan.set_option("fused", args.fused)
+    plan.set_option("compile", args.compile)
     if args.lds_pad:
         plan.set_option("lds_pad", args.lds_pad)
     for kv in args.opt:
@@ -134,9 +138,15 @@ def main():
     log(f"[bench] workspace {ws.numel() / 1e9:.2f} GB, {res.n_values_total} signs, "
         f"{len(res.slot_ids)} slots, malformed {res.n_malformed_numeric}")
 
+    notes = [res.note] if res.note else []
     for _ in range(args.warmup):
-        plan.extract(d_raw, d_off)
+        r = plan.extract(d_raw, d_off)
+        if r.note:
+            notes.append(r.note)
     torch.cuda.synchronize()
+    n_compiled, compile_ms = plan.compiled()
+    if args.compile:
+        log(f"[bench] {n_compiled} tile kernels compiled for the plan in {compile_ms / 1e3:.1f} s (before the timed calls)")
     kernel_ms = {}
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -187,6 +197,9 @@ def main():
         launch, kname = ("one_launch", "fbx::k_tile<2>") if has_ragged else ("write", "fbx::k_tile<1>")
     else:
         launch, kname = "count+write", "fbx::k_tile<1>"
+    compiled_now = plan.compiled()[0]
+    if compiled_now and res.tile_launches and "generic kernel" not in " ".join(notes + [res.note]):
+        kname = f"fbx_tile_fixed_{kname[-2]} ({kname} compiled for the plan)"
 
     out = {
         "metric": "records/s", "value": R / (ms_per_step * 1e-3), "unit": "records/s",
@@ -194,18 +207,25 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": w.name, "records": R, "fields": w.n_fields, "ops": w.n_ops, "layers": w.n_layers,
-                   "raw_bytes": raw_len, "signs": int(n_signs), "launch": launch},
+                   "raw_bytes": raw_len, "signs": int(n_signs), "launch": launch, "compile": args.compile},
         "signs_per_s": n_signs / (ms_per_step * 1e-3),
         "path_algorithmic_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "path_frac_of_hbm_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernel_ms": kernels,
         "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get((w.name, R, launch)),
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC.get((w.name, R, launch, args.compile)),
                      "algorithmic_bytes_per_launch": int(launches[dom]), "avg_launch_ms": dom_ms},
     }
+    if args.compile:
+        # host time spent compiling, all of it before the timed calls unless compiled_in_timed_calls says otherwise
+        out["compile"] = {"kernels": compiled_now, "ms": round(plan.compiled()[1], 1),
+                          "compiled_in_timed_calls": compiled_now - n_compiled}
     if res.note:
-        out["note"] = res.note
+        notes.append(res.note)
+    if notes:
+        out["note"] = "; ".join(dict.fromkeys(notes))
     if not args.no_cpu:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(w)

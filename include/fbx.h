@@ -166,9 +166,22 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
  *   "lds_budget"   LDS bytes per workgroup the tile size is chosen for (default 81920)
  *   "grid_limit"   0: as many workgroups as run at the same time (default); else at most that
  *   "profile"      1: time every kernel of fbx_extract with HIP events
+ *   "compile"      1: compile the tile kernel for this plan at run time, as Section 4 does with
+ *                  the meta-kernel of a layer: the first fbx_extract that meets a tile shape
+ *                  compiles the kernels it launches with the plan's counts and table offsets as
+ *                  literals (a few seconds each, on the host, inside that call), later calls
+ *                  reuse them.  When the compiler or the kernel sources (csrc/ beside the
+ *                  library) are missing the generic kernel runs and fbx_last_error says why.
+ *                  0: one generic kernel for every plan (default)
  * Errors: FBX_E_ARG for an unknown key or an out-of-range value.
  */
 fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value);
+
+/*
+ * Tile kernels compiled for the plan so far (option "compile" = 1) and the host time spent
+ * compiling them, in milliseconds.  Either pointer may be NULL.
+ */
+fbx_status fbx_plan_compiled(const fbx_plan* plan, uint32_t* n_kernels, double* ms);
 
 /*
  * Kernel timings of the last fbx_extract (needs option "profile" = 1).

@@ -19,7 +19,7 @@ OK, E_ARG, E_SPEC, E_NOMEM, E_INPUT, E_HIP = 0, -1, -2, -3, -4, -5
 EXPORTS = [
     "fbx_plan_create", "fbx_plan_destroy", "fbx_plan_workspace_hint", "fbx_plan_set_workspace",
     "fbx_extract", "fbx_last_error", "fbx_status_str", "fbx_plan_info", "fbx_plan_set_option",
-    "fbx_plan_kernel_ms", "fbx_arena_alloc", "fbx_arena_reset",
+    "fbx_plan_kernel_ms", "fbx_plan_compiled", "fbx_arena_alloc", "fbx_arena_reset",
 ]
 
 
@@ -72,6 +72,8 @@ def lib():
         L.fbx_last_error.argtypes = [vp]
         L.fbx_status_str.restype = ctypes.c_char_p
         L.fbx_status_str.argtypes = [ctypes.c_int]
+        L.fbx_plan_compiled.restype = ctypes.c_int
+        L.fbx_plan_compiled.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_double)]
         L.fbx_plan_info.restype = ctypes.c_int
         L.fbx_plan_info.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(u32), vp, vp]
         L.fbx_plan_set_option.restype = ctypes.c_int
@@ -181,6 +183,12 @@ class Plan:
         arity = (ctypes.c_uint32 * max(n_ops.value, 1))()
         self._check(lib().fbx_plan_info(self._h, None, None, layers, arity))
         return n_ops.value, n_layers.value, list(layers)[:n_ops.value], list(arity)[:n_ops.value]
+
+    def compiled(self) -> Tuple[int, float]:
+        """(tile kernels compiled for this plan so far, milliseconds spent compiling them)."""
+        n, ms = ctypes.c_uint32(), ctypes.c_double()
+        self._check(lib().fbx_plan_compiled(self._h, ctypes.byref(n), ctypes.byref(ms)))
+        return n.value, ms.value
 
     def set_option(self, key: str, value: int):
         self._check(lib().fbx_plan_set_option(self._h, key.encode(), int(value)))

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfbx.so")
-SOURCES = ["fbx_plan.cpp", "fbx_api.cpp", "fbx_support.hip", "fbx_walk.hip", "fbx_tile.hip"]
+SOURCES = ["fbx_plan.cpp", "fbx_api.cpp", "fbx_jit.cpp", "fbx_support.hip", "fbx_walk.hip", "fbx_tile.hip"]
 HEADERS = ["fbx_internal.h", "fbx_device.h", os.path.join(_ROOT, "include", "fbx.h")]
 
 
@@ -32,7 +32,7 @@ def command() -> list:
     ] + (["-DFBX_TILE_PROF"] if os.environ.get("FBX_TILE_PROF") else []) + [
         "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
         "-o", LIB,
-    ] + [os.path.join(CSRC, s) for s in SOURCES]
+    ] + [os.path.join(CSRC, s) for s in SOURCES] + ["-ldl"]
 
 
 def stale() -> bool:

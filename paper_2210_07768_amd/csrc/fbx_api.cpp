@@ -48,6 +48,8 @@ struct fbx_plan {
   uint32_t dbg = 0;
   uint32_t grid_limit = 0;
   int one_launch = 1;             // size ragged arrays from the last call and skip the counting launch
+  int compile = 0;                // compile the tile kernel for this plan at run time (Section 4's meta-kernel)
+  TileJit jit;
 
   // what the last successful call taught about ragged sizes (signs per ragged operator)
   bool learned = false;
@@ -231,6 +233,13 @@ void fbx_plan_destroy(fbx_plan* plan) {
   delete plan;
 }
 
+fbx_status fbx_plan_compiled(const fbx_plan* plan, uint32_t* n_kernels, double* ms) {
+  if (!plan) return FBX_E_ARG;
+  if (n_kernels) *n_kernels = plan->jit.compiled();
+  if (ms) *ms = plan->jit.compile_ms();
+  return FBX_OK;
+}
+
 fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_layers, uint32_t* layer_of_op,
                          uint32_t* arity_of_op) {
   if (!plan) return FBX_E_ARG;
@@ -261,6 +270,9 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "lds_budget") {
     if (value < 4096 || value > 160 * 1024) { plan->error = "lds_budget must be in 4096..163840"; return FBX_E_ARG; }
     plan->lds_budget = static_cast<uint32_t>(value);
+  } else if (k == "compile") {
+    if (value != 0 && value != 1) { plan->error = "compile must be 0 or 1"; return FBX_E_ARG; }
+    plan->compile = static_cast<int>(value);
   } else if (k == "one_launch") {
     if (value != 0 && value != 1) { plan->error = "one_launch must be 0 or 1"; return FBX_E_ARG; }
     plan->one_launch = static_cast<int>(value);
@@ -399,6 +411,16 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     if (e_ != hipSuccess) return hip_fail(plan, e_, what);     \
   } while (0)
 
+  const double compile_ms_before = plan->jit.compile_ms();
+  // The tile kernel in one of its modes: the one compiled for this plan if the plan asks for
+  // that and it can be had, else the generic one.
+  auto tile_launch = [&](const TileParams& Q, int mode) -> hipError_t {
+#ifndef FBX_TILE_PROF
+    if (plan->compile && !Q.dbg)
+      if (const FixedTileKernel* k = plan->jit.get(Q, mode)) return launch_tile_fixed(*k, Q, st);
+#endif
+    return launch_tile(Q, mode, st);
+  };
   // One attempt: everything is enqueued on the stream, then one synchronisation.
   auto run = [&](bool one) -> fbx_status {
     for (Timer& t : plan->timers) t.used = false;
@@ -442,7 +464,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
         tick(3, 1);
         FBX_LAUNCH(launch_fill64(Q.lb_state, uint64_t(h.n_ragged) * g.n_tiles, 0, st), "look-back state");
         tick(4, 0);
-        FBX_LAUNCH(launch_tile(Q, 2, st), "tile kernel (one launch)");
+        FBX_LAUNCH(tile_launch(Q, 2), "tile kernel (one launch)");
         tick(4, 1);
         plan->tile_launch_layer.push_back(1);
       } else {
@@ -451,7 +473,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
           FBX_LAUNCH(launch_programs(P, st), "program kernel");
           if (g.n_tiles) {
             tick(1, 0);
-            FBX_LAUNCH(launch_tile(Q, 0, st), "tile kernel (counting)");
+            FBX_LAUNCH(tile_launch(Q, 0), "tile kernel (counting)");
             tick(1, 1);
           }
           tick(2, 0);
@@ -463,7 +485,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
         tick(3, 1);
         if (g.n_tiles) {
           tick(4, 0);
-          FBX_LAUNCH(launch_tile(Q, 1, st), "tile kernel");
+          FBX_LAUNCH(tile_launch(Q, 1), "tile kernel");
           tick(4, 1);
           plan->tile_launch_layer.push_back(1);
         }
@@ -612,6 +634,15 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   out->n_layers = h.n_layers;
   out->slots = plan->slots.data();
   plan->error = fell_back ? fell_back : "";  // (not an error: fbx_last_error doubles as a note after FBX_OK)
+  if (plan->compile) {
+    std::string note = plan->jit.note();
+    if (plan->jit.compile_ms() > compile_ms_before) {
+      char buf[96];
+      snprintf(buf, sizeof buf, "compile=1: tile kernels compiled for this plan in %.0f ms", plan->jit.compile_ms() - compile_ms_before);
+      note = note.empty() ? std::string(buf) : note + "; " + buf;
+    }
+    if (!note.empty()) plan->error += (plan->error.empty() ? "" : "; ") + note;
+  }
   out->tile_launches = g.tile_engine ? (one ? 1u : (h.n_ragged ? 2u : 1u)) : 0u;
   return FBX_OK;
 }

@@ -76,12 +76,52 @@ struct TileParams {
   uint32_t dbg;    // phases to leave out (tuning builds only; results are then wrong)
 };
 
+// The fields of TileParams that the plan and the tile size fix (all but addresses, sizes of
+// the batch and tuning switches): a kernel compiled for one plan has them as literals.
+#define FBX_TILE_FIXED_FIELDS(X)                                                                                     \
+  X(n_ops) X(n_layers) X(n_ragged) X(n_rnr) X(n_lists) X(aux_bytes) X(rnr_words) X(n_mh) X(n_split) X(n_fields)     \
+  X(n_stage) X(log2T) X(raw_cap) X(row_stride) X(o_off) X(o_rs) X(o_re) X(o_rows) X(o_raw) X(o_stage) X(o_cnt)     \
+  X(o_start) X(o_run) X(o_base) X(o_prog) X(o_lbeg) X(o_rnr) X(o_aux) X(o_tot) X(o_ioff) X(o_ctab) X(o_cap)         \
+  X(item_cap) X(lds_bytes)
+
+#ifndef __HIPCC_RTC__  // (the launch wrappers are host code: not for the run-time compiler)
 // mode 0: counting launch; 1: writing launch (bases from the scan over tiles);
 // 2: counting and writing in one launch (bases by look-back, arrays sized by row_cap)
 hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st);
 hipError_t launch_fill64(uint64_t* p, uint64_t n, uint64_t value, hipStream_t st);
-uint32_t tile_max_lds();
-uint32_t tile_cu_count();  // dynamic LDS a workgroup of the tile kernel may ask for on this device
+uint32_t tile_max_lds();  // dynamic LDS a workgroup of the tile kernel may ask for on this device
+
+// A tile kernel compiled at run time for one plan, one tile shape and one mode.
+struct FixedTileKernel {
+  int mode = 0;
+  std::vector<uint32_t> key;   // the values of FBX_TILE_FIXED_FIELDS it was compiled for
+  void* module = nullptr;      // hipModule_t
+  void* function = nullptr;    // hipFunction_t; null: the attempt failed
+  uint32_t per_cu = 1;         // workgroups of it that fit a compute unit
+};
+// The compiled kernels of one plan.
+class TileJit {
+ public:
+  static constexpr size_t kMaxKernels = 12;
+  TileJit() { kernels_.reserve(kMaxKernels); }
+  ~TileJit();
+  TileJit(const TileJit&) = delete;
+  TileJit& operator=(const TileJit&) = delete;
+  // The kernel for these parameters, compiled now if it is not there yet; null if there is none
+  // (note() then says why).  The device the kernel is to run on must be current.
+  const FixedTileKernel* get(const TileParams& P, int mode);
+  void release();
+  const std::string& note() const { return note_; }
+  double compile_ms() const { return compile_ms_; }  // spent compiling so far
+  uint32_t compiled() const { return compiled_; }
+ private:
+  std::vector<FixedTileKernel> kernels_;
+  std::string note_;
+  double compile_ms_ = 0;
+  uint32_t compiled_ = 0;
+};
+hipError_t launch_tile_fixed(const FixedTileKernel& k, const TileParams& P, hipStream_t st);
+uint32_t tile_cu_count();
 
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st);
 hipError_t launch_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t raw_len, uint32_t log2T, Ctrl* ctrl,
@@ -95,5 +135,6 @@ hipError_t launch_programs(const WalkParams& P, hipStream_t st);
 hipError_t launch_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets, uint32_t threads,
                               hipStream_t st);
 hipError_t launch_arena_reset(uint64_t* head, uint64_t value, hipStream_t st);
+#endif  // __HIPCC_RTC__
 
 }  // namespace fbx

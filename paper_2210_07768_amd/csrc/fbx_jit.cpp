@@ -1,0 +1,225 @@
+// Tile kernels compiled for one plan at run time (plan option compile=1).
+//
+// Section 4 of the paper builds, once per layer and before training starts, a meta-kernel that
+// runs the layer's operators one after the other, and compiles it at run time.  Here the
+// template is the tile kernel itself (fbx_tile.hip): the same source is compiled again with the
+// numbers that the plan and the tile size fix written in as literals, which is worth several per
+// cent of its time.  The compiler is the HIP run-time compilation library, loaded when first
+// needed; whatever goes wrong (no library, no sources beside this library, a compile error)
+// leaves the call on the generic kernel and says why in the call's note.
+#include <dlfcn.h>
+#include <dirent.h>
+
+#include <chrono>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <sstream>
+
+#include <hip/hip_runtime.h>
+#include <hip/hiprtc.h>
+
+#include "fbx_device.h"
+
+namespace fbx {
+
+namespace {
+
+struct Rtc {
+  void* lib = nullptr;
+  hiprtcResult (*create)(hiprtcProgram*, const char*, const char*, int, const char**, const char**) = nullptr;
+  hiprtcResult (*compile)(hiprtcProgram, int, const char**) = nullptr;
+  hiprtcResult (*log_size)(hiprtcProgram, size_t*) = nullptr;
+  hiprtcResult (*log)(hiprtcProgram, char*) = nullptr;
+  hiprtcResult (*code_size)(hiprtcProgram, size_t*) = nullptr;
+  hiprtcResult (*code)(hiprtcProgram, char*) = nullptr;
+  hiprtcResult (*destroy)(hiprtcProgram*) = nullptr;
+  std::string why;  // why it is not usable
+  bool ok = false;
+};
+
+const Rtc& rtc() {
+  static Rtc r;
+  static std::once_flag once;
+  std::call_once(once, [] {
+    for (const char* name : {"libhiprtc.so", "libhiprtc.so.7", "/opt/rocm/lib/libhiprtc.so"}) {
+      r.lib = dlopen(name, RTLD_NOW | RTLD_LOCAL);
+      if (r.lib) break;
+    }
+    if (!r.lib) { r.why = "the run-time compilation library could not be loaded"; return; }
+    auto sym = [&](const char* n) { return dlsym(r.lib, n); };
+    r.create = reinterpret_cast<decltype(r.create)>(sym("hiprtcCreateProgram"));
+    r.compile = reinterpret_cast<decltype(r.compile)>(sym("hiprtcCompileProgram"));
+    r.log_size = reinterpret_cast<decltype(r.log_size)>(sym("hiprtcGetProgramLogSize"));
+    r.log = reinterpret_cast<decltype(r.log)>(sym("hiprtcGetProgramLog"));
+    r.code_size = reinterpret_cast<decltype(r.code_size)>(sym("hiprtcGetCodeSize"));
+    r.code = reinterpret_cast<decltype(r.code)>(sym("hiprtcGetCode"));
+    r.destroy = reinterpret_cast<decltype(r.destroy)>(sym("hiprtcDestroyProgram"));
+    r.ok = r.create && r.compile && r.log_size && r.log && r.code_size && r.code && r.destroy;
+    if (!r.ok) r.why = "the run-time compilation library lacks an entry point";
+  });
+  return r;
+}
+
+bool readable(const std::string& path) {
+  FILE* f = fopen(path.c_str(), "rb");
+  if (f) fclose(f);
+  return f != nullptr;
+}
+
+// The kernel sources lie beside this library (csrc/, ../include/); the compiler's own headers
+// under the ROCm tree.
+struct Paths {
+  std::string csrc, include, rocm_include, clang_include, why;
+  bool ok = false;
+};
+
+const Paths& paths() {
+  static Paths p;
+  static std::once_flag once;
+  std::call_once(once, [] {
+    Dl_info info;
+    if (!dladdr(reinterpret_cast<const void*>(&paths), &info) || !info.dli_fname) { p.why = "this library's own path is unknown"; return; }
+    std::string dir(info.dli_fname);
+    const size_t slash = dir.rfind('/');
+    dir = slash == std::string::npos ? std::string(".") : dir.substr(0, slash);
+    p.csrc = dir + "/csrc";
+    p.include = dir + "/../include";
+    if (!readable(p.csrc + "/fbx_tile.hip") || !readable(p.include + "/fbx.h")) { p.why = "the kernel sources are not beside the library"; return; }
+    const char* env = getenv("ROCM_PATH");
+    const std::string rocm = env && *env ? env : "/opt/rocm";
+    p.rocm_include = rocm + "/include";
+    const std::string clang = rocm + "/lib/llvm/lib/clang";
+    if (DIR* d = opendir(clang.c_str())) {
+      while (dirent* e = readdir(d)) {
+        if (e->d_name[0] == '.') continue;
+        const std::string cand = clang + "/" + e->d_name + "/include";
+        if (readable(cand + "/stddef.h")) p.clang_include = cand;
+      }
+      closedir(d);
+    }
+    if (p.clang_include.empty()) { p.why = "the compiler's headers were not found under " + rocm; return; }
+    p.ok = true;
+  });
+  return p;
+}
+
+#define FBX_FIELD_VALUE(name) v.push_back(P.name);
+std::vector<uint32_t> fixed_values(const TileParams& P) {
+  std::vector<uint32_t> v;
+  FBX_TILE_FIXED_FIELDS(FBX_FIELD_VALUE)
+  return v;
+}
+#undef FBX_FIELD_VALUE
+
+#define FBX_FIELD_ASSIGN(name) os << " P." #name " = " << P.name << "u;";
+std::string program_text(const TileParams& P, int mode) {
+  std::ostringstream os;
+  os << "#define FBX_FIXED_MODE " << mode << "\n#define FBX_FIXED_NAME fbx_tile_fixed_" << mode << "\n#define FBX_FIXED_ASSIGN";
+  FBX_TILE_FIXED_FIELDS(FBX_FIELD_ASSIGN)
+  os << "\n#include \"fbx_tile.hip\"\n";
+  return os.str();
+}
+#undef FBX_FIELD_ASSIGN
+
+}  // namespace
+
+TileJit::~TileJit() { release(); }
+
+void TileJit::release() {
+  for (FixedTileKernel& k : kernels_)
+    if (k.module) (void)hipModuleUnload(reinterpret_cast<hipModule_t>(k.module));
+  kernels_.clear();
+}
+
+const FixedTileKernel* TileJit::get(const TileParams& P, int mode) {
+  const std::vector<uint32_t> key = fixed_values(P);
+  for (const FixedTileKernel& k : kernels_)
+    if (k.mode == mode && k.key == key) return k.function ? &k : nullptr;
+  if (kernels_.size() >= kMaxKernels) {  // batches of ever new shapes: stop compiling for them
+    note_ = "compile=1: more tile shapes than compiled kernels are kept for; the generic kernel runs";
+    return nullptr;
+  }
+  FixedTileKernel k;
+  k.mode = mode;
+  k.key = key;
+  auto fail = [&](const std::string& why) -> const FixedTileKernel* {
+    note_ = "compile=1: " + why + "; the generic kernel runs";
+    kernels_.push_back(k);  // (remembered, so that the attempt is not made again)
+    return nullptr;
+  };
+  const Rtc& r = rtc();
+  if (!r.ok) return fail(r.why);
+  const Paths& p = paths();
+  if (!p.ok) return fail(p.why);
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail("the device's architecture is unknown");
+  std::string arch(prop.gcnArchName);
+  arch = arch.substr(0, arch.find(':'));
+
+  const auto t0 = std::chrono::steady_clock::now();
+  const std::string text = program_text(P, mode);
+  hiprtcProgram prog = nullptr;
+  if (r.create(&prog, text.c_str(), "fbx_tile_fixed.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS) return fail("the program could not be created");
+  const std::string o_arch = "--offload-arch=" + arch, i0 = "-I" + p.csrc, i1 = "-I" + p.include, i2 = "-I" + p.rocm_include,
+                    i3 = "-I" + p.clang_include;
+  // the same code generation options as the library's own build
+  const char* opts[] = {o_arch.c_str(), "-O3", "-std=c++17", i0.c_str(), i1.c_str(), i2.c_str(), i3.c_str(),
+                        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"};
+  const hiprtcResult rc = r.compile(prog, static_cast<int>(sizeof(opts) / sizeof(opts[0])), opts);
+  if (rc != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    std::string log;
+    if (r.log_size(prog, &n) == HIPRTC_SUCCESS && n > 1) {
+      log.resize(n);
+      (void)r.log(prog, &log[0]);
+      if (log.size() > 400) log.resize(400);
+    }
+    (void)r.destroy(&prog);
+    return fail("the kernel did not compile (" + log + ")");
+  }
+  size_t n = 0;
+  std::vector<char> code;
+  if (r.code_size(prog, &n) != HIPRTC_SUCCESS || n == 0) { (void)r.destroy(&prog); return fail("the compiler returned no code"); }
+  code.resize(n);
+  const hiprtcResult got = r.code(prog, code.data());
+  (void)r.destroy(&prog);
+  if (got != HIPRTC_SUCCESS) return fail("the compiler returned no code");
+  hipModule_t module = nullptr;
+  hipFunction_t fn = nullptr;
+  if (hipModuleLoadData(&module, code.data()) != hipSuccess) { (void)hipGetLastError(); return fail("the compiled code did not load"); }
+  const std::string name = "fbx_tile_fixed_" + std::to_string(mode);
+  if (hipModuleGetFunction(&fn, module, name.c_str()) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipModuleUnload(module);
+    return fail("the compiled code has no kernel");
+  }
+  int per_cu = 0;
+  if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kTileThreads, P.lds_bytes) != hipSuccess || per_cu < 1) {
+    (void)hipGetLastError();
+    per_cu = 1;
+  }
+  k.module = module;
+  k.function = fn;
+  k.per_cu = static_cast<uint32_t>(per_cu);
+  compile_ms_ += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  ++compiled_;
+  kernels_.push_back(k);
+  return &kernels_.back();
+}
+
+hipError_t launch_tile_fixed(const FixedTileKernel& k, const TileParams& P, hipStream_t st) {
+  if (P.n_tiles == 0) return hipSuccess;
+  if (fixed_values(P) != k.key) return hipErrorInvalidValue;  // (a kernel compiled for other numbers)
+  uint32_t capacity = tile_cu_count() * k.per_cu;  // as many workgroups as run at the same time
+  if (P.grid && P.grid < capacity) capacity = P.grid;
+  TileParams Q = P;
+  void* args[] = {&Q};
+  const uint32_t grid = std::min(P.n_tiles, capacity);
+  return hipModuleLaunchKernel(reinterpret_cast<hipFunction_t>(k.function), grid, 1, 1, kTileThreads, 1, 1, P.lds_bytes, st, args,
+                               nullptr);
+}
+
+}  // namespace fbx

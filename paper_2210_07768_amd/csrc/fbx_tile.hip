@@ -1419,7 +1419,7 @@ __device__ __forceinline__ u32x4 load_chunk(uintptr_t ca, uintptr_t ok_lo, uintp
 // Workgroups are persistent: each copies the plan tables into LDS once and then
 // takes tiles off a shared counter until none is left.
 template <int MODE>
-__global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
+__device__ __forceinline__ void tile_body(const TileParams& P) {
   constexpr bool WRITE = MODE != 0;
   __shared__ uint32_t s_err, s_len, s_cur, s_nxt;
   __shared__ uint32_t s_bad[2];  // what is wrong with the offsets of the current and of the next tile (CE_ bits)
@@ -1652,8 +1652,32 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
   }
 }
 
+#ifndef FBX_FIXED_MODE
+// The kernel for any plan: everything it needs to know arrives in P.
+template <int MODE>
+__global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
+  tile_body<MODE>(P);
+}
+#endif
+
 }  // namespace
 
+#ifdef FBX_FIXED_MODE
+// The kernel for one plan and one shape of tile, compiled when the plan first meets that shape
+// (the meta-kernel of Section 4, with this file as its template): FBX_FIXED_ASSIGN sets the
+// fields of P that the plan and the tile size fix (counts, LDS offsets, tile size) to literal
+// values, so that loops over layers and lists unroll or vanish, the LDS sections have constant
+// addresses and far fewer values compete for scalar registers.  The launch checks that the
+// fields it passes are the ones compiled in.
+// (its name, FBX_FIXED_NAME, ends in the mode, so that a trace tells the three kernels apart)
+extern "C" __global__ __launch_bounds__(kTileThreads, 4) void FBX_FIXED_NAME(TileParams Pin) {
+  TileParams P = Pin;
+  FBX_FIXED_ASSIGN
+  tile_body<FBX_FIXED_MODE>(P);
+}
+#endif
+
+#ifndef __HIPCC_RTC__
 // ----------------------------------------------------------- launch wrappers
 uint32_t tile_max_lds() {
   static uint32_t cached = 0;
@@ -1704,5 +1728,6 @@ uint32_t tile_cu_count() {
   }
   return cached;
 }
+#endif  // __HIPCC_RTC__
 
 }  // namespace fbx

@@ -390,6 +390,59 @@ def test_one_launch_mode_matches_and_falls_back():
     plan.close()
 
 
+@pytest.mark.parametrize("case", ["config5", "config4", "config2", "config3", "framing", "filters_T8_cap64"])
+def test_kernels_compiled_for_the_plan_match(case):
+    """Plan option compile=1: the tile kernel is compiled again at run time with the plan's numbers
+    written in (the meta-kernel of Section 4).  Counting, writing and one-launch kernels, a second
+    batch of another size on the same kernels, several passes per tile and records read in place."""
+    from gpu_harness import expand
+    opts = {"compile": 1}
+    if case.startswith("config"):
+        cfg = int(case[-1])
+        w = W.get(cfg, {5: 3000, 4: 900, 2: 400, 3: 2000}[cfg])
+        spec = w.spec
+        raw, off = w.generate()
+        raw2, off2 = w.generate(rec_begin=10000, n_records=w.n_records // 3)
+    elif case == "framing":
+        spec = FRAMING_SPEC
+        raw, off = _cat(FRAMING_RECORDS * 29)
+        raw2, off2 = _cat(FRAMING_RECORDS * 3)
+    else:
+        spec = _filter_spec()
+        opts.update({"tile_log2": 3, "raw_cap": 64})
+        rng = random.Random(99)
+        tok = lambda: "abababab"[:rng.randint(0, 8)] + rng.choice(["", "x"])
+        recs = [f"{tok()}\t{','.join(tok() for _ in range(rng.randint(1, 12)))}\tk{i % 3}\n".encode() for i in range(200)]
+        raw, off = _cat(recs)
+        raw2, off2 = _cat(recs[:37])
+    raw, raw2 = (np.frombuffer(x, np.uint8) if isinstance(x, bytes) else x for x in (raw, raw2))
+    plan = B.Plan(spec)
+    for k, v in opts.items():
+        plan.set_option(k, v)
+    d_raw, d_off = to_device(raw, off)
+    res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.2)
+    assert "generic kernel" not in res.note, res.note
+    n_compiled = plan.compiled()[0]
+    assert n_compiled >= 1                                   # (not the generic kernel under another name)
+    n = len(off) - 1
+    want = O.extract(spec, raw, off)
+    assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, case)
+    for _ in range(2):   # the calls after the first know the ragged sizes: one launch where the plan allows it
+        ws.fill_(0xAB)
+        plan.set_workspace(ws)
+        res = plan.extract(d_raw, d_off)
+        assert "generic kernel" not in res.note, res.note
+        assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, case)
+    d_raw2, d_off2 = to_device(raw2, off2)
+    ws.fill_(0xCD)
+    plan.set_workspace(ws)
+    res2 = plan.extract(d_raw2, d_off2)
+    assert "generic kernel" not in res2.note, res2.note
+    assert_same({s: expand(res2.slots[s], len(off2) - 1) for s in res2.slot_ids}, res2, O.extract(spec, raw2, off2), case)
+    assert n_compiled <= plan.compiled()[0] <= 6             # a kernel per mode and tile shape (the batch size may change the shape)
+    plan.close()
+
+
 def test_results_do_not_depend_on_op_order_or_launch_mode():
     w = W.get(4, 300)
     raw, off = w.generate()
