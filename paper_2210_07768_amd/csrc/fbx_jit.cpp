@@ -133,7 +133,10 @@ void TileJit::release() {
 }
 
 const FixedTileKernel* TileJit::get(const TileParams& P, int mode) {
-  const std::vector<uint32_t> key = fixed_values(P);
+  std::vector<uint32_t> key = fixed_values(P);
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = 0; }
+  key.push_back(static_cast<uint32_t>(dev));  // (a loaded kernel belongs to one device)
   for (const FixedTileKernel& k : kernels_)
     if (k.mode == mode && k.key == key) return k.function ? &k : nullptr;
   if (kernels_.size() >= kMaxKernels) {  // batches of ever new shapes: stop compiling for them
@@ -152,9 +155,8 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode) {
   if (!r.ok) return fail(r.why);
   const Paths& p = paths();
   if (!p.ok) return fail(p.why);
-  int dev = 0;
   hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail("the device's architecture is unknown");
+  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail("the device's architecture is unknown");
   std::string arch(prop.gcnArchName);
   arch = arch.substr(0, arch.find(':'));
 
@@ -212,7 +214,9 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode) {
 
 hipError_t launch_tile_fixed(const FixedTileKernel& k, const TileParams& P, hipStream_t st) {
   if (P.n_tiles == 0) return hipSuccess;
-  if (fixed_values(P) != k.key) return hipErrorInvalidValue;  // (a kernel compiled for other numbers)
+  std::vector<uint32_t> now = fixed_values(P);
+  now.push_back(k.key.back());
+  if (now != k.key) return hipErrorInvalidValue;  // (a kernel compiled for other numbers)
   uint32_t capacity = tile_cu_count() * k.per_cu;  // as many workgroups as run at the same time
   if (P.grid && P.grid < capacity) capacity = P.grid;
   TileParams Q = P;
