@@ -151,7 +151,14 @@ bool tile_geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records, Tile
   const uint32_t dev_max = tile_max_lds();
   const int lt_hi = p.tile_log2 >= 0 ? p.tile_log2 : 6, lt_lo = p.tile_log2 >= 0 ? p.tile_log2 : 0;
   for (int lt = lt_hi; lt >= lt_lo; --lt) {
-    const uint64_t want = (uint64_t(1) << lt) * avg * 5 / 4 + 64;
+    uint64_t want = (uint64_t(1) << lt) * avg * 5 / 4 + 64;
+    if (p.compile) {
+      // kernels compiled for the plan are compiled for one section size: batches of about the
+      // same record length must agree on it, so sizes go up in steps of an eighth of a power of two
+      uint64_t step = 128;
+      while (step * 16 <= want) step <<= 1;
+      want = (want + step - 1) / step * step;
+    }
     const uint32_t cap = p.raw_cap ? p.raw_cap : round16(std::min<uint64_t>(std::max<uint64_t>(want, 1024), 65000));
     tile_lds_layout(h, static_cast<uint32_t>(lt), cap, tp);
     const uint32_t limit = (lt == lt_lo) ? dev_max : std::min(p.lds_budget, dev_max);
