@@ -424,7 +424,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   auto tile_launch = [&](const TileParams& Q, int mode) -> hipError_t {
 #ifndef FBX_TILE_PROF
     if (plan->compile && !Q.dbg)
-      if (const FixedTileKernel* k = plan->jit.get(Q, mode)) return launch_tile_fixed(*k, Q, st);
+      if (const FixedTileKernel* k = plan->jit.get(Q, mode, plan->host)) return launch_tile_fixed(*k, Q, st);
 #endif
     return launch_tile(Q, mode, st);
   };

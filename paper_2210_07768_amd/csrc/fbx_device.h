@@ -108,8 +108,9 @@ class TileJit {
   TileJit(const TileJit&) = delete;
   TileJit& operator=(const TileJit&) = delete;
   // The kernel for these parameters, compiled now if it is not there yet; null if there is none
-  // (note() then says why).  The device the kernel is to run on must be current.
-  const FixedTileKernel* get(const TileParams& P, int mode);
+  // (note() then says why).  The device the kernel is to run on must be current; h is the plan
+  // the object belongs to (always the same one: its list bounds are compiled in too).
+  const FixedTileKernel* get(const TileParams& P, int mode, const PlanHost& h);
   void release();
   const std::string& note() const { return note_; }
   double compile_ms() const { return compile_ms_; }  // spent compiling so far

@@ -113,10 +113,23 @@ std::vector<uint32_t> fixed_values(const TileParams& P) {
 #undef FBX_FIELD_VALUE
 
 #define FBX_FIELD_ASSIGN(name) os << " P." #name " = " << P.name << "u;";
-std::string program_text(const TileParams& P, int mode) {
+void braces(std::ostringstream& os, const uint32_t* v, size_t n) {
+  os << "{";
+  for (size_t i = 0; i < n; ++i) os << (i ? ", " : "") << v[i] << "u";
+  os << "}";
+}
+
+std::string program_text(const TileParams& P, int mode, const PlanHost& h) {
   std::ostringstream os;
   os << "#define FBX_FIXED_MODE " << mode << "\n#define FBX_FIXED_NAME fbx_tile_fixed_" << mode << "\n#define FBX_FIXED_ASSIGN";
   FBX_TILE_FIXED_FIELDS(FBX_FIELD_ASSIGN)
+  os << "\n#define FBX_FIXED_LIST_BEGIN ";
+  braces(os, h.tile_list_begin.data(), h.tile_list_begin.size());
+  // (the table of derived counts starts with the first entry of every layer, padded to four words)
+  const uint32_t none = 0;
+  const size_t head = h.derive_tab.empty() ? 0 : 4u * ((h.n_layers + 3u) / 4u);
+  os << "\n#define FBX_FIXED_RNR_HEAD ";
+  braces(os, head ? h.derive_tab.data() : &none, head ? head : 1);
   os << "\n#include \"fbx_tile.hip\"\n";
   return os.str();
 }
@@ -132,7 +145,7 @@ void TileJit::release() {
   kernels_.clear();
 }
 
-const FixedTileKernel* TileJit::get(const TileParams& P, int mode) {
+const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHost& h) {
   std::vector<uint32_t> key = fixed_values(P);
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = 0; }
@@ -161,7 +174,7 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode) {
   arch = arch.substr(0, arch.find(':'));
 
   const auto t0 = std::chrono::steady_clock::now();
-  const std::string text = program_text(P, mode);
+  const std::string text = program_text(P, mode, h);
   hiprtcProgram prog = nullptr;
   if (r.create(&prog, text.c_str(), "fbx_tile_fixed.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS) return fail("the program could not be created");
   const std::string o_arch = "--offload-arch=" + arch, i0 = "-I" + p.csrc, i1 = "-I" + p.include, i2 = "-I" + p.rocm_include,

@@ -105,6 +105,19 @@ __device__ __forceinline__ uint32_t thread_id() {
 __device__ __forceinline__ uint32_t lane_id() { return thread_id() & 63u; }
 
 // Views of the LDS sections of one workgroup.
+#ifdef FBX_FIXED_MODE
+// The bounds of the plan's work lists and the first entry of every layer in the table of derived
+// counts: small tables of the plan, literals in a kernel compiled for it.
+__device__ __forceinline__ uint32_t fixed_list_begin(uint32_t i) {
+  constexpr uint32_t t[] = FBX_FIXED_LIST_BEGIN;
+  return t[i];
+}
+__device__ __forceinline__ uint32_t fixed_rnr_head(uint32_t i) {
+  constexpr uint32_t t[] = FBX_FIXED_RNR_HEAD;
+  return t[i];
+}
+#endif
+
 struct Sh {
   uint64_t* off;    // [2][T + 1] record offsets of this tile and of the next one
   uint32_t* rs;     // [T] LDS position of the first byte of a staged record
@@ -125,6 +138,14 @@ struct Sh {
   const uint32_t* list_begin;
   const uint32_t* rnr;         // how the counts of the ragged operators of layers >= 2 follow from their inputs'
   const uint8_t* aux;          // bucket boundaries and filter prefixes
+  // bounds of work list i; first entry of layer i + 2 in rnr (i < n_layers)
+#ifdef FBX_FIXED_MODE
+  __device__ __forceinline__ uint32_t lbeg(uint32_t i) const { return fixed_list_begin(i); }
+  __device__ __forceinline__ uint32_t rnr_head(uint32_t i) const { return fixed_rnr_head(i); }
+#else
+  __device__ __forceinline__ uint32_t lbeg(uint32_t i) const { return list_begin[i]; }
+  __device__ __forceinline__ uint32_t rnr_head(uint32_t i) const { return rnr[i]; }
+#endif
 };
 
 __device__ __forceinline__ Sh views(const TileParams& P) {
@@ -710,11 +731,11 @@ struct Pass {
     g = g_first + r;
   }
   __device__ __forceinline__ uint32_t units_of(uint32_t list) const {
-    return (sh.list_begin[list + 1] - sh.list_begin[list] + G - 1u) / G;
+    return (sh.lbeg(list + 1) - sh.lbeg(list) + G - 1u) / G;
   }
   // the operator of this lane in unit u of a list, or null
   __device__ __forceinline__ const OpProg* op_of(uint32_t list, uint32_t u) const {
-    const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
+    const uint32_t lb = sh.lbeg(list), m = sh.lbeg(list + 1) - lb;
     const uint32_t i = u * G + og;
     return i < m ? &sh.prog[lb + i] : nullptr;
   }
@@ -736,11 +757,11 @@ struct Pass {
       const bool act = pr < np && rr < nb;
       uint32_t s = 0, e = 0, row = 0;
       if (act) {
-        const OpProg& d = sh.prog[sh.list_begin[TL_RAGROOT] + i];
+        const OpProg& d = sh.prog[sh.lbeg(TL_RAGROOT) + i];
         src.span(rr, d.field, s, e);
         row = d.rag_row;
       } else if (pr < np) {
-        row = sh.prog[sh.list_begin[TL_RAGROOT] + i].rag_row;
+        row = sh.prog[sh.lbeg(TL_RAGROOT) + i].rag_row;
       }
       uint16_t* tab = sh.ctab + pr * P.item_cap;
       const uint32_t cap = P.item_cap;
@@ -765,7 +786,7 @@ struct Pass {
       const uint32_t pr = p0 + (tid >> lg);
       const uint32_t i = pr / T, rr = pr & (T - 1u);
       const bool in = pr < np, act = in && rr < nb;
-      const OpProg& d = sh.prog[sh.list_begin[TL_RAGROOT] + P.n_mh + (in ? i : 0u)];
+      const OpProg& d = sh.prog[sh.lbeg(TL_RAGROOT) + P.n_mh + (in ? i : 0u)];
       const bool filter = d.kind == OP_FILTER;
       uint32_t s = 0, e = 0;
       if (act) src.span(rr, d.field, s, e);
@@ -788,7 +809,7 @@ struct Pass {
   // operators per unit; records read in place count all their ragged root operators here.
   __device__ __forceinline__ uint32_t count_skip() const { return !Src::kTable ? 0u : (split_all ? P.n_split : P.n_mh); }
   __device__ __forceinline__ uint32_t count_root_units() const {
-    return (sh.list_begin[TL_RAGROOT + 1] - sh.list_begin[TL_RAGROOT] - count_skip() + G - 1u) / G;
+    return (sh.lbeg(TL_RAGROOT + 1) - sh.lbeg(TL_RAGROOT) - count_skip() + G - 1u) / G;
   }
   __device__ __forceinline__ uint32_t count_units() const { return count_root_units() + units_of(TL_NGRAM); }
   __device__ __forceinline__ void count_unit(uint32_t u) {
@@ -797,7 +818,7 @@ struct Pass {
     const OpProg* d;
     uint32_t i = 0;  // position in the ragged root list
     if (u < ur) {
-      const uint32_t lb = sh.list_begin[TL_RAGROOT], m = sh.list_begin[TL_RAGROOT + 1] - lb;
+      const uint32_t lb = sh.lbeg(TL_RAGROOT), m = sh.lbeg(TL_RAGROOT + 1) - lb;
       i = count_skip() + u * G + og;
       d = i < m ? &sh.prog[lb + i] : nullptr;
     } else {
@@ -835,12 +856,12 @@ struct Pass {
   // Counts of the later layers follow from the inputs' counts, record by record and layer
   // by layer (the operators of one layer do not depend on each other): G operators per unit.
   __device__ __forceinline__ uint32_t derive_units(uint32_t layer) const {
-    return (sh.rnr[layer - 1u] - sh.rnr[layer - 2u] + G - 1u) / G;
+    return (sh.rnr_head(layer - 1u) - sh.rnr_head(layer - 2u) + G - 1u) / G;
   }
   __device__ __forceinline__ void derive_unit(uint32_t layer, uint32_t u) {
     refresh();
-    const uint32_t i = sh.rnr[layer - 2u] + u * G + og;
-    if (i >= sh.rnr[layer - 1u]) return;
+    const uint32_t i = sh.rnr_head(layer - 2u) + u * G + og;
+    if (i >= sh.rnr_head(layer - 1u)) return;
     const uint32_t header = 4u * ((P.n_layers + 3u) >> 2);
     const u32x4 d = *reinterpret_cast<const u32x4*>(sh.rnr + header + 4u * i);  // result row, a, b, cross or concat
     const uint64_t ca = (d.y >> 31) ? (d.y & 0x7fffffffu) : sh.cnt[d.y * T + r];
@@ -853,7 +874,7 @@ struct Pass {
   // The ragged operators of the last layer (if it is not the first) hold the last rows, in the
   // order of their table entries: their counts are derived here, right before they are summed.
   __device__ __forceinline__ uint32_t last_layer_rows() const {
-    return P.n_rnr ? sh.rnr[P.n_layers - 1u] - sh.rnr[P.n_layers - 2u] : 0u;
+    return P.n_rnr ? sh.rnr_head(P.n_layers - 1u) - sh.rnr_head(P.n_layers - 2u) : 0u;
   }
   __device__ __forceinline__ uint32_t scan_units() const {
     const uint32_t nl = last_layer_rows();
@@ -874,7 +895,7 @@ struct Pass {
       ok = i < nl;
       if (ok) {
         const uint32_t header = 4u * ((P.n_layers + 3u) >> 2);
-        const u32x4 d = *reinterpret_cast<const u32x4*>(sh.rnr + header + 4u * (sh.rnr[P.n_layers - 2u] + i));
+        const u32x4 d = *reinterpret_cast<const u32x4*>(sh.rnr + header + 4u * (sh.rnr_head(P.n_layers - 2u) + i));
         const uint64_t ca = (d.y >> 31) ? (d.y & 0x7fffffffu) : sh.cnt[d.y * T + r];
         const uint64_t cb = (d.z >> 31) ? (d.z & 0x7fffffffu) : sh.cnt[d.z * T + r];
         const uint64_t c = d.w == 0u ? ca * cb : ca + cb;
@@ -899,12 +920,12 @@ struct Pass {
   // ---- layer 1
   // (a unit is 2 G operators, each lane taking two of them one after the other: half the hand-outs and set-ups)
   __device__ __forceinline__ uint32_t hash1_units() const {
-    return (sh.list_begin[TL_HASH1 + 1] - sh.list_begin[TL_HASH1] + 2u * G - 1u) / (2u * G);
+    return (sh.lbeg(TL_HASH1 + 1) - sh.lbeg(TL_HASH1) + 2u * G - 1u) / (2u * G);
   }
   __device__ __forceinline__ void hash1_unit(uint32_t u) {
     refresh();
     if (!live) return;
-    const uint32_t lb = sh.list_begin[TL_HASH1], m = sh.list_begin[TL_HASH1 + 1] - lb;
+    const uint32_t lb = sh.lbeg(TL_HASH1), m = sh.lbeg(TL_HASH1 + 1) - lb;
     for (uint32_t i = 2u * u * G + og; i < min(m, 2u * (u + 1u) * G); i += G) {
       const OpProg& d = sh.prog[lb + i];
       uint32_t s, e;
@@ -938,11 +959,11 @@ struct Pass {
   }
   // the other ragged root operators (filters, multi-valued buckets): a lane writes its record's list
   __device__ __forceinline__ uint32_t other_units() const {
-    return (sh.list_begin[TL_RAGROOT + 1] - sh.list_begin[TL_RAGROOT] - P.n_mh + G - 1u) / G;
+    return (sh.lbeg(TL_RAGROOT + 1) - sh.lbeg(TL_RAGROOT) - P.n_mh + G - 1u) / G;
   }
   __device__ __forceinline__ void other_unit(uint32_t u) {
     refresh();
-    const uint32_t lb = sh.list_begin[TL_RAGROOT] + P.n_mh, m = sh.list_begin[TL_RAGROOT + 1] - lb;
+    const uint32_t lb = sh.lbeg(TL_RAGROOT) + P.n_mh, m = sh.lbeg(TL_RAGROOT + 1) - lb;
     const uint32_t i = u * G + og;
     const OpProg* d = i < m ? &sh.prog[lb + i] : nullptr;
     if (!d || !live) return;
@@ -962,7 +983,7 @@ struct Pass {
     for (uint32_t i0 = 0; i0 < P.n_mh; i0 += 64u) {
       const uint32_t i = i0 + lane;
       uint32_t v = 0;
-      if (i < P.n_mh) v = sh.tot[sh.prog[sh.list_begin[TL_RAGROOT] + i].rag_row];
+      if (i < P.n_mh) v = sh.tot[sh.prog[sh.lbeg(TL_RAGROOT) + i].rag_row];
       uint32_t incl = v;
       for (uint32_t d = 1; d < 64u; d <<= 1) {
         const uint32_t t = __shfl_up(incl, d, 64);
@@ -985,7 +1006,7 @@ struct Pass {
       if (sh.ioff[mid] <= q) lo = mid; else hi = mid - 1u;
     }
     const uint32_t i = lo;
-    const OpProg& d = sh.prog[sh.list_begin[TL_RAGROOT] + i];
+    const OpProg& d = sh.prog[sh.lbeg(TL_RAGROOT) + i];
     const uint32_t row = d.rag_row;
     const uint32_t before = sh.run[row] - sh.tot[row];     // signs of the tile's earlier passes
     const uint32_t pos = before + (q - sh.ioff[i]);         // the item's position inside the tile
@@ -1041,11 +1062,11 @@ struct Pass {
 
   // n-grams: the lanes of a wavefront run over the grams of one record; unit = (operator, record)
   __device__ __forceinline__ uint32_t ngram_units() const {
-    return (sh.list_begin[TL_NGRAM + 1] - sh.list_begin[TL_NGRAM]) * nb;
+    return (sh.lbeg(TL_NGRAM + 1) - sh.lbeg(TL_NGRAM)) * nb;
   }
   __device__ __forceinline__ void ngram_unit(uint32_t u) {
     const uint32_t lane = lane_id();
-    const OpProg& d = sh.prog[sh.list_begin[TL_NGRAM] + u / nb];
+    const OpProg& d = sh.prog[sh.lbeg(TL_NGRAM) + u / nb];
     const uint32_t rr = u % nb;
     uint32_t s, e;
     src.span(rr, d.field, s, e);
@@ -1124,7 +1145,7 @@ struct Pass {
   __device__ __forceinline__ void gen_layer(uint32_t layer, uint32_t* ctr, Skip&& skip) {
     const uint32_t lane = lane_id();
     const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
-    const uint32_t lb = sh.list_begin[list], m = sh.list_begin[list + 1] - lb;
+    const uint32_t lb = sh.lbeg(list), m = sh.lbeg(list + 1) - lb;
     uint32_t u = grab_unit(ctr), units_before = 0;
     for (uint32_t i0 = 0; i0 < m; i0 += 64u) {  // 64 operators at a time: lane l knows the units of operator i0 + l
       uint32_t chunks = 0;
@@ -1380,7 +1401,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // ---- the list crosses / concats, layer by layer
   for (uint32_t layer = 2, turn = 0; layer <= P.n_layers; ++layer) {
     const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
-    if (sh.list_begin[list + 1] == sh.list_begin[list]) continue;  // (no such operator in this layer: no barrier either)
+    if (sh.lbeg(list + 1) == sh.lbeg(list)) continue;  // (no such operator in this layer: no barrier either)
     __syncthreads();  // the layer barrier
     uint32_t* ctr = &s_ctr[7u + (turn & 1u)];
     if (tid == 0) s_ctr[7u + ((turn + 1u) & 1u)] = 0;  // the counter of the next layer that has any (idle since the barrier before this one)
