@@ -143,7 +143,12 @@ struct Sh {
   __device__ __forceinline__ uint32_t lbeg(uint32_t i) const { return fixed_list_begin(i); }
   __device__ __forceinline__ uint32_t rnr_head(uint32_t i) const { return fixed_rnr_head(i); }
 #else
-  __device__ __forceinline__ uint32_t lbeg(uint32_t i) const { return list_begin[i]; }
+  // (the bounds of the lists that every plan has are fetched once per kernel and stay in scalar
+  // registers: a unit of work then starts without a look-up it would have to wait for)
+  uint32_t lb[TL_LAYER + 1];
+  __device__ __forceinline__ uint32_t lbeg(uint32_t i) const {
+    return (__builtin_constant_p(i) && i <= (uint32_t)TL_LAYER) ? lb[i] : list_begin[i];
+  }
   __device__ __forceinline__ uint32_t rnr_head(uint32_t i) const { return rnr[i]; }
 #endif
 };
@@ -1444,7 +1449,11 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
   constexpr bool WRITE = MODE != 0;
   __shared__ uint32_t s_err, s_len, s_cur, s_nxt;
   __shared__ uint32_t s_bad[2];  // what is wrong with the offsets of the current and of the next tile (CE_ bits)
-  const Sh sh = views(P);
+  Sh sh_ = views(P);
+#ifndef FBX_FIXED_MODE
+  for (uint32_t i = 0; i <= (uint32_t)TL_LAYER; ++i) sh_.lb[i] = P.list_begin[i];  // (n_lists >= TL_LAYER: always there)
+#endif
+  const Sh& sh = sh_;
   const uint32_t tid = threadIdx.x;
   const uint32_t T = 1u << P.log2T;
   const FBX_GLOBAL uint64_t* rec_off = gptr(P.rec_off);
