@@ -171,7 +171,9 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
  *                  compiles the kernels it launches with the plan's counts and table offsets as
  *                  literals (a few seconds each, on the host, inside that call), later calls
  *                  reuse them.  When the compiler or the kernel sources (csrc/ beside the
- *                  library) are missing the generic kernel runs and fbx_last_error says why.
+ *                  library and include/ one level up, or <dir>/csrc and <dir>/include with the
+ *                  environment variable FBX_KERNEL_SOURCES=<dir>) are missing the generic kernel
+ *                  runs and fbx_last_error says why.
  *                  0: one generic kernel for every plan (default)
  * Errors: FBX_E_ARG for an unknown key or an out-of-range value.
  */

@@ -422,10 +422,8 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   // The tile kernel in one of its modes: the one compiled for this plan if the plan asks for
   // that and it can be had, else the generic one.
   auto tile_launch = [&](const TileParams& Q, int mode) -> hipError_t {
-#ifndef FBX_TILE_PROF
-    if (plan->compile && !Q.dbg)
+    if (plan->compile)
       if (const FixedTileKernel* k = plan->jit.get(Q, mode, plan->host)) return launch_tile_fixed(*k, Q, st);
-#endif
     return launch_tile(Q, mode, st);
   };
   // One attempt: everything is enqueued on the stream, then one synchronisation.

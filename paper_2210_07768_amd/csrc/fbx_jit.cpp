@@ -67,8 +67,9 @@ bool readable(const std::string& path) {
   return f != nullptr;
 }
 
-// The kernel sources lie beside this library (csrc/, ../include/); the compiler's own headers
-// under the ROCm tree.
+// The kernel sources lie beside this library (csrc/, ../include/) unless the environment
+// variable FBX_KERNEL_SOURCES names the directory that holds csrc/ and include/; the compiler's
+// own headers lie under the ROCm tree.
 struct Paths {
   std::string csrc, include, rocm_include, clang_include, why;
   bool ok = false;
@@ -85,6 +86,9 @@ const Paths& paths() {
     dir = slash == std::string::npos ? std::string(".") : dir.substr(0, slash);
     p.csrc = dir + "/csrc";
     p.include = dir + "/../include";
+    if (const char* moved = getenv("FBX_KERNEL_SOURCES")) {  // a library installed away from its sources: <dir>/csrc, <dir>/include
+      if (*moved) { p.csrc = std::string(moved) + "/csrc"; p.include = std::string(moved) + "/include"; }
+    }
     if (!readable(p.csrc + "/fbx_tile.hip") || !readable(p.include + "/fbx.h")) { p.why = "the kernel sources are not beside the library"; return; }
     const char* env = getenv("ROCM_PATH");
     const std::string rocm = env && *env ? env : "/opt/rocm";
@@ -182,7 +186,11 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHos
   // the same code generation options as the library's own build
   const char* opts[] = {o_arch.c_str(), "-O3", "-std=c++17", i0.c_str(), i1.c_str(), i2.c_str(), i3.c_str(),
                         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                        "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"};
+                        "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
+#ifdef FBX_TILE_PROF
+                        "-DFBX_TILE_PROF",  // (a tuning build of the library compiles tuning kernels)
+#endif
+  };
   const hiprtcResult rc = r.compile(prog, static_cast<int>(sizeof(opts) / sizeof(opts[0])), opts);
   if (rc != HIPRTC_SUCCESS) {
     size_t n = 0;

@@ -931,14 +931,23 @@ struct Pass {
     refresh();
     if (!live) return;
     const uint32_t lb = sh.lbeg(TL_HASH1), m = sh.lbeg(TL_HASH1 + 1) - lb;
-    for (uint32_t i = 2u * u * G + og; i < min(m, 2u * (u + 1u) * G); i += G) {
-      const OpProg& d = sh.prog[lb + i];
-      uint32_t s, e;
-      src.span(r, d.field, s, e);
-      const uint64_t v = hash_span(src, s, e, d.key);
-      store_single(d.values, g, v);
-      if (d.stage != kNoRow) sh.stage[d.stage * T + r] = v;
-    }
+    // both operators' programs and fields are looked up before either is hashed: the look-ups
+    // (program, then field table) are waited for once, not once per operator
+    const uint32_t i0 = 2u * u * G + og, i1 = i0 + G;
+    const bool two = i1 < m;
+    if (i0 >= m) return;
+    const OpProg& d0 = sh.prog[lb + i0];
+    const OpProg& d1 = sh.prog[lb + (two ? i1 : i0)];
+    uint32_t s0, e0, s1, e1;
+    src.span(r, d0.field, s0, e0);
+    src.span(r, d1.field, s1, e1);
+    const uint64_t v0 = hash_span(src, s0, e0, d0.key);
+    store_single(d0.values, g, v0);
+    if (d0.stage != kNoRow) sh.stage[d0.stage * T + r] = v0;
+    if (!two) return;
+    const uint64_t v1 = hash_span(src, s1, e1, d1.key);
+    store_single(d1.values, g, v1);
+    if (d1.stage != kNoRow) sh.stage[d1.stage * T + r] = v1;
   }
   __device__ __forceinline__ void bucket1_unit(uint32_t u) {
     refresh();
