@@ -1285,7 +1285,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     const uint32_t u = grab_unit(&s_ctr[0]);
     if (u >= uh + ub) return false;
     if (FBX_SKIP(1u)) return true;
-    if (u < uh) ps.hash1_unit(u); else ps.bucket1_unit(u - uh);
+    if (u < ub) ps.bucket1_unit(u); else ps.hash1_unit(u - ub);  // (the longer units first: a shorter tail)
     return true;
   };
 
@@ -1355,7 +1355,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   if (P.n_mh && wave == kWaves - 1) ps.item_offsets();
   for_units(&s_ctr[0], uh + ub, [&](uint32_t u) {
     if (FBX_SKIP(1u)) return;
-    if (u < uh) ps.hash1_unit(u); else ps.bucket1_unit(u - uh);
+    if (u < ub) ps.bucket1_unit(u); else ps.hash1_unit(u - ub);  // (the longer units first: a shorter tail)
   });
   FBX_MARK(7);
   // One-launch mode: the words of the tiles before this one (for the wavefront's first ragged
