@@ -118,3 +118,71 @@ def test_options_and_calls_without_workspace():
     res = B.Result()
     assert B.lib().fbx_extract(p._h, None, 0, None, 0, None, ctypes.byref(res)) == B.E_ARG
     p.close()
+
+
+def test_compile_option_and_counters_on_the_host():
+    p = B.Plan(FRAMING_SPEC)
+    assert p.compiled() == (0, 0.0)
+    p.set_option("compile", 1)
+    p.set_option("compile", 0)
+    with pytest.raises(B.FbxError) as e:
+        p.set_option("compile", 2)
+    assert e.value.status == B.E_ARG
+    assert p.compiled() == (0, 0.0)       # nothing is compiled before a call needs it
+    p.close()
+
+
+def test_tile_kernel_source_compiles_for_a_plan_with_the_run_time_compiler():
+    """What plan option compile=1 does on the GPU machine, as far as it goes without a GPU: the tile
+    kernel's source, with a plan's numbers defined as literals the way fbx_jit.cpp writes them, goes
+    through the HIP run-time compilation library for gfx950 (host-only code must stay behind its
+    guards, the three modes must build, the kernels must carry the expected names)."""
+    try:
+        rtc = ctypes.CDLL("libhiprtc.so")
+    except OSError:
+        try:
+            rtc = ctypes.CDLL("/opt/rocm/lib/libhiprtc.so")
+        except OSError:
+            pytest.skip("no run-time compilation library here")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    csrc = os.path.join(root, "paper_2210_07768_amd", "csrc")
+    header = open(os.path.join(csrc, "fbx_device.h")).read()
+    fields = re.findall(r"X\((\w+)\)", header.split("#define FBX_TILE_FIXED_FIELDS(X)")[1].split("\n\n")[0])
+    assert len(fields) >= 30 and "log2T" in fields and "o_prog" in fields
+    # the shape of a two-layer plan on tiles of 32 records (values as the library computes them for
+    # the largest benchmark workload; any consistent set would do for a compile check)
+    shape = dict(n_ops=164, n_layers=2, n_ragged=8, n_rnr=4, n_lists=7, aux_bytes=4096, rnr_words=24, n_mh=4, n_split=4,
+                 n_fields=100, n_stage=68, log2T=5, raw_cap=32768, row_stride=101, o_off=0, o_rs=528, o_re=656, o_rows=784,
+                 o_raw=7248, o_stage=40064, o_cnt=57472, o_start=58496, o_run=59520, o_base=59552, o_prog=63840,
+                 o_lbeg=74336, o_rnr=74368, o_aux=74464, o_tot=59616, o_ioff=59712, o_ctab=59744, o_cap=59648, item_cap=16,
+                 lds_bytes=78560)
+    assert sorted(shape) == sorted(fields), "FBX_TILE_FIXED_FIELDS changed: update the shape used here"
+    clang_inc = None
+    base = os.path.join(os.environ.get("ROCM_PATH", "/opt/rocm"), "lib", "llvm", "lib", "clang")
+    for v in sorted(os.listdir(base)) if os.path.isdir(base) else []:
+        if os.path.exists(os.path.join(base, v, "include", "stddef.h")):
+            clang_inc = os.path.join(base, v, "include")
+    if clang_inc is None:
+        pytest.skip("the compiler's headers are not installed here")
+    for mode in (0, 1, 2):
+        text = (f"#define FBX_FIXED_MODE {mode}\n#define FBX_FIXED_NAME fbx_tile_fixed_{mode}\n#define FBX_FIXED_ASSIGN "
+                + " ".join(f"P.{k} = {shape[k]}u;" for k in fields)
+                + "\n#define FBX_FIXED_LIST_BEGIN {0u, 88u, 96u, 100u, 100u, 104u, 164u, 164u}"
+                + "\n#define FBX_FIXED_RNR_HEAD {0u, 4u, 0u, 0u}\n#include \"fbx_tile.hip\"\n").encode()
+        prog = ctypes.c_void_p()
+        assert rtc.hiprtcCreateProgram(ctypes.byref(prog), text, b"fbx_tile_fixed.hip", 0, None, None) == 0
+        opts = [o.encode() for o in ("--offload-arch=gfx950", "-O3", "-std=c++17", "-I" + csrc, "-I" + os.path.join(root, "include"),
+                                      "-I" + os.path.join(os.environ.get("ROCM_PATH", "/opt/rocm"), "include"), "-I" + clang_inc,
+                                      "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                                      "-mllvm", "-amdgpu-atomic-optimizer-strategy=None")]
+        rc = rtc.hiprtcCompileProgram(prog, len(opts), (ctypes.c_char_p * len(opts))(*opts))
+        n = ctypes.c_size_t()
+        rtc.hiprtcGetProgramLogSize(prog, ctypes.byref(n))
+        log = ctypes.create_string_buffer(max(n.value, 1))
+        rtc.hiprtcGetProgramLog(prog, log)
+        assert rc == 0, log.value.decode()[:2000]
+        rtc.hiprtcGetCodeSize(prog, ctypes.byref(n))
+        code = ctypes.create_string_buffer(n.value)
+        assert rtc.hiprtcGetCode(prog, code) == 0
+        assert f"fbx_tile_fixed_{mode}".encode() in code.raw and n.value > 10000
+        rtc.hiprtcDestroyProgram(ctypes.byref(prog))
