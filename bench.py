@@ -20,6 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# vector instructions the chip can issue per second: one per wavefront, SIMD and 4 cycles
+# (256 compute units x 4 SIMDs x 2.4 GHz / 4); 64 lanes each, i.e. the 157.3 TFLOP/s fp32 vector
+# peak counted in (packed, fused) instructions instead of flops
+VALU_PEAK_PER_S = 256 * 4 * 2.4e9 / 4
 
 # HBM traffic of one launch of the dominant kernel as rocprofv3 counted it (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a device-to-device copy of known
@@ -28,6 +32,11 @@ MEASURED_TRAFFIC = {
     # (workload, records, launch sequence, compiled for the plan): bytes per launch; profiles/k_tile_config5_hbm_traffic.md
     ("config5", 16000000, "one_launch", 1): 42383847152,
     ("config5", 16000000, "one_launch", 0): 42386037351,
+}
+# Vector instructions (SQ_INSTS_VALU) of one launch of the dominant kernel, same keys;
+# profiles/k_tile_config5_instruction_mix.md
+MEASURED_VALU = {
+    ("config5", 16000000, "one_launch", 1): 7752272912,
 }
 
 
@@ -219,6 +228,14 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((w.name, R, launch, args.compile)),
                      "algorithmic_bytes_per_launch": int(launches[dom]), "avg_launch_ms": dom_ms},
     }
+    valu = MEASURED_VALU.get((w.name, R, launch, args.compile))
+    if valu:
+        # what actually bounds the kernel: vector instruction issue.  The count per launch is the
+        # profiled one, the duration this run's.
+        rate = valu / (dom_ms * 1e-3)
+        out["roofline_alu"] = {"bound": "alu", "kernel": kname, "achieved": rate, "peak": VALU_PEAK_PER_S,
+                               "unit": "wavefront vector instructions/s", "frac": rate / VALU_PEAK_PER_S,
+                               "valu_instructions_per_launch": valu, "per_record": valu / R}
     if args.compile:
         # host time spent compiling, all of it before the timed calls unless compiled_in_timed_calls says otherwise
         out["compile"] = {"kernels": compiled_now, "ms": round(plan.compiled()[1], 1),
