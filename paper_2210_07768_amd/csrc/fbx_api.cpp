@@ -99,7 +99,7 @@ namespace {
 struct CallGeometry {
   bool tile_engine = false;
   uint32_t n_tiles = 0, count_waves = 1;
-  uint64_t off_tile_cnt = 0, off_tile_base = 0, arena_base = 0;
+  uint64_t off_tile_cnt = 0, off_tile_base = 0, off_scan_part = 0, arena_base = 0;
   TileParams tp{};  // LDS layout and tile size (tile engine only)
 };
 
@@ -182,6 +182,7 @@ CallGeometry geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records) {
   uint64_t w = p.off_static_end;
   g.off_tile_cnt = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 4);
   g.off_tile_base = w; w = align_up(w + uint64_t(p.host.n_ragged) * g.n_tiles * 8);
+  g.off_scan_part = w; w = align_up(w + uint64_t(p.host.n_ragged) * scan_segments(g.n_tiles) * 8);
   g.arena_base = w;
   return g;
 }
@@ -482,7 +483,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
             tick(1, 1);
           }
           tick(2, 0);
-          FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
+          FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, reinterpret_cast<uint64_t*>(ws + g.off_scan_part), h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
           tick(2, 1);
         }
         tick(3, 0);
@@ -507,7 +508,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
           tick(1, 1);
         }
         tick(2, 0);
-        FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
+        FBX_LAUNCH(launch_scan(P.tile_cnt, P.tile_base, row_total, reinterpret_cast<uint64_t*>(ws + g.off_scan_part), h.n_ragged, g.n_tiles, ctrl, st), "scan kernel");
         tick(2, 1);
       }
       tick(3, 0);

@@ -129,7 +129,10 @@ hipError_t launch_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t
                            hipStream_t st);
 hipError_t launch_count(const WalkParams& P, hipStream_t st);
 hipError_t launch_walk(const WalkParams& P, hipStream_t st);
-hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total, uint32_t n_ragged,
+// part: n_ragged * scan_segments(n_tiles) words of scratch (the sums of the segments a row is cut into)
+constexpr uint32_t kScanSeg = 4096;  // tiles a workgroup of the scan kernels takes
+uint32_t scan_segments(uint32_t n_tiles);
+hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total, uint64_t* part, uint32_t n_ragged,
                        uint32_t n_tiles, const Ctrl* ctrl, hipStream_t st);
 hipError_t launch_alloc(const WalkParams& P, const uint64_t* row_total, uint64_t ws_bytes, int reuse, hipStream_t st);
 hipError_t launch_programs(const WalkParams& P, hipStream_t st);

@@ -37,29 +37,69 @@ __global__ void k_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t
 }
 
 // --------------------------------------------------------------------- scan
-// Exclusive scan over tiles of one ragged operator's per-tile counts.
-__global__ __launch_bounds__(kBlock) void k_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total,
-                                                 uint32_t n_tiles, const Ctrl* ctrl) {
-  __shared__ uint64_t s[kBlock];
+// Exclusive scan over tiles of every ragged operator's per-tile counts, in two launches.  A row
+// (one operator) is cut into segments of kScanSeg tiles; a workgroup takes one segment of one
+// row.  k_scan_sums adds its segment up; k_scan adds the sums of the segments before its own
+// (its carry), then scans its segment 256 tiles at a time.  Neighbouring lanes read and write
+// neighbouring entries throughout.
+__device__ __forceinline__ uint64_t block_sum(uint64_t v, uint64_t* s) {  // s: kBlock / 64 entries; every lane gets the sum
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  const uint32_t w = threadIdx.x >> 6;
+  __syncthreads();  // (s may still be read from an earlier call)
+  if ((threadIdx.x & 63u) == 0) s[w] = v;
+  __syncthreads();
+  uint64_t t = 0;
+  for (uint32_t i = 0; i < kBlock / 64; ++i) t += s[i];
+  return t;
+}
+
+__global__ __launch_bounds__(kBlock) void k_scan_sums(const uint32_t* tile_cnt, uint64_t* part, uint32_t n_tiles,
+                                                      uint32_t n_seg, const Ctrl* ctrl) {
+  __shared__ uint64_t s[kBlock / 64];
   if (ctrl->err) return;
-  const uint32_t row = blockIdx.x, tid = threadIdx.x;
+  const uint32_t row = blockIdx.x / n_seg, seg = blockIdx.x % n_seg, tid = threadIdx.x;
+  const uint32_t* src = tile_cnt + (uint64_t)row * n_tiles;
+  const uint32_t lo = seg * kScanSeg, hi = min(lo + kScanSeg, n_tiles);
+  uint64_t sum = 0;
+  for (uint32_t i = lo + tid; i < hi; i += kBlock) sum += src[i];
+  sum = block_sum(sum, s);
+  if (tid == 0) part[(uint64_t)row * n_seg + seg] = sum;
+}
+
+__global__ __launch_bounds__(kBlock) void k_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total,
+                                                 const uint64_t* part, uint32_t n_tiles, uint32_t n_seg, const Ctrl* ctrl) {
+  __shared__ uint64_t s[kBlock / 64];
+  __shared__ uint64_t s_wave[kBlock / 64];
+  if (ctrl->err) return;
+  const uint32_t row = blockIdx.x / n_seg, seg = blockIdx.x % n_seg, tid = threadIdx.x;
+  const uint32_t lane = tid & 63u, wave = tid >> 6;
   const uint32_t* src = tile_cnt + (uint64_t)row * n_tiles;
   uint64_t* dst = tile_base + (uint64_t)row * n_tiles;
-  const uint32_t chunk = (n_tiles + kBlock - 1) / kBlock;
-  const uint32_t lo = min(tid * chunk, n_tiles), hi = min(lo + chunk, n_tiles);
-  uint64_t sum = 0;
-  for (uint32_t i = lo; i < hi; ++i) sum += src[i];
-  s[tid] = sum;
-  __syncthreads();
-  for (int d = 1; d < kBlock; d <<= 1) {
-    uint64_t t = tid >= (uint32_t)d ? s[tid - d] : 0;
+  uint64_t before = 0;
+  for (uint32_t i = tid; i < seg; i += kBlock) before += part[(uint64_t)row * n_seg + i];
+  uint64_t carry = block_sum(before, s);
+  const uint32_t lo = seg * kScanSeg, hi = min(lo + kScanSeg, n_tiles);
+  for (uint32_t i0 = lo; i0 < hi; i0 += kBlock) {
+    const uint32_t i = i0 + tid;
+    const uint64_t v = i < hi ? src[i] : 0u;
+    uint64_t incl = v;
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint64_t t = __shfl_up(incl, d, 64);
+      if (lane >= (uint32_t)d) incl += t;
+    }
+    __syncthreads();  // (s_wave of the step before has been read)
+    if (lane == 63u) s_wave[wave] = incl;
     __syncthreads();
-    s[tid] += t;
-    __syncthreads();
+    uint64_t below = 0, all = 0;
+    for (uint32_t w = 0; w < kBlock / 64; ++w) {
+      const uint64_t t = s_wave[w];
+      if (w < wave) below += t;
+      all += t;
+    }
+    if (i < hi) dst[i] = carry + below + incl - v;
+    carry += all;
   }
-  uint64_t run = s[tid] - sum;
-  for (uint32_t i = lo; i < hi; ++i) { dst[i] = run; run += src[i]; }
-  if (tid == kBlock - 1) row_total[row] = s[tid];
+  if (seg + 1u == n_seg && tid == 0) row_total[row] = carry;
 }
 
 // ------------------------------------------------------------------- arena
@@ -257,10 +297,19 @@ hipError_t launch_validate(const uint64_t* rec_off, uint64_t n_records, uint64_t
   return hipGetLastError();
 }
 
-hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total, uint32_t n_ragged,
+uint32_t scan_segments(uint32_t n_tiles) { return n_tiles ? (n_tiles + kScanSeg - 1u) / kScanSeg : 1u; }
+
+hipError_t launch_scan(const uint32_t* tile_cnt, uint64_t* tile_base, uint64_t* row_total, uint64_t* part, uint32_t n_ragged,
                        uint32_t n_tiles, const Ctrl* ctrl, hipStream_t st) {
   if (n_ragged == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_scan, dim3(n_ragged), dim3(kBlock), 0, st, tile_cnt, tile_base, row_total, n_tiles, ctrl);
+  const uint32_t n_seg = scan_segments(n_tiles);
+  if (n_seg > 1u) {  // (one segment a row: nothing lies before it)
+    hipLaunchKernelGGL(k_scan_sums, dim3(n_ragged * n_seg), dim3(kBlock), 0, st, tile_cnt, part, n_tiles, n_seg, ctrl);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_scan, dim3(n_ragged * n_seg), dim3(kBlock), 0, st, tile_cnt, tile_base, row_total, part, n_tiles, n_seg,
+                     ctrl);
   return hipGetLastError();
 }
 
