@@ -10,6 +10,7 @@
 #include <dlfcn.h>
 #include <dirent.h>
 
+#include <algorithm>
 #include <chrono>
 #include <cstdlib>
 #include <cstring>
@@ -127,6 +128,9 @@ std::string program_text(const TileParams& P, int mode, const PlanHost& h) {
   std::ostringstream os;
   os << "#define FBX_FIXED_MODE " << mode << "\n#define FBX_FIXED_NAME fbx_tile_fixed_" << mode << "\n#define FBX_FIXED_ASSIGN";
   FBX_TILE_FIXED_FIELDS(FBX_FIELD_ASSIGN)
+  // wavefronts per SIMD the kernel must leave registers for: as many workgroups as the LDS admits
+  const uint32_t groups = std::max(1u, std::min(4u, tile_max_lds() / std::max(P.lds_bytes, 1u)));
+  os << "\n#define FBX_FIXED_WAVES " << std::max(4u, groups * (kTileThreads / 64u) / 4u);
   os << "\n#define FBX_FIXED_LIST_BEGIN ";
   braces(os, h.tile_list_begin.data(), h.tile_list_begin.size());
   // (the table of derived counts starts with the first entry of every layer, padded to four words)

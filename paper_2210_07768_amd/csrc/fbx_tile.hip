@@ -1709,7 +1709,10 @@ __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
 // addresses and far fewer values compete for scalar registers.  The launch checks that the
 // fields it passes are the ones compiled in.
 // (its name, FBX_FIXED_NAME, ends in the mode, so that a trace tells the three kernels apart)
-extern "C" __global__ __launch_bounds__(kTileThreads, 4) void FBX_FIXED_NAME(TileParams Pin) {
+#ifndef FBX_FIXED_WAVES
+#define FBX_FIXED_WAVES 4
+#endif
+extern "C" __global__ __launch_bounds__(kTileThreads, FBX_FIXED_WAVES) void FBX_FIXED_NAME(TileParams Pin) {
   TileParams P = Pin;
   FBX_FIXED_ASSIGN
   tile_body<FBX_FIXED_MODE>(P);
