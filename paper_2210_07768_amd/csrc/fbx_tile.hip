@@ -220,6 +220,32 @@ __device__ __forceinline__ uint32_t eq_flags(uint32_t w, uint32_t pat) {
 }
 constexpr uint32_t kTabs = 0x09090909u, kCommas = 0x2c2c2c2cu;
 
+// Inclusive prefix sum of v inside groups of 1 << lg neighbouring lanes (j: the lane's number in
+// its group).  Inside a row of 16 lanes the steps of 1, 2, 4 and 8 lanes are single
+// data-parallel-primitive moves (row_shr, zero for a lane without a source); a group of several
+// rows then adds the totals of its earlier rows, which come through the LDS crossbar.  Every
+// lane of the wavefront must call it.
+template <int D>
+__device__ __forceinline__ uint32_t row_shr(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x110 + D, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t group_prefix(uint32_t v, uint32_t lg, uint32_t j) {
+  if (lg >= 1u) { const uint32_t t = row_shr<1>(v); v += j >= 1u ? t : 0u; }
+  if (lg >= 2u) { const uint32_t t = row_shr<2>(v); v += j >= 2u ? t : 0u; }
+  if (lg >= 3u) { const uint32_t t = row_shr<4>(v); v += j >= 4u ? t : 0u; }
+  if (lg >= 4u) { const uint32_t t = row_shr<8>(v); v += j >= 8u ? t : 0u; }
+  if (lg > 4u) {  // groups of two or four rows: add the totals of the group's rows before the lane's own
+    const uint32_t first = lane_id() - j;
+    uint32_t carry = 0;
+    for (uint32_t k = 1; k < (1u << (lg - 4u)); ++k) {
+      const uint32_t t = __shfl(v, (int)(first + 16u * k - 1u), 64);
+      if ((j >> 4) >= k) carry += t;
+    }
+    v += carry;
+  }
+  return v;
+}
+
 // 1 << lg neighbouring lanes of a wavefront (j = 0 .. (1 << lg) - 1) split the staged
 // bytes [rs, re) at every delimiter (pat: the delimiter in all four bytes).  Each lane
 // takes an equal run of the 16-byte chunks that cover the range and counts its
@@ -297,11 +323,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
   } else {
     for (uint32_t ci = c0; ci < c1; ++ci) cnt += __popc(chunk_bits(ci) & (uint32_t)inside(ab + 16u * ci, 16u));
   }
-  uint32_t incl = cnt;
-  for (uint32_t s = 1; s < gsz; s <<= 1) {
-    const uint32_t t = __shfl_up(incl, s, 64);
-    if (j >= s) incl += t;
-  }
+  const uint32_t incl = group_prefix(cnt, lg, j);
   const uint32_t total = __shfl(incl, (int)(lane_id() | (gsz - 1u)), 64);
   if (!act || !limit) return total;
   uint32_t k = incl - cnt;
@@ -646,12 +668,7 @@ __device__ __forceinline__ void ragged_root_emit(const Src& src, const OpProg& d
 // ------------------------------------------------------------ one pass of a tile
 // Inclusive prefix sum inside groups of T neighbouring lanes.
 __device__ __forceinline__ uint32_t group_incl_scan(uint32_t v, uint32_t T) {
-  const uint32_t r = lane_id() & (T - 1u);
-  for (uint32_t d = 1; d < T; d <<= 1) {
-    const uint32_t t = __shfl_up(v, d, 64);
-    if (r >= d) v += t;
-  }
-  return v;
+  return group_prefix(v, 31u - (uint32_t)__clz((int)T), lane_id() & (T - 1u));
 }
 
 constexpr uint32_t kWaves = kTileThreads / 64;
