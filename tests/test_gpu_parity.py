@@ -136,20 +136,24 @@ def test_filters_with_short_and_long_prefixes(mode):
     check(_filter_spec(), *_cat(recs), mode, label=f"filters {mode}")
 
 
-@pytest.mark.parametrize("cfg,one_launch", [(5, True), (2, False), (3, True), (4, False)])
-def test_full_size_workloads_on_sampled_records(cfg, one_launch):
-    """The benchmark configurations at their full sizes, run the way bench.py times them (a first
-    call that sizes the workspace, then a call that knows the ragged sizes): properties that hold
-    for the whole result, and windows of records against the oracle."""
+@pytest.mark.parametrize("cfg,one_launch,compile_for_plan", [(5, True, 1), (5, True, 0), (2, False, 1), (3, True, 1), (4, False, 1)],
+                         ids=["config5", "config5_generic_kernel", "config2", "config3", "config4"])
+def test_full_size_workloads_on_sampled_records(cfg, one_launch, compile_for_plan):
+    """The benchmark configurations at their full sizes, run the way bench.py times them (kernels
+    compiled for the plan; a first call that sizes the workspace, then a call that knows the
+    ragged sizes): properties that hold for the whole result, and windows of records against the
+    oracle.  The largest one also with the generic kernel."""
     import torch
 
     w = W.get(cfg)
     d_raw, d_off = device_workload(w)
     R = w.n_records
     plan = B.Plan(w.spec)
+    plan.set_option("compile", compile_for_plan)
     first_res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.03)
     res = plan.extract(d_raw, d_off)
     assert res.tile_launches == (1 if one_launch else 2), res.note
+    assert "generic kernel" not in res.note and (plan.compiled()[0] >= 2) == bool(compile_for_plan), res.note
     assert res.n_records == R and res.n_values_total == first_res.n_values_total
     total = 0
     for s in res.slot_ids:
