@@ -130,6 +130,13 @@ void tile_lds_layout(const PlanHost& h, uint32_t lt, uint32_t raw_cap, TileParam
   tp.o_base = o; o = round16(o + 8ull * h.n_ragged);
   tp.o_tot = o; o = round16(o + 4ull * h.n_ragged);
   tp.o_cap = o; o = round16(o + 8ull * h.n_ragged);
+  tp.n_gen = 0;
+  for (uint32_t layer = 2; layer <= h.n_layers; ++layer) {
+    const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
+    tp.n_gen += h.tile_list_begin[list + 1] - h.tile_list_begin[list];
+  }
+  tp.o_gfirst = o; o = round16(o + (tp.n_gen ? 4ull * h.ops.size() : 0ull));
+  tp.o_gtot = o; o = round16(o + (tp.n_gen ? 4ull * (h.n_layers + 1u) : 0ull));
   tp.o_ioff = o; o = round16(o + 4ull * (tp.n_mh + 1));
   tp.item_cap = 16;
   tp.o_ctab = o; o = round16(o + 2ull * tp.n_mh * T * tp.item_cap);

@@ -61,6 +61,7 @@ struct TileParams {
   uint32_t rnr_words;   // 32-bit words of the rnr table
   uint32_t n_mh;        // multi-valued hashes: the first n_mh entries of the ragged root list
   uint32_t n_split;     // multi-valued root operators of any kind: the first n_split entries of that list
+  uint32_t n_gen;       // list operators of layers >= 2 (crosses and concats that are not computed along with their input)
   uint32_t n_tiles, n_fields, n_stage;
   uint32_t grid;        // upper limit of workgroups to launch (0: as many as run at the same time)
   uint32_t log2T;       // records per tile = 1 << log2T (at most 64)
@@ -69,7 +70,7 @@ struct TileParams {
   // byte offsets of the LDS sections
   uint32_t o_off, o_rs, o_re, o_rows, o_raw, o_stage, o_cnt, o_start, o_run, o_base;
   uint32_t o_prog, o_lbeg, o_rnr, o_aux;  // plan tables
-  uint32_t o_tot, o_ioff, o_ctab, o_cap;
+  uint32_t o_tot, o_ioff, o_ctab, o_cap, o_gfirst, o_gtot;
   uint32_t item_cap;    // comma positions kept per record and multi-valued hash
   uint32_t lds_bytes;
   uint64_t* prof;  // 32 phase counters (tuning builds only), else NULL
@@ -79,10 +80,10 @@ struct TileParams {
 // The fields of TileParams that the plan and the tile size fix (all but addresses, sizes of
 // the batch and tuning switches): a kernel compiled for one plan has them as literals.
 #define FBX_TILE_FIXED_FIELDS(X)                                                                                     \
-  X(n_ops) X(n_layers) X(n_ragged) X(n_rnr) X(n_lists) X(aux_bytes) X(rnr_words) X(n_mh) X(n_split) X(n_fields)     \
+  X(n_ops) X(n_layers) X(n_ragged) X(n_rnr) X(n_lists) X(aux_bytes) X(rnr_words) X(n_mh) X(n_split) X(n_gen) X(n_fields) \
   X(n_stage) X(log2T) X(raw_cap) X(row_stride) X(o_off) X(o_rs) X(o_re) X(o_rows) X(o_raw) X(o_stage) X(o_cnt)     \
   X(o_start) X(o_run) X(o_base) X(o_prog) X(o_lbeg) X(o_rnr) X(o_aux) X(o_tot) X(o_ioff) X(o_ctab) X(o_cap)         \
-  X(item_cap) X(lds_bytes)
+  X(o_gfirst) X(o_gtot) X(item_cap) X(lds_bytes)
 
 #ifndef __HIPCC_RTC__  // (the launch wrappers are host code: not for the run-time compiler)
 // mode 0: counting launch; 1: writing launch (bases from the scan over tiles);

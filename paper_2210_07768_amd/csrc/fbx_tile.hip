@@ -131,6 +131,8 @@ struct Sh {
   uint64_t* base;   // [n_ragged] the tile's base in the operator's values array
   uint32_t* tot;    // [n_ragged] signs of this pass
   uint64_t* cap;    // [n_ragged] signs the operator's array has room for (one-launch mode)
+  uint32_t* gfirst; // [n_ops] list operators of layers >= 2, by program position: first sign among the signs of the layer's list operators in this pass
+  uint32_t* gtot;   // [n_layers + 1] signs of all list operators of a layer in this pass
   uint32_t* ioff;   // [n_mh + 1] first item of every multi-valued hash among the pass's items
   uint16_t* ctab;   // [n_mh][T][item_cap] comma positions of the multi-valued hash fields
   // plan tables, copied once per workgroup so that no lane waits on memory for a descriptor
@@ -167,6 +169,8 @@ __device__ __forceinline__ Sh views(const TileParams& P) {
   s.base = reinterpret_cast<uint64_t*>(smem + P.o_base);
   s.tot = reinterpret_cast<uint32_t*>(smem + P.o_tot);
   s.cap = reinterpret_cast<uint64_t*>(smem + P.o_cap);
+  s.gfirst = reinterpret_cast<uint32_t*>(smem + P.o_gfirst);
+  s.gtot = reinterpret_cast<uint32_t*>(smem + P.o_gtot);
   s.ioff = reinterpret_cast<uint32_t*>(smem + P.o_ioff);
   s.ctab = reinterpret_cast<uint16_t*>(smem + P.o_ctab);
   s.prog = reinterpret_cast<const OpProg*>(smem + P.o_prog);
@@ -1121,12 +1125,33 @@ struct Pass {
     store_single(d->values, g, v);
     if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
   }
-  // Every other cross or concat: lanes are output signs.  A unit is 64 consecutive outputs
-  // of one operator in this pass (operator after operator, record after record); a lane
-  // finds its record by a search over the records' first positions, its place in the
-  // record's list tells which input signs it combines, and neighbouring lanes write
-  // neighbouring signs.
+  // Every other cross or concat: lanes are output signs.  The signs that the list operators of
+  // one layer produce in this pass, operator after operator and record after record, form one
+  // index space; a unit is 64 consecutive ones, whichever operators they belong to, so that
+  // operators with few signs share wavefronts.  A lane finds its operator by a search over the
+  // operators' first signs (gen_offsets), its record by a search over the records' first
+  // positions; its place in the record's list tells which input signs it combines, and
+  // neighbouring lanes write neighbouring signs.  Units before those hand the offsets entries of
+  // the ragged operators to lanes, one (operator, record) each.
   __device__ __forceinline__ uint32_t gen_total(const OpProg& d) const { return d.arity ? d.arity * nb : sh.tot[d.rag_row]; }
+  __device__ __forceinline__ uint32_t gen_list(uint32_t layer) const { return TL_LAYER + 2u * (layer - 2u) + 1u; }
+  // one wavefront, after the positions are known: where every list operator's signs start
+  __device__ __forceinline__ void gen_offsets() {
+    const uint32_t lane = lane_id();
+    for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
+      const uint32_t lb = sh.lbeg(gen_list(layer)), m = sh.lbeg(gen_list(layer) + 1u) - lb;
+      uint32_t carry = 0;
+      for (uint32_t i0 = 0; i0 < m; i0 += 64u) {
+        const uint32_t i = i0 + lane;
+        const uint32_t v = i < m ? gen_total(sh.prog[lb + i]) : 0u;
+        const uint32_t incl = group_prefix(v, 6u, lane);
+        if (i < m) sh.gfirst[lb + i] = carry + incl - v;
+        carry += __shfl(incl, 63, 64);
+      }
+      if (lane == 0) sh.gtot[layer] = carry;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  }
   // sign x of record rr of an earlier operator (single signs from the on-chip table, lists
   // from the arrays this workgroup wrote before the layer barrier)
   __device__ __forceinline__ uint64_t input_sign(const OpProg& d, uint32_t rr, uint32_t x) const {
@@ -1134,27 +1159,49 @@ struct Pass {
     const uint64_t at = d.arity ? (g_first + rr) * d.arity : sh.base[d.rag_row] + sh.start[d.rag_row * T + rr];
     return gptr<const uint64_t>(d.values)[at + x];
   }
-  __device__ __forceinline__ void gen_items(const OpProg& d, uint32_t chunk) {
-    const uint32_t lane = lane_id();
+  __device__ __forceinline__ uint32_t gen_place_units(uint32_t layer) const {
+    return (sh.lbeg(gen_list(layer) + 1u) - sh.lbeg(gen_list(layer)) + G - 1u) / G;
+  }
+  __device__ __forceinline__ uint32_t gen_units(uint32_t layer) const { return gen_place_units(layer) + ((sh.gtot[layer] + 63u) >> 6); }
+  __device__ __forceinline__ void gen_unit(uint32_t layer, uint32_t u) {
+    const uint32_t lb = sh.lbeg(gen_list(layer)), m = sh.lbeg(gen_list(layer) + 1u) - lb;
+    const uint32_t up = gen_place_units(layer);
+    if (u < up) {  // the offsets entries: a lane takes one record of one operator
+      refresh();
+      const uint32_t i = u * G + og;
+      if (i < m && live) {
+        const OpProg& d = sh.prog[lb + i];
+        if (!d.arity) place(d, r, g);
+      }
+      return;
+    }
+    const uint32_t q = (u - up) * 64u + lane_id();
+    if (q >= sh.gtot[layer]) return;
+    // operator: the last one whose first sign is <= q (operators without signs in this pass share
+    // their first sign with the one after them and are passed over)
+    uint32_t lo = 0, hi = m - 1u;
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi + 1u) >> 1;
+      if (sh.gfirst[lb + mid] <= q) lo = mid; else hi = mid - 1u;
+    }
+    const OpProg& d = sh.prog[lb + lo];
+    const uint32_t qq = q - sh.gfirst[lb + lo];  // the sign's number among the operator's signs of this pass
     const uint32_t row = d.rag_row;
-    if (chunk == 0 && !d.arity && lane < nb) place(d, lane, g_first + lane);  // the offsets entries (T <= 64 records)
-    const uint32_t q = chunk * 64u + lane;
-    if (q >= gen_total(d)) return;
     uint32_t rr, j;
     uint64_t at;  // where the sign goes
     if (d.arity) {
-      rr = q / d.arity;
-      j = q - rr * d.arity;
+      rr = qq / d.arity;
+      j = qq - rr * d.arity;
       at = (g_first + rr) * d.arity + j;
     } else {
-      const uint32_t pos = sh.run[row] - sh.tot[row] + q;  // position inside the tile (earlier passes come first)
+      const uint32_t pos = sh.run[row] - sh.tot[row] + qq;  // position inside the tile (earlier passes come first)
       const uint32_t* st = sh.start + row * T;
-      uint32_t lo = 0, hi = nb - 1u;  // the last record whose first position is <= pos (it is the one that has the sign)
-      while (lo < hi) {
-        const uint32_t mid = (lo + hi + 1u) >> 1;
-        if (st[mid] <= pos) lo = mid; else hi = mid - 1u;
+      uint32_t l2 = 0, h2 = nb - 1u;  // the last record whose first position is <= pos (it is the one that has the sign)
+      while (l2 < h2) {
+        const uint32_t mid = (l2 + h2 + 1u) >> 1;
+        if (st[mid] <= pos) l2 = mid; else h2 = mid - 1u;
       }
-      rr = lo;
+      rr = l2;
       j = pos - st[rr];
       at = sh.base[row] + pos;
     }
@@ -1170,39 +1217,6 @@ struct Pass {
       v = j < na ? input_sign(da, rr, j) : input_sign(db, rr, j - na);
     }
     store_sign(gptr<uint64_t>(d.values) + at, v, d.flags & F_STREAM);
-  }
-  // all list operators of one layer; `ctr` numbers the layer's units from zero
-  template <class Skip>
-  __device__ __forceinline__ void gen_layer(uint32_t layer, uint32_t* ctr, Skip&& skip) {
-    const uint32_t lane = lane_id();
-    const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
-    const uint32_t lb = sh.lbeg(list), m = sh.lbeg(list + 1) - lb;
-    uint32_t u = grab_unit(ctr), units_before = 0;
-    for (uint32_t i0 = 0; i0 < m; i0 += 64u) {  // 64 operators at a time: lane l knows the units of operator i0 + l
-      uint32_t chunks = 0;
-      if (i0 + lane < m) {  // (a ragged operator without a sign in this pass still has offsets to write)
-        const OpProg& d = sh.prog[lb + i0 + lane];
-        chunks = max((gen_total(d) + 63u) >> 6, d.arity ? 0u : 1u);
-      }
-      uint32_t incl = chunks;
-      for (uint32_t d = 1; d < 64u; d <<= 1) {
-        const uint32_t t = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += t;
-      }
-      const uint32_t first = units_before + incl - chunks;
-      const uint32_t end = units_before + __shfl(incl, 63, 64);
-      while (u < end) {
-        uint32_t next = 0;
-        if (lane == 0) next = atomicAdd(ctr, 1u);
-        // the unit's operator: the last lane that has units and whose first unit is <= u
-        const uint64_t owners = __ballot(chunks != 0u && first <= u);
-        const uint32_t l = 63u - (uint32_t)__clzll((unsigned long long)owners);
-        const uint32_t c = u - (uint32_t)__shfl(first, (int)l, 64);
-        if (!skip()) gen_items(sh.prog[lb + i0 + l], c);
-        u = __builtin_amdgcn_readfirstlane(next);
-      }
-      units_before = end;
-    }
   }
 };
 
@@ -1370,6 +1384,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // ---- phase C: the rest of layer 1's single signs; one wavefront first lays out the item
   // index space of the multi-valued hashes (needed after at least one more barrier)
   if (P.n_mh && wave == kWaves - 1) ps.item_offsets();
+  if (P.n_gen && wave == kWaves - 2) ps.gen_offsets();  // (likewise: where the list operators' signs start)
   for_units(&s_ctr[0], uh + ub, [&](uint32_t u) {
     if (FBX_SKIP(1u)) return;
     if (u < ub) ps.bucket1_unit(u); else ps.hash1_unit(u - ub);  // (the longer units first: a shorter tail)
@@ -1431,13 +1446,15 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   FBX_MARK(10);
   // ---- the list crosses / concats, layer by layer
   for (uint32_t layer = 2, turn = 0; layer <= P.n_layers; ++layer) {
-    const uint32_t list = TL_LAYER + 2u * (layer - 2u) + 1u;
+    const uint32_t list = ps.gen_list(layer);
     if (sh.lbeg(list + 1) == sh.lbeg(list)) continue;  // (no such operator in this layer: no barrier either)
     __syncthreads();  // the layer barrier
     uint32_t* ctr = &s_ctr[7u + (turn & 1u)];
     if (tid == 0) s_ctr[7u + ((turn + 1u) & 1u)] = 0;  // the counter of the next layer that has any (idle since the barrier before this one)
     ++turn;
-    ps.gen_layer(layer, ctr, [&]() { return (bool)FBX_SKIP(2u); });
+    for_units(ctr, ps.gen_units(layer), [&](uint32_t u) {
+      if (!FBX_SKIP(2u)) ps.gen_unit(layer, u);
+    });
   }
 }
 

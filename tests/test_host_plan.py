@@ -151,10 +151,11 @@ def test_tile_kernel_source_compiles_for_a_plan_with_the_run_time_compiler():
     assert len(fields) >= 30 and "log2T" in fields and "o_prog" in fields
     # the shape of a two-layer plan on tiles of 32 records (values as the library computes them for
     # the largest benchmark workload; any consistent set would do for a compile check)
-    shape = dict(n_ops=164, n_layers=2, n_ragged=8, n_rnr=4, n_lists=7, aux_bytes=4096, rnr_words=24, n_mh=4, n_split=4,
+    shape = dict(n_ops=164, n_layers=2, n_ragged=8, n_rnr=4, n_lists=7, aux_bytes=4096, rnr_words=24, n_mh=4, n_split=4, n_gen=0,
                  n_fields=100, n_stage=68, log2T=5, raw_cap=32768, row_stride=101, o_off=0, o_rs=528, o_re=656, o_rows=784,
                  o_raw=7248, o_stage=40064, o_cnt=57472, o_start=58496, o_run=59520, o_base=59552, o_prog=63840,
-                 o_lbeg=74336, o_rnr=74368, o_aux=74464, o_tot=59616, o_ioff=59712, o_ctab=59744, o_cap=59648, item_cap=16,
+                 o_lbeg=74336, o_rnr=74368, o_aux=74464, o_tot=59616, o_ioff=59712, o_ctab=59744, o_cap=59648, o_gfirst=59712,
+                 o_gtot=59712, item_cap=16,
                  lds_bytes=78560)
     assert sorted(shape) == sorted(fields), "FBX_TILE_FIXED_FIELDS changed: update the shape used here"
     clang_inc = None
