@@ -183,6 +183,21 @@ def test_tile_boundaries(n):
         check(w.spec, raw, off, label=f"{w.name} n={n}")
 
 
+@pytest.mark.parametrize("n", [4095, 4096, 4097, 8192, 12289])
+def test_tile_counts_around_the_scan_segments(n):
+    # the scan over tiles cuts a row into segments of 4 096 tiles: one-record tiles put the record
+    # count right at, one short of and one past whole segments
+    rng = random.Random(n)
+    recs = [(",".join("ab"[:rng.randint(0, 2)] for _ in range(rng.randint(1, 3))) + "\tq" + ("\n" if i % 2 else "")).encode()
+            for i in range(n)]
+    spec = ("fbx 1\nfields 2\n"
+            "op a hash slot=0 seed=1 emit=1 field=0 multi=1\n"
+            "op b hash slot=1 seed=2 emit=1 field=1 multi=0\n"
+            "op c cross slot=2 seed=3 emit=1 a=a b=b\n"
+            "op d cross slot=3 seed=4 emit=1 a=a b=a\n")
+    check(spec, *_cat(recs), {"tile_log2": 0, "one_launch": 0}, label=f"{n} tiles")
+
+
 @pytest.mark.parametrize("misalign", [1, 7, 15])
 def test_unaligned_raw_pointer_and_slack(misalign):
     w = W.get(1, 300)
