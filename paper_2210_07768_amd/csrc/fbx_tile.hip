@@ -340,7 +340,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
       uint32_t n = min((uint32_t)__popc(m), room);
       room -= n;
       for (; n; --n) {
-        const uint32_t i = (uint32_t)__ffs((int)m) - 1u;
+        const uint32_t i = (uint32_t)__builtin_ctz(m);  // (m is not zero here)
         emit(k, base + i);
         ++k;
         m &= m - 1u;
@@ -357,7 +357,7 @@ __device__ __forceinline__ uint32_t split_bytes(const uint8_t* raw, uint32_t rs,
       uint32_t n = min((uint32_t)__popc(m), room);
       room -= n;
       for (; n; --n) {
-        const uint32_t i = (uint32_t)__ffs((int)m) - 1u;
+        const uint32_t i = (uint32_t)__builtin_ctz(m);  // (m is not zero here)
         emit(k, base + i);
         ++k;
         m &= m - 1u;
