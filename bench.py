@@ -112,7 +112,7 @@ def main():
                          "traffic against which FETCH_SIZE / WRITE_SIZE readings of rocprofv3 are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (records shard trivially, see DESIGN.md); use --gpus 1")
+        sys.exit("bench.py: this build runs on exactly one GPU (records are independent: a batch shards by record range); use --gpus 1")
 
     import numpy as np
     import torch
@@ -230,7 +230,7 @@ def main():
     }
     valu = MEASURED_VALU.get((w.name, R, launch, args.compile))
     if valu:
-        # what actually bounds the kernel (DESIGN.md): vector instruction issue.  The count per launch is the
+        # what actually bounds the kernel: vector instruction issue.  The count per launch is the
         # profiled one, the duration this run's.
         rate = valu / (dom_ms * 1e-3)
         out["roofline_alu"] = {"bound": "alu", "kernel": kname, "achieved": rate, "peak": VALU_PEAK_PER_S,
