@@ -55,3 +55,30 @@ BAD_SPECS = {
 }
 
 
+def random_dag(rng, n_roots, n_rest):
+    """A random operator DAG over four fields: (spec text, operator ids in spec order, inputs of each)."""
+    lines = ["fbx 1", "fields 4"]
+    ids, deps = [], {}
+    for i in range(n_roots):
+        kind = rng.choice(["hash", "ngram", "bucket", "filter"])
+        common = f"slot={i} seed={rng.getrandbits(64)} emit={rng.randrange(2)} field={rng.randrange(4)}"
+        if kind == "hash":
+            lines.append(f"op r{i} hash {common} multi={rng.randrange(2)}")
+        elif kind == "ngram":
+            lines.append(f"op r{i} ngram {common} n={rng.randrange(1, 9)}")
+        elif kind == "bucket":
+            b = sorted(rng.randrange(-100, 100) for _ in range(rng.randrange(0, 6)))
+            lines.append(f"op r{i} bucket {common} multi={rng.randrange(2)} bounds={','.join(map(str, b))}")
+        else:
+            lines.append(f"op r{i} filter {common} multi={rng.randrange(2)} prefix={bytes([rng.randrange(97, 100)]).hex()}")
+        ids.append(f"r{i}")
+        deps[f"r{i}"] = ()
+    for i in range(n_rest):
+        a, b = rng.choice(ids), rng.choice(ids)
+        if rng.random() < 0.5:
+            lines.append(f"op n{i} cross slot={1000 + i} seed={rng.getrandbits(64)} emit=1 a={a} b={b}")
+        else:
+            lines.append(f"op n{i} concat slot={1000 + i} emit=1 a={a} b={b}")
+        ids.append(f"n{i}")
+        deps[f"n{i}"] = (a, b)
+    return "\n".join(lines) + "\n", ids, deps

@@ -8,7 +8,7 @@ import pytest
 from oracle import fbx_oracle as O
 from paper_2210_07768_amd import binding as B
 from paper_2210_07768_amd import workloads as W
-from helpers import FRAMING_RECORDS, FRAMING_SPEC
+from helpers import FRAMING_RECORDS, FRAMING_SPEC, random_dag
 from gpu_harness import assert_same, check, check_window, device_workload, run_gpu, to_device
 
 pytestmark = pytest.mark.gpu
@@ -460,6 +460,53 @@ def test_kernels_compiled_for_the_plan_match(case):
     assert_same({s: expand(res2.slots[s], len(off2) - 1) for s in res2.slot_ids}, res2, O.extract(spec, raw2, off2), case)
     assert n_compiled <= plan.compiled()[0] <= 6             # a kernel per mode and tile shape (the batch size may change the shape)
     plan.close()
+
+
+def _random_records(rng, n):
+    def field():
+        kind = rng.randrange(4)
+        if kind == 0:
+            return ",".join("abcab"[:rng.randint(0, 4)] for _ in range(rng.randint(1, 3)))
+        if kind == 1:
+            return ",".join(f"{rng.randint(-120, 120)}.{rng.randint(0, 99)}" for _ in range(rng.randint(1, 2)))
+        if kind == 2:
+            return "".join(rng.choice("abc .") for _ in range(rng.randint(0, 14)))
+        return ""
+    return [("\t".join(field() for _ in range(rng.randint(1, 5))) + ("\n" if i % 3 else "")).encode() for i in range(n)]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_dags_against_the_oracle(seed):
+    """Operator DAGs drawn at random (every kind of root on any field, crosses and concats of anything
+    earlier, emitted or not), on records whose fields are lists, numbers, text or missing: generic and
+    compiled kernels, one- and two-launch sequences, whole tiles and tiles in several passes."""
+    from gpu_harness import expand
+    rng = random.Random(1000 + seed)
+    while True:
+        spec, ids, deps = random_dag(rng, rng.randrange(2, 9), rng.randrange(1, 9))
+        recs = _random_records(rng, rng.choice([70, 257, 600]))
+        raw, off = _cat(recs)
+        raw = np.frombuffer(raw, np.uint8)
+        try:
+            want = O.extract(spec, raw, off)
+        except O.OracleError:
+            continue                       # (a cross of crosses that outgrows the sign limit: draw again)
+        if want.n_values_total <= 3_000_000:
+            break
+    modes = [{}, {"compile": 1}, {"tile_log2": 3, "raw_cap": 64}] if seed % 2 else [{}, {"one_launch": 0, "tile_log2": 5}]
+    for mode in modes:
+        plan = B.Plan(spec)
+        for k, v in mode.items():
+            plan.set_option(k, v)
+        d_raw, d_off = to_device(raw, off)
+        res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.2)
+        assert_same({s: expand(res.slots[s], len(recs)) for s in res.slot_ids}, res, want, f"seed {seed} {mode}")
+        ws.fill_(0x5A)
+        plan.set_workspace(ws)
+        res = plan.extract(d_raw, d_off)   # the second call knows the sizes
+        assert "generic kernel" not in res.note, res.note
+        assert_same({s: expand(res.slots[s], len(recs)) for s in res.slot_ids}, res, want, f"seed {seed} {mode} again")
+        plan.close()
 
 
 def test_results_do_not_depend_on_op_order_or_launch_mode():

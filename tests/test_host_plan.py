@@ -11,7 +11,7 @@ import pytest
 from oracle import fbx_oracle as O
 from paper_2210_07768_amd import binding as B
 from paper_2210_07768_amd import workloads as W
-from helpers import BAD_SPECS, FRAMING_SPEC
+from helpers import BAD_SPECS, FRAMING_SPEC, random_dag
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -53,40 +53,12 @@ def test_layers_and_arity_match_oracle_on_configs(cfg):
     p.close()
 
 
-def _random_dag(rng, n_roots, n_rest):
-    lines = ["fbx 1", "fields 4"]
-    ids, deps = [], {}
-    for i in range(n_roots):
-        kind = rng.choice(["hash", "ngram", "bucket", "filter"])
-        common = f"slot={i} seed={rng.getrandbits(64)} emit={rng.randrange(2)} field={rng.randrange(4)}"
-        if kind == "hash":
-            lines.append(f"op r{i} hash {common} multi={rng.randrange(2)}")
-        elif kind == "ngram":
-            lines.append(f"op r{i} ngram {common} n={rng.randrange(1, 9)}")
-        elif kind == "bucket":
-            b = sorted(rng.randrange(-100, 100) for _ in range(rng.randrange(0, 6)))
-            lines.append(f"op r{i} bucket {common} multi={rng.randrange(2)} bounds={','.join(map(str, b))}")
-        else:
-            lines.append(f"op r{i} filter {common} multi={rng.randrange(2)} prefix={bytes([rng.randrange(97, 100)]).hex()}")
-        ids.append(f"r{i}")
-        deps[f"r{i}"] = ()
-    for i in range(n_rest):
-        a, b = rng.choice(ids), rng.choice(ids)
-        if rng.random() < 0.5:
-            lines.append(f"op n{i} cross slot={1000 + i} seed={rng.getrandbits(64)} emit=1 a={a} b={b}")
-        else:
-            lines.append(f"op n{i} concat slot={1000 + i} emit=1 a={a} b={b}")
-        ids.append(f"n{i}")
-        deps[f"n{i}"] = (a, b)
-    return "\n".join(lines) + "\n", ids, deps
-
-
 def test_layer_rule_properties_on_random_dags():
     # Section 4, "Scheduling": roots in layer 1, every other operator one below its
     # deepest input, hence every edge goes from a lower to a strictly higher layer.
     rng = random.Random(11)
     for _ in range(50):
-        spec, ids, deps = _random_dag(rng, rng.randrange(1, 8), rng.randrange(0, 25))
+        spec, ids, deps = random_dag(rng, rng.randrange(1, 8), rng.randrange(0, 25))
         p = B.Plan(spec)
         _, n_layers, layers, arity = p.info()
         layer = dict(zip(ids, layers))
