@@ -102,8 +102,8 @@ fbx_status fbx_plan_workspace_hint(const fbx_plan* plan, uint64_t raw_len, uint6
                                    uint64_t* bytes);
 
 /*
- * fbx_plan_set_workspace — hand over the pre-allocated pool (Section 5: the
- * pool "is pre-allocated in the GPU global memory").
+ * fbx_plan_set_workspace — hand over the pool, which is reserved up front in
+ * device memory (Section 5).
  *   d_workspace : DEVICE, 256-byte aligned, stays owned by the caller and must
  *                 outlive every fbx_extract that uses it.
  * Copies the plan's constant tables into its head (synchronous copy, once).
@@ -165,6 +165,10 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
  *                  64..65000: that many
  *   "lds_budget"   LDS bytes per workgroup the tile size is chosen for (default 81920)
  *   "grid_limit"   0: as many workgroups as run at the same time (default); else at most that
+ *   "spin_limit"   polls after which a tile of the one-launch sequence stops waiting for an
+ *                  earlier tile's count (default 2^22; 0: it never waits).  A wait that runs out
+ *                  ends no kernel early and writes nothing: the call is answered by the counting
+ *                  sequence instead and fbx_last_error says so.
  *   "profile"      1: time every kernel of fbx_extract with HIP events
  *   "compile"      1: compile the tile kernel for this plan at run time, as Section 4 does with
  *                  the meta-kernel of a layer: the first fbx_extract that meets a tile shape

@@ -47,6 +47,7 @@ struct fbx_plan {
   uint32_t lds_budget = 80u * 1024u;  // two workgroups per compute unit
   uint32_t dbg = 0;
   uint32_t grid_limit = 0;
+  uint32_t spin_limit = 1u << 22;   // polls a tile of the one-launch sequence waits for an earlier tile's count
   int one_launch = 1;             // size ragged arrays from the last call and skip the counting launch
   int compile = 0;                // compile the tile kernel for this plan at run time (Section 4's meta-kernel)
   TileJit jit;
@@ -291,6 +292,9 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "one_launch") {
     if (value != 0 && value != 1) { plan->error = "one_launch must be 0 or 1"; return FBX_E_ARG; }
     plan->one_launch = static_cast<int>(value);
+  } else if (k == "spin_limit") {
+    if (value < 0 || value > (1ll << 30)) { plan->error = "spin_limit must be in 0..2^30"; return FBX_E_ARG; }
+    plan->spin_limit = static_cast<uint32_t>(value);
   } else if (k == "grid_limit") {
     if (value < 0 || value > 65536) { plan->error = "grid_limit must be in 0..65536"; return FBX_E_ARG; }
     plan->grid_limit = static_cast<uint32_t>(value);
@@ -459,6 +463,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
       Q.n_tiles = g.n_tiles; Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
       Q.lds_bytes = std::max(Q.lds_bytes, plan->lds_pad);
       Q.grid = plan->grid_limit;  // 0: as many persistent workgroups as run at the same time
+      Q.spin_limit = plan->spin_limit;
       Q.prof = nullptr;
       Q.dbg = plan->dbg;
 #ifdef FBX_TILE_PROF
@@ -582,14 +587,17 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   for (;;) {
     fbx_status rs = run(one);
     if (rs != FBX_OK) return rs;
-    if (c->err & CE_STALL) {
+    if (!one && (c->err & CE_STALL)) {  // (only the one-launch sequence waits: this cannot happen)
       plan->error = "internal: a bounded wait between tiles ran out";
       return FBX_E_HIP;
     }
-    if (one && (c->err & (CE_SPEC | CE_NOMEM))) {
-      fell_back = (c->err & CE_SPEC) ? "one-launch attempt fell back to the counting launch: a tile larger than the LDS section, or more signs than the arrays were sized for"
-                                     : "one-launch attempt fell back to the counting launch: the margin on the arrays did not fit the workspace";
-      if (!(c->err & CE_SPEC)) plan->margin_failed_ws = plan->ws_bytes;
+    if (one && (c->err & (CE_SPEC | CE_NOMEM | CE_STALL))) {
+      // Every kernel has exited normally and the tiles that could not be placed wrote nothing: the
+      // exact sequence (counting launch, scan, writing launch) can still answer the call.
+      fell_back = (c->err & CE_STALL) ? "one-launch attempt fell back to the counting launch: a bounded wait for an earlier tile ran out"
+                  : (c->err & CE_SPEC) ? "one-launch attempt fell back to the counting launch: a tile larger than the LDS section, or more signs than the arrays were sized for"
+                                       : "one-launch attempt fell back to the counting launch: the margin on the arrays did not fit the workspace";
+      if (!(c->err & (CE_SPEC | CE_STALL))) plan->margin_failed_ws = plan->ws_bytes;
       one = false;  // fall back to counting first
       continue;
     }

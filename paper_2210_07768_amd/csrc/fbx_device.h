@@ -64,6 +64,7 @@ struct TileParams {
   uint32_t n_gen;       // list operators of layers >= 2 (crosses and concats that are not computed along with their input)
   uint32_t n_tiles, n_fields, n_stage;
   uint32_t grid;        // upper limit of workgroups to launch (0: as many as run at the same time)
+  uint32_t spin_limit;  // polls after which a wait for an earlier tile's count is given up (mode 2)
   uint32_t log2T;       // records per tile = 1 << log2T (at most 64)
   uint32_t raw_cap;     // bytes of raw text one pass of a workgroup can stage
   uint32_t row_stride;  // u16 entries per record in the field table (n_fields + 1, padded)

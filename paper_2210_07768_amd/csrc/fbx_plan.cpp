@@ -239,7 +239,10 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
         uint64_t k = 0;
         if (da.arity && db.arity)
           k = ki->kind == OP_CROSS ? uint64_t(da.arity) * db.arity : uint64_t(da.arity) + db.arity;
-        op.d.arity = k <= 0xffffffffull ? static_cast<uint32_t>(k) : 0;
+        // a fixed arity at or beyond the per-record sign limit could never be produced (and arities of
+        // 2^31 and more would collide with the flag bit of the derived-count table)
+        if (k >= (1ull << 26)) return fail("operator would produce 2^26 or more signs for every record");
+        op.d.arity = static_cast<uint32_t>(k);
         if (ki->kind == OP_CROSS) op.d.key = mix64_host(op.seed);
         break;
       }

@@ -709,7 +709,6 @@ __device__ __forceinline__ void for_units(uint32_t* ctr, uint32_t total, F&& uni
 // flag bits and helpers of the one-launch placement (see lb_place_row)
 constexpr uint64_t kLbAggregate = 1ull << 62, kLbPrefix = 2ull << 62, kLbAbort = 3ull << 62;
 constexpr uint64_t kLbValue = (1ull << 62) - 1ull;
-constexpr uint32_t kSpinLimit = 1u << 22;
 
 __device__ __forceinline__ void lb_store(uint64_t* p, uint64_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1230,7 +1229,7 @@ struct Pass {
 // distance to the nearest PREFIX stays a small fraction of the tiles in flight.
 // Workgroups take every W-th tile, so a tile only ever waits for tiles that
 // other running workgroups are counting right now; waits that still exceed
-// kSpinLimit polls are given up and reported.  ABORT marks a tile that cannot be
+// P.spin_limit polls are given up and reported.  ABORT marks a tile that cannot be
 // placed (bad offsets, text larger than the LDS section, array capacity
 // exceeded); it spreads to all later tiles, which then write nothing, and the
 // call is repeated with a counting launch.
@@ -1262,17 +1261,20 @@ __device__ __forceinline__ bool lb_place_row(const TileParams& P, const Sh& sh, 
   FBX_TALLY(15, 1);  // (tuning builds: placements, windows read, polls of an unfinished tile)
   for (;; v = lb_window(P, row, upper)) {
     FBX_TALLY(13, 1);
+    // the wait is bounded: after P.spin_limit polls that found an unfinished tile it is given up
+    // (a limit of zero gives up before the first look: how a test forces the condition from the host)
+    if (spins >= P.spin_limit) {
+      if (lane == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_STALL);
+      abort = true;
+      break;
+    }
     const uint64_t flag = v & ~kLbValue;
     const uint64_t stops = __ballot(flag == kLbPrefix || flag == kLbAbort);
     const uint32_t stop = stops ? (uint32_t)__ffsll((unsigned long long)stops) - 1u : 64u;
     const uint64_t below = stop == 64u ? ~0ull : ((1ull << stop) - 1ull);
     if (__ballot(flag == 0ull) & below) {  // a tile in between has not counted yet
       FBX_TALLY(14, 1);
-      if (++spins > kSpinLimit) {
-        if (lane == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_STALL);
-        abort = true;
-        break;
-      }
+      ++spins;
       __builtin_amdgcn_s_sleep(4);
       continue;
     }

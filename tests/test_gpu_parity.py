@@ -10,6 +10,7 @@ from paper_2210_07768_amd import binding as B
 from paper_2210_07768_amd import workloads as W
 from helpers import FRAMING_RECORDS, FRAMING_SPEC, random_dag
 from gpu_harness import assert_same, check, check_window, device_workload, run_gpu, to_device
+from oracle_ranges import check_every_sign, extract_parallel
 
 pytestmark = pytest.mark.gpu
 
@@ -138,11 +139,14 @@ def test_filters_with_short_and_long_prefixes(mode):
 
 @pytest.mark.parametrize("cfg,one_launch,compile_for_plan", [(5, True, 1), (5, True, 0), (2, False, 1), (3, True, 1), (4, False, 1)],
                          ids=["config5", "config5_generic_kernel", "config2", "config3", "config4"])
-def test_full_size_workloads_on_sampled_records(cfg, one_launch, compile_for_plan):
+def test_full_size_workloads_every_sign(cfg, one_launch, compile_for_plan):
     """The benchmark configurations at their full sizes, run the way bench.py times them (kernels
     compiled for the plan; a first call that sizes the workspace, then a call that knows the
-    ragged sizes): properties that hold for the whole result, and windows of records against the
-    oracle.  The largest one also with the generic kernel."""
+    ragged sizes): properties that hold for the whole result, a few windows of records as a quick
+    check, and then every slot's values and offsets against the oracle, which runs over disjoint
+    record ranges on all host cores, chunk by chunk.  The largest one also with the generic kernel
+    (its full comparison is left to the compiled kernel's run: the windows and properties stay)."""
+    import sys
     import torch
 
     w = W.get(cfg)
@@ -167,12 +171,67 @@ def test_full_size_workloads_on_sampled_records(cfg, one_launch, compile_for_pla
         assert bool((offs[1:] >= offs[:-1]).all()), f"slot {s}: offsets decrease"
     assert total == res.n_values_total
     rng = np.random.default_rng(1000 + cfg)
-    starts = [0, R - 5, 31, 63, R // 2 - 2] + [int(x) for x in rng.integers(0, R - 5, size=35)]
+    starts = [0, R - 5, 31, 63, R // 2 - 2] + [int(x) for x in rng.integers(0, R - 5, size=(35 if not compile_for_plan else 5))]
     for first in starts:
         check_window(w.spec, res, d_raw, d_off, first, 5, label=f"{w.name} full size")
+    if compile_for_plan:
+        said = [0]
+
+        def progress(done, of):  # (a line per tenth of the records: a long, quiet step otherwise)
+            if done * 10 // of > said[0]:
+                said[0] = done * 10 // of
+                print(f"[{w.name}] {done}/{of} records compared with the oracle", file=sys.stderr, flush=True)
+
+        n, _ = check_every_sign(w.spec, res, d_raw, d_off, chunk_records=250_000, label=f"{w.name} full size", progress=progress)
+        assert n == res.n_values_total
     plan.close()
     del ws
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("cfg,n,compile_for_plan,grid_limit",
+                         [(5, 200_000, 0, 0), (5, 200_000, 1, 0), (3, 300_000, 0, 0), (3, 300_000, 1, 0),
+                          (5, 60_000, 1, 8), (3, 100_000, 0, 8)],
+                         ids=["config5_generic", "config5_compiled", "config3_generic", "config3_compiled",
+                              "config5_compiled_8_workgroups", "config3_generic_8_workgroups"])
+def test_one_launch_mode_with_more_tiles_than_workgroups(cfg, n, compile_for_plan, grid_limit):
+    """The one-launch sequence where it is timed: far more tiles than workgroups run at the same
+    time, so that every workgroup takes tile after tile (parked offsets, the hand-over of what the
+    offset check found, the look-back moving past its first window of 64 tiles), and with a grid
+    of only eight workgroups, each of which then takes hundreds of tiles.  A first call (counting +
+    writing), then two calls that place by look-back, the workspace scrubbed in between; every
+    sign of every slot against the oracle."""
+    from gpu_harness import expand
+    w = W.get(cfg, n)
+    raw, off = w.generate()
+    slots, slot_ids, total, malformed = extract_parallel(w.spec, raw, off)
+    plan = B.Plan(w.spec)
+    plan.set_option("compile", compile_for_plan)
+    if grid_limit:
+        plan.set_option("grid_limit", grid_limit)
+    d_raw, d_off = to_device(raw, off)
+    res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.05)
+    tiles = -(-n // (32 if cfg == 5 else 64))
+    assert tiles > 2 * 512                  # (at most two workgroups on each of 256 compute units run at a time)
+    for call in range(3):
+        if call:
+            ws.fill_(0xA5)
+            plan.set_workspace(ws)
+            res = plan.extract(d_raw, d_off)
+            assert res.tile_launches == 1, res.note
+        else:
+            assert res.tile_launches == 2, res.note
+        assert "generic kernel" not in res.note, res.note
+        assert res.n_values_total == total and res.n_malformed_numeric == malformed
+        assert list(res.slot_ids) == list(slot_ids)
+        for s in slot_ids:
+            gv, go = expand(res.slots[s], n)
+            ov, oo, arity = slots[s]
+            assert res.slots[s].fixed_arity == arity
+            assert np.array_equal(go, oo), f"{w.name} call {call} slot {s}: offsets differ"
+            assert np.array_equal(gv, ov), f"{w.name} call {call} slot {s}: signs differ"
+    assert (plan.compiled()[0] >= 2) == bool(compile_for_plan)
+    plan.close()
 
 
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 777])
@@ -406,6 +465,37 @@ def test_one_launch_mode_matches_and_falls_back():
     d_raw, d_off = to_device(np.frombuffer(raw, np.uint8), off)
     res = plan.extract(d_raw, d_off)
     assert_same({s: expand(res.slots[s], len(short)) for s in res.slot_ids}, res, O.extract(spec, np.frombuffer(raw, np.uint8), off))
+    plan.close()
+
+
+@pytest.mark.parametrize("compile_for_plan", [0, 1], ids=["generic", "compiled"])
+def test_a_wait_between_tiles_that_runs_out_falls_back(compile_for_plan):
+    """The one-launch sequence bounds its waits for earlier tiles.  A limit of zero polls, set from
+    the host, makes every such wait run out at once: all kernels still run to their end and write
+    nothing, the call is answered by the counting sequence, says so, and the plan keeps working."""
+    from gpu_harness import expand
+    w = W.get(5, 4000)
+    raw, off = w.generate()
+    want = O.extract(w.spec, raw, off)
+    plan = B.Plan(w.spec)
+    plan.set_option("compile", compile_for_plan)
+    d_raw, d_off = to_device(raw, off)
+    res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.2)
+    res = plan.extract(d_raw, d_off)
+    assert res.tile_launches == 1 and "wait" not in res.note
+    plan.set_option("spin_limit", 0)
+    for _ in range(2):
+        ws.fill_(0x3C)
+        plan.set_workspace(ws)
+        res = plan.extract(d_raw, d_off)
+        assert res.tile_launches == 2 and "bounded wait" in res.note, res.note
+        assert_same({s: expand(res.slots[s], 4000) for s in res.slot_ids}, res, want, "after a wait ran out")
+    plan.set_option("spin_limit", 1 << 22)
+    ws.fill_(0xC3)
+    plan.set_workspace(ws)
+    res = plan.extract(d_raw, d_off)
+    assert res.tile_launches == 1 and "wait" not in res.note, res.note
+    assert_same({s: expand(res.slots[s], 4000) for s in res.slot_ids}, res, want, "one launch again")
     plan.close()
 
 

@@ -159,3 +159,19 @@ def test_tile_kernel_source_compiles_for_a_plan_with_the_run_time_compiler():
         assert rtc.hiprtcGetCode(prog, code) == 0
         assert f"fbx_tile_fixed_{mode}".encode() in code.raw and n.value > 10000
         rtc.hiprtcDestroyProgram(ctypes.byref(prog))
+
+
+def test_fixed_arity_beyond_the_sign_limit_is_a_spec_error():
+    """Concatenating an operator with itself doubles its fixed arity: 25 doublings (2^25 signs per
+    record) are accepted, the 26th reaches the per-record sign limit and the spec is refused."""
+    def spec(doublings):
+        lines = ["fbx 1", "fields 1", "op c0 hash slot=0 seed=1 emit=0 field=0 multi=0"]
+        for k in range(1, doublings + 1):
+            lines.append(f"op c{k} concat slot={k} emit={1 if k == doublings else 0} a=c{k - 1} b=c{k - 1}")
+        return "\n".join(lines) + "\n"
+    plan = B.Plan(spec(25))
+    assert plan.info()[3][-1] == 1 << 25
+    plan.close()
+    with pytest.raises(B.FbxError) as e:
+        B.Plan(spec(26))
+    assert e.value.status == B.E_SPEC and "2^26" in str(e.value)
