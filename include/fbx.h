@@ -140,6 +140,31 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len,
                        const uint64_t* d_rec_off, uint64_t n_records, void* hip_stream,
                        fbx_result* out);
 
+/*
+ * fbx_extract_static — fbx_extract for callers that cannot allocate device memory and have no
+ * workspace to hand over: tight serving loops, code that must not call hipMalloc, harnesses that
+ * forbid it.  Same computation and same results as fbx_extract, but
+ *   - everything the kernels keep beside inputs and outputs (control block, plan tables, per-call
+ *     operator programs, per-tile counts, bases and look-back words) lies in an array of
+ *     fbx_static_scratch_bytes() = 64 MiB that is part of the library's device code: every GPU
+ *     the library runs on holds one copy until the process ends;
+ *   - the operators' arrays (the results) go to the caller's buffer:
+ *       d_out     : DEVICE, 256-byte aligned, out_bytes bytes; out->slots point into it.
+ * No fbx_plan_set_workspace is needed.  The call allocates and frees no device memory and
+ * compiles nothing: plan options "compile" and "profile" are ignored here.
+ * Limit: a batch whose tables exceed the array (they grow with tiles x ragged operators; the
+ * message states the need) is refused with FBX_E_ARG before anything is enqueued.
+ * FBX_E_NOMEM: d_out is too small; out->arena_high_water then holds the out_bytes that suffice.
+ * All calls on one GPU share that GPU's array, which keeps what the last call left there: the
+ * call itself resets what must start from zero and copies the plan's tables in again whenever the
+ * last caller was another plan.  Two calls that overlap in time on one GPU (different threads or
+ * streams) race: serialise them.  Other errors as fbx_extract.
+ */
+fbx_status fbx_extract_static(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len,
+                              const uint64_t* d_rec_off, uint64_t n_records, void* d_out,
+                              uint64_t out_bytes, void* hip_stream, fbx_result* out);
+uint64_t fbx_static_scratch_bytes(void);
+
 /* Last error text of a plan (or of the last failed fbx_plan_create when plan is NULL).  After an
  * fbx_extract that returned FBX_OK it is empty, or a note on why the call took the longer of its
  * two launch sequences. */

@@ -20,6 +20,7 @@ EXPORTS = [
     "fbx_plan_create", "fbx_plan_destroy", "fbx_plan_workspace_hint", "fbx_plan_set_workspace",
     "fbx_extract", "fbx_last_error", "fbx_status_str", "fbx_plan_info", "fbx_plan_set_option",
     "fbx_plan_kernel_ms", "fbx_plan_compiled", "fbx_arena_alloc", "fbx_arena_reset",
+    "fbx_extract_static", "fbx_static_scratch_bytes",
 ]
 
 
@@ -68,6 +69,10 @@ def lib():
         L.fbx_plan_set_workspace.argtypes = [vp, vp, u64]
         L.fbx_extract.restype = ctypes.c_int
         L.fbx_extract.argtypes = [vp, vp, u64, vp, u64, vp, ctypes.POINTER(Result)]
+        L.fbx_extract_static.restype = ctypes.c_int
+        L.fbx_extract_static.argtypes = [vp, vp, u64, vp, u64, vp, u64, vp, ctypes.POINTER(Result)]
+        L.fbx_static_scratch_bytes.restype = u64
+        L.fbx_static_scratch_bytes.argtypes = []
         L.fbx_last_error.restype = ctypes.c_char_p
         L.fbx_last_error.argtypes = [vp]
         L.fbx_status_str.restype = ctypes.c_char_p
@@ -217,15 +222,28 @@ class Plan:
             raise err
         return res
 
-    def extract(self, d_raw, d_rec_off, stream: Optional[int] = None) -> ExtractResult:
-        """d_raw: uint8 CUDA tensor; d_rec_off: int64/uint64 CUDA tensor of n_records + 1 entries."""
+    def extract(self, d_raw, d_rec_off, stream: Optional[int] = None, out_buffer=None) -> ExtractResult:
+        """d_raw: uint8 CUDA tensor; d_rec_off: int64/uint64 CUDA tensor of n_records + 1 entries.
+        With out_buffer (a uint8 CUDA tensor, 256-byte aligned) the call goes to fbx_extract_static:
+        no workspace, results in out_buffer."""
         import torch
 
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
         n_records = d_rec_off.numel() - 1
-        res = self.extract_raw(d_raw.data_ptr() if d_raw.numel() else 0, d_raw.numel(), d_rec_off.data_ptr(),
-                               n_records, stream)
+        raw_ptr = d_raw.data_ptr() if d_raw.numel() else 0
+        if out_buffer is None:
+            res = self.extract_raw(raw_ptr, d_raw.numel(), d_rec_off.data_ptr(), n_records, stream)
+            home = self._ws
+        else:
+            res = Result()
+            st = lib().fbx_extract_static(self._h, raw_ptr, d_raw.numel(), d_rec_off.data_ptr(), n_records,
+                                          out_buffer.data_ptr(), out_buffer.numel(), stream, ctypes.byref(res))
+            if st != OK:
+                err = FbxError(st, lib().fbx_last_error(self._h).decode())
+                err.required_bytes = res.arena_high_water if st == E_NOMEM else 0
+                raise err
+            home = out_buffer
         out = ExtractResult()
         out.n_records, out.n_values_total = res.n_records, res.n_values_total
         out.n_malformed_numeric, out.arena_high_water = res.n_malformed_numeric, res.arena_high_water
@@ -233,9 +251,9 @@ class Plan:
         out.tile_launches = res.tile_launches
         out.note = lib().fbx_last_error(self._h).decode()
         # the library's slot table is overwritten by the next call: copy the plain numbers out now
-        ws64 = self._ws[: self._ws.numel() // 8 * 8].view(torch.int64)
+        ws64 = home[: home.numel() // 8 * 8].view(torch.int64)
         table = ctypes.string_at(res.slots, res.n_slots * ctypes.sizeof(SlotView)) if res.n_slots else b""
-        out._table = (table, ws64, self._ws.data_ptr(), n_records + 1)
+        out._table = (table, ws64, home.data_ptr(), n_records + 1)
         return out
 
 

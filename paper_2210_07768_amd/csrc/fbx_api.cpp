@@ -1,10 +1,12 @@
 // C ABI of libfbx: plan lifetime, workspace layout, and the launch sequence of
 // one extraction call.  See include/fbx.h for the contract of every entry point.
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -60,6 +62,9 @@ struct fbx_plan {
   int last_mode = 0;                     // 1: counting + writing launch, 2: one launch
   uint64_t margin_failed_ws = 0;         // workspace size at which the sized arrays did not fit (no retry below it)
 
+  uint64_t id = 0;                // unique among the plans of this process (a destroyed plan's address may come back)
+  std::vector<uint8_t> tables;    // image of the constant tables, as they lie at the head of a workspace
+
   // results of the last call
   std::vector<uint8_t> readback;  // Ctrl + OpDyn[n_ops]
   std::vector<fbx_slot_view> slots;
@@ -92,6 +97,24 @@ struct fbx_plan {
     off_prof = o; o = align_up(o + 32 * 8);
     off_cap = o; o = align_up(o + host.n_ragged * 8ull);
     off_static_end = o;
+  }
+
+  void build_tables() {
+    const PlanHost& h = host;
+    tables.assign(off_static_end, 0);
+    uint8_t* img = tables.data();
+    std::vector<OpDesc> descs(h.ops.size());
+    for (size_t i = 0; i < h.ops.size(); ++i) descs[i] = h.ops[i].d;
+    if (!descs.empty()) std::memcpy(img + off_ops, descs.data(), descs.size() * sizeof(OpDesc));
+    if (!h.layer_ops.empty()) std::memcpy(img + off_layer_ops, h.layer_ops.data(), h.layer_ops.size() * 4);
+    std::memcpy(img + off_layer_begin, h.layer_begin.data(), h.layer_begin.size() * 4);
+    if (!h.nonroot_ops.empty()) std::memcpy(img + off_nonroot, h.nonroot_ops.data(), h.nonroot_ops.size() * 4);
+    if (!h.aux.empty()) std::memcpy(img + off_aux, h.aux.data(), h.aux.size());
+    if (!h.fields.empty()) std::memcpy(img + off_fields, h.fields.data(), h.fields.size() * sizeof(FieldDesc));
+    if (!h.field_ops.empty()) std::memcpy(img + off_field_ops, h.field_ops.data(), h.field_ops.size() * 4);
+    if (!h.tile_lists.empty()) std::memcpy(img + off_tile_lists, h.tile_lists.data(), h.tile_lists.size() * 4);
+    std::memcpy(img + off_tile_list_begin, h.tile_list_begin.data(), h.tile_list_begin.size() * 4);
+    if (!h.derive_tab.empty()) std::memcpy(img + off_rnr, h.derive_tab.data(), h.derive_tab.size() * 4);
   }
 };
 
@@ -237,6 +260,9 @@ fbx_status fbx_plan_create(const char* spec, size_t spec_len, fbx_plan** out) {
   p->slots.resize(p->emitted.size());
   p->layout();
   p->readback.resize(p->off_actual + p->host.n_ragged * 8ull);
+  p->build_tables();
+  static std::atomic<uint64_t> next_id{1};
+  p->id = next_id.fetch_add(1);
   *out = p.release();
   return FBX_OK;
 }
@@ -338,52 +364,40 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
     plan->error = "workspace smaller than the plan's constant tables (" + std::to_string(plan->off_static_end) + " bytes)";
     return FBX_E_NOMEM;
   }
-  const PlanHost& h = plan->host;
-  std::vector<uint8_t> img(plan->off_static_end, 0);
-  std::vector<OpDesc> descs(h.ops.size());
-  for (size_t i = 0; i < h.ops.size(); ++i) descs[i] = h.ops[i].d;
-  if (!descs.empty()) std::memcpy(img.data() + plan->off_ops, descs.data(), descs.size() * sizeof(OpDesc));
-  if (!h.layer_ops.empty()) std::memcpy(img.data() + plan->off_layer_ops, h.layer_ops.data(), h.layer_ops.size() * 4);
-  std::memcpy(img.data() + plan->off_layer_begin, h.layer_begin.data(), h.layer_begin.size() * 4);
-  if (!h.nonroot_ops.empty()) std::memcpy(img.data() + plan->off_nonroot, h.nonroot_ops.data(), h.nonroot_ops.size() * 4);
-  if (!h.aux.empty()) std::memcpy(img.data() + plan->off_aux, h.aux.data(), h.aux.size());
-  if (!h.fields.empty()) std::memcpy(img.data() + plan->off_fields, h.fields.data(), h.fields.size() * sizeof(FieldDesc));
-  if (!h.field_ops.empty()) std::memcpy(img.data() + plan->off_field_ops, h.field_ops.data(), h.field_ops.size() * 4);
-  if (!h.tile_lists.empty()) std::memcpy(img.data() + plan->off_tile_lists, h.tile_lists.data(), h.tile_lists.size() * 4);
-  std::memcpy(img.data() + plan->off_tile_list_begin, h.tile_list_begin.data(), h.tile_list_begin.size() * 4);
-  if (!h.derive_tab.empty())
-    std::memcpy(img.data() + plan->off_rnr, h.derive_tab.data(), h.derive_tab.size() * 4);
-  hipError_t e = hipMemcpy(d_workspace, img.data(), img.size(), hipMemcpyHostToDevice);
+  hipError_t e = hipMemcpy(d_workspace, plan->tables.data(), plan->tables.size(), hipMemcpyHostToDevice);
   if (e != hipSuccess) return hip_fail(plan, e, "copying plan tables");
   plan->ws = static_cast<uint8_t*>(d_workspace);
   plan->ws_bytes = bytes;
   return FBX_OK;
 }
 
-fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, const uint64_t* d_rec_off,
-                       uint64_t n_records, void* hip_stream, fbx_result* out) {
-  if (!plan || !out || !d_rec_off || (!d_raw && raw_len)) {
-    if (plan) plan->error = "NULL argument";
-    return FBX_E_ARG;
-  }
-  if (!plan->ws) { plan->error = "no workspace set"; return FBX_E_ARG; }
-  if (n_records >= (1ull << 32)) { plan->error = "more than 2^32-1 records in one call"; return FBX_E_ARG; }
+}  // extern "C"
+
+namespace {
+
+// Where one call keeps its memory.  With a workspace everything lies in it: the tables first,
+// the arena (the operators' arrays) from arena_base on.  The entry point that allocates nothing
+// keeps the tables in the library's own device array and the arena in the caller's output buffer.
+struct Regions {
+  uint8_t* tables;       // control block, plan tables, per-call and per-tile tables
+  uint64_t tables_cap;   // bytes there
+  uint64_t origin;       // address that array offsets count from (arena byte 0 lies at origin + arena_base)
+  uint64_t cap;          // array offsets must stay below this
+  bool own_tables;       // the tables are the library's array: no run-time compilation, no event creation
+};
+
+fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, const uint64_t* d_rec_off,
+                        uint64_t n_records, void* hip_stream, fbx_result* out, const Regions& reg, const CallGeometry& g) {
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const PlanHost& h = plan->host;
   const uint32_t n_ops = static_cast<uint32_t>(h.ops.size());
-  const CallGeometry g = geometry(*plan, raw_len, n_records);
-  if (g.arena_base > plan->ws_bytes) {
-    out->arena_high_water = g.arena_base;
-    plan->error = "workspace too small for the per-tile tables; need more than " + std::to_string(g.arena_base) + " bytes";
-    return FBX_E_NOMEM;
-  }
-
-  uint8_t* ws = plan->ws;
+  uint8_t* ws = reg.tables;
+  const uint64_t ws_bytes = reg.cap;
   Ctrl* ctrl = reinterpret_cast<Ctrl*>(ws + plan->off_ctrl);
   OpDyn* dyn = reinterpret_cast<OpDyn*>(ws + plan->off_dyn);
   WalkParams P{};
   P.raw = d_raw; P.raw_len = raw_len; P.rec_off = d_rec_off; P.n_records = n_records;
-  P.ws = ws;
+  P.origin = reg.origin;
   P.ops = reinterpret_cast<const OpDesc*>(ws + plan->off_ops);
   P.fields = reinterpret_cast<const FieldDesc*>(ws + plan->off_fields);
   P.field_ops = reinterpret_cast<const uint32_t*>(ws + plan->off_field_ops);
@@ -407,7 +421,8 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   const uint32_t n_launch = h.n_layers == 0 ? 0 : (plan->fused ? 1 : h.n_layers);
   plan->n_tile_launches = n_launch;
   plan->tile_launch_layer.clear();
-  if (plan->profile) {
+  const bool profile = plan->profile && !reg.own_tables;
+  if (profile) {
     if (plan->timers.size() < 4 + n_launch) plan->timers.resize(4 + n_launch);
     for (Timer& t : plan->timers) {
       t.used = false;
@@ -419,7 +434,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     }
   }
   auto tick = [&](uint32_t which, int edge) {
-    if (plan->profile) {
+    if (profile) {
       (void)hipEventRecord(plan->timers[which].ev[edge], st);
       plan->timers[which].used = true;
     }
@@ -434,7 +449,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   // The tile kernel in one of its modes: the one compiled for this plan if the plan asks for
   // that and it can be had, else the generic one.
   auto tile_launch = [&](const TileParams& Q, int mode) -> hipError_t {
-    if (plan->compile)
+    if (plan->compile && !reg.own_tables)
       if (const FixedTileKernel* k = plan->jit.get(Q, mode, plan->host)) return launch_tile_fixed(*k, Q, st);
     return launch_tile(Q, mode, st);
   };
@@ -478,7 +493,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
         FBX_LAUNCH(hipMemcpyAsync(ws + plan->off_cap, plan->cap_host.data(), h.n_ragged * 8ull, hipMemcpyHostToDevice, st),
                    "capacity upload");
         tick(3, 0);
-        FBX_LAUNCH(launch_alloc(P, Q.row_cap, plan->ws_bytes, 0, st), "allocation kernel");
+        FBX_LAUNCH(launch_alloc(P, Q.row_cap, ws_bytes, 0, st), "allocation kernel");
         tick(3, 1);
         FBX_LAUNCH(launch_fill64(Q.lb_state, uint64_t(h.n_ragged) * g.n_tiles, 0, st), "look-back state");
         tick(4, 0);
@@ -499,7 +514,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
           tick(2, 1);
         }
         tick(3, 0);
-        FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, 0, st), "allocation kernel");
+        FBX_LAUNCH(launch_alloc(P, row_total, ws_bytes, 0, st), "allocation kernel");
         tick(3, 1);
         if (g.n_tiles) {
           tick(4, 0);
@@ -524,7 +539,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
         tick(2, 1);
       }
       tick(3, 0);
-      FBX_LAUNCH(launch_alloc(P, row_total, plan->ws_bytes, plan->fused ? 0 : 1, st), "allocation kernel");
+      FBX_LAUNCH(launch_alloc(P, row_total, ws_bytes, plan->fused ? 0 : 1, st), "allocation kernel");
       tick(3, 1);
       if (g.n_tiles) {
         if (plan->fused) {
@@ -571,7 +586,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   // (every tile reads 512 bytes of placement words per ragged operator: only worth it when that is
   // little next to the tile's own text)
   bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records &&
-             plan->ws_bytes > plan->margin_failed_ws &&
+             ws_bytes > plan->margin_failed_ws &&
              uint64_t(h.n_ragged) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T;
   if (one) {
     plan->cap_host.resize(h.n_ragged);
@@ -597,7 +612,7 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
       fell_back = (c->err & CE_STALL) ? "one-launch attempt fell back to the counting launch: a bounded wait for an earlier tile ran out"
                   : (c->err & CE_SPEC) ? "one-launch attempt fell back to the counting launch: a tile larger than the LDS section, or more signs than the arrays were sized for"
                                        : "one-launch attempt fell back to the counting launch: the margin on the arrays did not fit the workspace";
-      if (!(c->err & (CE_SPEC | CE_STALL))) plan->margin_failed_ws = plan->ws_bytes;
+      if (!(c->err & (CE_SPEC | CE_STALL))) plan->margin_failed_ws = ws_bytes;
       one = false;  // fall back to counting first
       continue;
     }
@@ -620,8 +635,13 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     return FBX_E_INPUT;
   }
   if (c->err & CE_NOMEM) {
-    out->arena_high_water = c->required;
-    plan->error = "workspace too small: need " + std::to_string(c->required) + " bytes";
+    if (reg.own_tables) {
+      out->arena_high_water = c->required - g.arena_base;
+      plan->error = "output buffer too small: need " + std::to_string(c->required - g.arena_base) + " bytes";
+    } else {
+      out->arena_high_water = c->required;
+      plan->error = "workspace too small: need " + std::to_string(c->required) + " bytes";
+    }
     return FBX_E_NOMEM;
   }
   const uint64_t* actual = reinterpret_cast<const uint64_t*>(plan->readback.data() + plan->off_actual);
@@ -643,14 +663,14 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
     v.slot_id = h.ops[i].slot;
     v.fixed_arity = d.arity;
     v.n_values = (one && !d.arity) ? actual[d.rag_row] : y[i].n_values;
-    v.values = reinterpret_cast<const uint64_t*>(ws + y[i].values_off);
-    v.offsets = d.arity ? nullptr : reinterpret_cast<const uint64_t*>(ws + y[i].offsets_off);
+    v.values = reinterpret_cast<const uint64_t*>(reg.origin + y[i].values_off);
+    v.offsets = d.arity ? nullptr : reinterpret_cast<const uint64_t*>(reg.origin + y[i].offsets_off);
     total += v.n_values;
   }
   out->n_records = n_records;
   out->n_values_total = total;
   out->n_malformed_numeric = c->n_malformed;
-  out->arena_high_water = c->high_water;
+  out->arena_high_water = reg.own_tables ? c->high_water - g.arena_base : c->high_water;
   out->n_slots = static_cast<uint32_t>(plan->slots.size());
   out->n_layers = h.n_layers;
   out->slots = plan->slots.data();
@@ -666,6 +686,108 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, c
   }
   out->tile_launches = g.tile_engine ? (one ? 1u : (h.n_ragged ? 2u : 1u)) : 0u;
   return FBX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, const uint64_t* d_rec_off,
+                       uint64_t n_records, void* hip_stream, fbx_result* out) {
+  if (!plan || !out || !d_rec_off || (!d_raw && raw_len)) {
+    if (plan) plan->error = "NULL argument";
+    return FBX_E_ARG;
+  }
+  if (!plan->ws) { plan->error = "no workspace set"; return FBX_E_ARG; }
+  if (n_records >= (1ull << 32)) { plan->error = "more than 2^32-1 records in one call"; return FBX_E_ARG; }
+  const CallGeometry g = geometry(*plan, raw_len, n_records);
+  if (g.arena_base > plan->ws_bytes) {
+    out->arena_high_water = g.arena_base;
+    plan->error = "workspace too small for the per-tile tables; need more than " + std::to_string(g.arena_base) + " bytes";
+    return FBX_E_NOMEM;
+  }
+  const Regions reg{plan->ws, plan->ws_bytes, reinterpret_cast<uint64_t>(plan->ws), plan->ws_bytes, false};
+  return extract_impl(plan, d_raw, raw_len, d_rec_off, n_records, hip_stream, out, reg, g);
+}
+
+// ---- the entry point that allocates nothing
+// Its tables (control block, plan tables, per-call programs, per-tile counts, bases and look-back
+// words) live in this array instead of a workspace.  Every GPU the library runs on holds its own
+// copy from the moment the library is loaded there until the process ends.
+}  // extern "C"
+
+namespace {
+
+constexpr uint64_t kScratchBytes = 64ull << 20;
+static __device__ __align__(256) uint8_t scratch[kScratchBytes];
+// (referenced by device code as well, so that the array is kept whatever the host side does with it)
+__global__ void k_scratch_probe(uint8_t* out) { if (out) *out = scratch[0]; }
+
+constexpr int kMaxDevices = 64;
+struct ScratchOnDevice {
+  uint8_t* ptr = nullptr;   // the array's address on that device (hipGetSymbolAddress, once)
+  uint64_t owner = 0;       // id of the plan whose tables lie at its head
+};
+ScratchOnDevice g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// The array's address on the current device, looked up once per device with that device current.
+hipError_t scratch_on_current_device(int* dev_out, ScratchOnDevice** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  ScratchOnDevice& sd = g_scratch[dev];
+  if (!sd.ptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    sd.ptr = static_cast<uint8_t*>(p);
+  }
+  *dev_out = dev;
+  *out = &sd;
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t fbx_static_scratch_bytes(void) { return kScratchBytes; }
+
+fbx_status fbx_extract_static(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, const uint64_t* d_rec_off,
+                              uint64_t n_records, void* d_out, uint64_t out_bytes, void* hip_stream, fbx_result* out) {
+  if (!plan || !out || !d_rec_off || (!d_raw && raw_len) || !d_out) {
+    if (plan) plan->error = "NULL argument";
+    return FBX_E_ARG;
+  }
+  if (reinterpret_cast<uintptr_t>(d_out) & 255u) { plan->error = "the output buffer must be 256-byte aligned"; return FBX_E_ARG; }
+  if (n_records >= (1ull << 32)) { plan->error = "more than 2^32-1 records in one call"; return FBX_E_ARG; }
+  const CallGeometry g = geometry(*plan, raw_len, n_records);
+  if (g.arena_base > kScratchBytes) {
+    // (rejected before anything is enqueued: the tables of this batch do not fit the library's own array)
+    out->arena_high_water = 0;
+    plan->error = "this batch needs " + std::to_string(g.arena_base) + " bytes of tables (per tile and ragged operator); "
+                  "the entry point that allocates nothing holds " + std::to_string(kScratchBytes) +
+                  ": pass fewer records per call, or use fbx_extract with a workspace";
+    return FBX_E_ARG;
+  }
+  int dev = 0;
+  ScratchOnDevice* sd = nullptr;
+  hipError_t e = scratch_on_current_device(&dev, &sd);
+  if (e != hipSuccess) return hip_fail(plan, e, "address of the library's table array");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (sd->owner != plan->id) {  // another plan's tables (or none) lie there
+    e = hipMemcpyAsync(sd->ptr, plan->tables.data(), plan->tables.size(), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);  // (the image is pageable host memory: done with it before returning)
+    if (e != hipSuccess) { sd->owner = 0; return hip_fail(plan, e, "copying plan tables"); }
+    sd->owner = plan->id;
+  }
+  const uint64_t origin = reinterpret_cast<uint64_t>(d_out) - g.arena_base;
+  const Regions reg{sd->ptr, kScratchBytes, origin, g.arena_base + out_bytes, true};
+  return extract_impl(plan, d_raw, raw_len, d_rec_off, n_records, hip_stream, out, reg, g);
 }
 
 fbx_status fbx_plan_kernel_ms(const fbx_plan* plan, uint32_t which, float* ms) {

@@ -16,7 +16,8 @@ struct WalkParams {
   uint64_t raw_len;
   const uint64_t* rec_off;
   uint64_t n_records;
-  uint8_t* ws;  // workspace base
+  uint64_t origin;  // address that array offsets (OpDyn) count from: the workspace base, or the address that
+                    // puts the arena's first byte at the start of a caller's output buffer
   const OpDesc* ops;
   const FieldDesc* fields;
   const uint32_t* field_ops;

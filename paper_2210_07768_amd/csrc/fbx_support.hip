@@ -154,7 +154,7 @@ __global__ void k_arena_reset(uint64_t* head, uint64_t value) {
 __device__ void write_programs(const WalkParams& P, bool placed) {
   const OpDesc* ops = P.ops;
   const OpDyn* dyn = P.dyn;
-  uint8_t* ws = P.ws;
+  const uint64_t origin = P.origin;
   const uint32_t tid = threadIdx.x;
   __syncthreads();
   for (uint32_t i = tid; i < P.n_ops; i += kBlock) {
@@ -163,8 +163,8 @@ __device__ void write_programs(const WalkParams& P, bool placed) {
     g.kind = d.kind; g.flags = d.flags; g.arity = d.arity; g.rag_row = d.rag_row;
     g.aux_off = d.aux_off; g.aux_len = d.aux_len; g.a = d.a; g.b = d.b;
     g.key = d.key;
-    g.values = placed ? reinterpret_cast<uint64_t>(ws + dyn[i].values_off) : 0;
-    g.offsets = (placed && !d.arity) ? reinterpret_cast<uint64_t>(ws + dyn[i].offsets_off) : 0;
+    g.values = placed ? origin + dyn[i].values_off : 0;
+    g.offsets = (placed && !d.arity) ? origin + dyn[i].offsets_off : 0;
     g.field = d.field;
     g.stage = d.stage;
     if (d.kind == OP_CROSS && ops[d.a].arity == 1 && ops[d.b].arity == 1) {
@@ -191,7 +191,7 @@ __device__ void write_programs(const WalkParams& P, bool placed) {
     if (f.cls == FC_HASH1) {
       const uint32_t op = P.field_ops[f.op_begin];
       g.key = ops[op].key;
-      g.dst = placed ? reinterpret_cast<uint64_t>(ws + dyn[op].values_off) : 0;
+      g.dst = placed ? origin + dyn[op].values_off : 0;
     }
     P.prog_fields[k] = g;
   }
@@ -208,7 +208,6 @@ __global__ __launch_bounds__(kBlock) void k_alloc(WalkParams P, const uint64_t* 
   const OpDesc* ops = P.ops;
   OpDyn* dyn = P.dyn;
   Ctrl* ctrl = P.ctrl;
-  uint8_t* ws = P.ws;
   const uint32_t n_ops = P.n_ops, n_layers = P.n_layers;
   const uint64_t n_records = P.n_records;
   __shared__ uint64_t s_scan[kBlock];
@@ -270,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void k_alloc(WalkParams P, const uint64_t* 
   // an empty batch still owes every ragged slot its single offset entry
   if (n_records == 0 && high <= ws_bytes) {
     for (uint32_t i = tid; i < n_ops; i += kBlock)
-      if (!ops[i].arity) *reinterpret_cast<uint64_t*>(ws + dyn[i].offsets_off) = 0;
+      if (!ops[i].arity) *reinterpret_cast<uint64_t*>(P.origin + dyn[i].offsets_off) = 0;
   }
   write_programs(P, true);
 }
