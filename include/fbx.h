@@ -204,6 +204,16 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
  *                  environment variable FBX_KERNEL_SOURCES=<dir>) are missing the generic kernel
  *                  runs and fbx_last_error says why.
  *                  0: one generic kernel for every plan (default)
+ *   "tile_threads" 512 (default) or 1024: lanes of a workgroup of the kernels compiled for the plan
+ *   "lane_ops"     kernels compiled for the plan, tiles of 64 records ("tile_log2" = 6) only: how the
+ *                  single-sign operators (single-valued hashes and buckets, crosses of two single
+ *                  signs) run.  0 (default): as on any other tile, lanes being (record, operator)
+ *                  pairs; 1: one operator per wavefront at a time, one record per lane, the
+ *                  operator's numbers read from the program table; 2: the same as straight-line
+ *                  code generated for the plan, one piece per operator with its field, key and
+ *                  table rows as literals (Section 4, "Inner-GPU operator launching": every
+ *                  operator a device function, called one after the other).  Measured slower than 0
+ *                  on the benchmark workloads, which is why 0 is the default.
  * Errors: FBX_E_ARG for an unknown key or an out-of-range value.
  */
 fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value);
@@ -213,6 +223,17 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value);
  * compiling them, in milliseconds.  Either pointer may be NULL.
  */
 fbx_status fbx_plan_compiled(const fbx_plan* plan, uint32_t* n_kernels, double* ms);
+
+/*
+ * The source text that option "compile" = 1 hands to the run-time compiler for a batch of this
+ * shape (raw_len bytes, n_records records) and launch mode (0 counting, 1 writing, 2 both in one
+ * launch): the tile kernel's own file behind the definitions that fix the plan's numbers.  HOST
+ * only, needs no GPU.  buf (HOST, buf_len bytes, may be NULL with buf_len 0) receives the text,
+ * NUL-terminated and cut to fit; *needed (may be NULL) the size that holds all of it.
+ * Errors: FBX_E_ARG (also for a plan too wide for the tile kernel).
+ */
+fbx_status fbx_plan_kernel_source(const fbx_plan* plan, uint64_t raw_len, uint64_t n_records, int mode,
+                                  char* buf, size_t buf_len, size_t* needed);
 
 /*
  * Kernel timings of the last fbx_extract (needs option "profile" = 1).

@@ -20,7 +20,7 @@ EXPORTS = [
     "fbx_plan_create", "fbx_plan_destroy", "fbx_plan_workspace_hint", "fbx_plan_set_workspace",
     "fbx_extract", "fbx_last_error", "fbx_status_str", "fbx_plan_info", "fbx_plan_set_option",
     "fbx_plan_kernel_ms", "fbx_plan_compiled", "fbx_arena_alloc", "fbx_arena_reset",
-    "fbx_extract_static", "fbx_static_scratch_bytes",
+    "fbx_extract_static", "fbx_static_scratch_bytes", "fbx_plan_kernel_source",
 ]
 
 
@@ -73,6 +73,9 @@ def lib():
         L.fbx_extract_static.argtypes = [vp, vp, u64, vp, u64, vp, u64, vp, ctypes.POINTER(Result)]
         L.fbx_static_scratch_bytes.restype = u64
         L.fbx_static_scratch_bytes.argtypes = []
+        L.fbx_plan_kernel_source.restype = ctypes.c_int
+        L.fbx_plan_kernel_source.argtypes = [vp, u64, u64, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t,
+                                             ctypes.POINTER(ctypes.c_size_t)]
         L.fbx_last_error.restype = ctypes.c_char_p
         L.fbx_last_error.argtypes = [vp]
         L.fbx_status_str.restype = ctypes.c_char_p
@@ -194,6 +197,14 @@ class Plan:
         n, ms = ctypes.c_uint32(), ctypes.c_double()
         self._check(lib().fbx_plan_compiled(self._h, ctypes.byref(n), ctypes.byref(ms)))
         return n.value, ms.value
+
+    def kernel_source(self, raw_len: int, n_records: int, mode: int) -> str:
+        """The text that compile=1 hands to the run-time compiler for a batch of this shape."""
+        need = ctypes.c_size_t()
+        self._check(lib().fbx_plan_kernel_source(self._h, raw_len, n_records, mode, None, 0, ctypes.byref(need)))
+        buf = ctypes.create_string_buffer(need.value)
+        self._check(lib().fbx_plan_kernel_source(self._h, raw_len, n_records, mode, buf, need.value, None))
+        return buf.value.decode()
 
     def set_option(self, key: str, value: int):
         self._check(lib().fbx_plan_set_option(self._h, key.encode(), int(value)))

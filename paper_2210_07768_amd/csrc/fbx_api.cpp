@@ -52,6 +52,8 @@ struct fbx_plan {
   uint32_t spin_limit = 1u << 22;   // polls a tile of the one-launch sequence waits for an earlier tile's count
   int one_launch = 1;             // size ragged arrays from the last call and skip the counting launch
   int compile = 0;                // compile the tile kernel for this plan at run time (Section 4's meta-kernel)
+  uint32_t tile_threads = 512;    // lanes of a workgroup of the kernels compiled for the plan
+  uint32_t lane_ops = 0;          // tiles of 64 records in compiled kernels: how single-sign operators run (see fbx_tile.hip)
   TileJit jit;
 
   // what the last successful call taught about ragged sizes (signs per ragged operator)
@@ -282,6 +284,30 @@ fbx_status fbx_plan_compiled(const fbx_plan* plan, uint32_t* n_kernels, double* 
   return FBX_OK;
 }
 
+fbx_status fbx_plan_kernel_source(const fbx_plan* plan, uint64_t raw_len, uint64_t n_records, int mode, char* buf,
+                                  size_t buf_len, size_t* needed) {
+  if (!plan || mode < 0 || mode > 2 || (!buf && buf_len)) return FBX_E_ARG;
+  const CallGeometry g = geometry(*plan, raw_len, n_records);
+  if (!g.tile_engine) return FBX_E_ARG;  // (plans too wide for the tile kernel have no such kernel)
+  TileParams Q = g.tp;
+  const PlanHost& h = plan->host;
+  Q.n_ops = static_cast<uint32_t>(h.ops.size()); Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged;
+  Q.n_rnr = h.n_derive;
+  Q.rnr_words = static_cast<uint32_t>(h.derive_tab.size());
+  Q.n_lists = static_cast<uint32_t>(h.tile_list_begin.size()) - 1u;
+  Q.aux_bytes = static_cast<uint32_t>(h.aux.size());
+  Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
+  Q.lds_bytes = std::max(Q.lds_bytes, plan->lds_pad);
+  const std::string text = tile_kernel_source(Q, mode, h, plan->tile_threads, plan->lane_ops);
+  if (needed) *needed = text.size() + 1;
+  if (buf_len) {
+    const size_t n = std::min(buf_len - 1, text.size());
+    std::memcpy(buf, text.data(), n);
+    buf[n] = 0;
+  }
+  return FBX_OK;
+}
+
 fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_layers, uint32_t* layer_of_op,
                          uint32_t* arity_of_op) {
   if (!plan) return FBX_E_ARG;
@@ -315,6 +341,12 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "compile") {
     if (value != 0 && value != 1) { plan->error = "compile must be 0 or 1"; return FBX_E_ARG; }
     plan->compile = static_cast<int>(value);
+  } else if (k == "lane_ops") {
+    if (value < 0 || value > 2) { plan->error = "lane_ops must be 0, 1 or 2"; return FBX_E_ARG; }
+    plan->lane_ops = static_cast<uint32_t>(value);
+  } else if (k == "tile_threads") {
+    if (value != 512 && value != 1024) { plan->error = "tile_threads must be 512 or 1024"; return FBX_E_ARG; }
+    plan->tile_threads = static_cast<uint32_t>(value);
   } else if (k == "one_launch") {
     if (value != 0 && value != 1) { plan->error = "one_launch must be 0 or 1"; return FBX_E_ARG; }
     plan->one_launch = static_cast<int>(value);
@@ -450,7 +482,7 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
   // that and it can be had, else the generic one.
   auto tile_launch = [&](const TileParams& Q, int mode) -> hipError_t {
     if (plan->compile && !reg.own_tables)
-      if (const FixedTileKernel* k = plan->jit.get(Q, mode, plan->host)) return launch_tile_fixed(*k, Q, st);
+      if (const FixedTileKernel* k = plan->jit.get(Q, mode, plan->host, plan->tile_threads, plan->lane_ops)) return launch_tile_fixed(*k, Q, st);
     return launch_tile(Q, mode, st);
   };
   // One attempt: everything is enqueued on the stream, then one synchronisation.

@@ -39,7 +39,11 @@ struct WalkParams {
 };
 
 // ---- tile kernel: one workgroup takes a tile of 2^log2T records through every layer
-constexpr int kTileThreads = 512;
+// (512 lanes in the kernel for any plan; a kernel compiled for one plan may be compiled for 1024)
+#ifndef FBX_TILE_THREADS
+#define FBX_TILE_THREADS 512
+#endif
+constexpr int kTileThreads = FBX_TILE_THREADS;
 constexpr uint32_t kRawPad = 16;  // first byte position of the staged raw text inside its LDS section
 
 struct TileParams {
@@ -101,6 +105,8 @@ struct FixedTileKernel {
   void* module = nullptr;      // hipModule_t
   void* function = nullptr;    // hipFunction_t; null: the attempt failed
   uint32_t per_cu = 1;         // workgroups of it that fit a compute unit
+  uint32_t threads = 512;      // lanes of a workgroup it was compiled for
+  uint32_t lane_ops = 0;       // how tiles of 64 records run single-sign operators (FBX_LANE_OPS in fbx_tile.hip)
 };
 // The compiled kernels of one plan.
 class TileJit {
@@ -113,7 +119,7 @@ class TileJit {
   // The kernel for these parameters, compiled now if it is not there yet; null if there is none
   // (note() then says why).  The device the kernel is to run on must be current; h is the plan
   // the object belongs to (always the same one: its list bounds are compiled in too).
-  const FixedTileKernel* get(const TileParams& P, int mode, const PlanHost& h);
+  const FixedTileKernel* get(const TileParams& P, int mode, const PlanHost& h, uint32_t threads, uint32_t lane_ops);
   void release();
   const std::string& note() const { return note_; }
   double compile_ms() const { return compile_ms_; }  // spent compiling so far
@@ -125,6 +131,8 @@ class TileJit {
   uint32_t compiled_ = 0;
 };
 hipError_t launch_tile_fixed(const FixedTileKernel& k, const TileParams& P, hipStream_t st);
+// The text that TileJit compiles for these parameters (fbx_tile.hip behind a few definitions).
+std::string tile_kernel_source(const TileParams& P, int mode, const PlanHost& h, uint32_t threads, uint32_t lane_ops);
 uint32_t tile_cu_count();
 
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st);

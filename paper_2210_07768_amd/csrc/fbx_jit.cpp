@@ -124,13 +124,14 @@ void braces(std::ostringstream& os, const uint32_t* v, size_t n) {
   os << "}";
 }
 
-std::string program_text(const TileParams& P, int mode, const PlanHost& h) {
+std::string program_text(const TileParams& P, int mode, const PlanHost& h, uint32_t threads, uint32_t lane_ops) {
   std::ostringstream os;
+  os << "#define FBX_TILE_THREADS " << threads << "\n";
   os << "#define FBX_FIXED_MODE " << mode << "\n#define FBX_FIXED_NAME fbx_tile_fixed_" << mode << "\n#define FBX_FIXED_ASSIGN";
   FBX_TILE_FIXED_FIELDS(FBX_FIELD_ASSIGN)
   // wavefronts per SIMD the kernel must leave registers for: as many workgroups as the LDS admits
   const uint32_t groups = std::max(1u, std::min(4u, tile_max_lds() / std::max(P.lds_bytes, 1u)));
-  os << "\n#define FBX_FIXED_WAVES " << std::max(4u, groups * (kTileThreads / 64u) / 4u);
+  os << "\n#define FBX_FIXED_WAVES " << std::max(4u, groups * (threads / 64u) / 4u);
   os << "\n#define FBX_FIXED_LIST_BEGIN ";
   braces(os, h.tile_list_begin.data(), h.tile_list_begin.size());
   // (the table of derived counts starts with the first entry of every layer, padded to four words)
@@ -138,12 +139,57 @@ std::string program_text(const TileParams& P, int mode, const PlanHost& h) {
   const size_t head = h.derive_tab.empty() ? 0 : 4u * ((h.n_layers + 3u) / 4u);
   os << "\n#define FBX_FIXED_RNR_HEAD ";
   braces(os, head ? h.derive_tab.data() : &none, head ? head : 1);
+  if (P.log2T != 6u) lane_ops = 0;
+  os << "\n#define FBX_LANE_OPS " << lane_ops;
+  if (lane_ops == 2u) {
+    // Tiles of 64 records: a wavefront runs one single-sign operator at a time, one record per lane.
+    // Those operators become straight-line code with their numbers written in, one case each:
+    // single-valued buckets and hashes of layer 1 (in the order of their work lists: a unit of
+    // work is an operator), and per later layer the crosses of two single signs.
+    auto hex = [&](uint64_t v) { os << "0x" << std::hex << v << std::dec << "ull"; };
+    uint32_t u = 0;
+    os << "\n#define FBX_GEN_L1";
+    for (uint32_t list : {(uint32_t)TL_BUCKET1, (uint32_t)TL_HASH1}) {
+      for (uint32_t i = h.tile_list_begin[list]; i < h.tile_list_begin[list + 1]; ++i, ++u) {
+        const uint32_t op = h.tile_lists[i];
+        const OpDesc& d = h.ops[op].d;
+        os << " case " << u << "u: ";
+        if (list == TL_BUCKET1) {
+          os << "lane_bucket1(" << d.field << "u, here(";
+          hex(d.key);
+          os << "), " << d.aux_off << "u, " << d.aux_len << "u, values_of(" << op << "u), " << d.stage << "u); break;";
+        } else {
+          os << "lane_hash1(" << d.field << "u, here(";
+          hex(d.key);
+          os << "), values_of(" << op << "u), " << d.stage << "u); break;";
+        }
+      }
+    }
+    os << "\n#define FBX_GEN_X11";
+    for (uint32_t layer = 2; layer <= h.n_layers; ++layer) {
+      const uint32_t list = TL_LAYER + 2u * (layer - 2u);
+      os << " case " << layer << "u: switch (u) {";
+      u = 0;
+      for (uint32_t i = h.tile_list_begin[list]; i < h.tile_list_begin[list + 1]; ++i, ++u) {
+        const uint32_t op = h.tile_lists[i];
+        const OpDesc& d = h.ops[op].d;
+        os << " case " << u << "u: lane_x11(" << h.ops[d.a].d.stage << "u, " << h.ops[d.b].d.stage << "u, here(";
+        hex(d.key);
+        os << "), values_of(" << op << "u), " << d.stage << "u); break;";
+      }
+      os << " } break;";
+    }
+  }
   os << "\n#include \"fbx_tile.hip\"\n";
   return os.str();
 }
 #undef FBX_FIELD_ASSIGN
 
 }  // namespace
+
+std::string tile_kernel_source(const TileParams& P, int mode, const PlanHost& h, uint32_t threads, uint32_t lane_ops) {
+  return program_text(P, mode, h, threads, lane_ops);
+}
 
 TileJit::~TileJit() { release(); }
 
@@ -153,8 +199,9 @@ void TileJit::release() {
   kernels_.clear();
 }
 
-const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHost& h) {
+const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHost& h, uint32_t threads, uint32_t lane_ops) {
   std::vector<uint32_t> key = fixed_values(P);
+  key.push_back(threads | (lane_ops << 16));
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = 0; }
   key.push_back(static_cast<uint32_t>(dev));  // (a loaded kernel belongs to one device)
@@ -167,6 +214,8 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHos
   FixedTileKernel k;
   k.mode = mode;
   k.key = key;
+  k.threads = threads;
+  k.lane_ops = lane_ops;
   auto fail = [&](const std::string& why) -> const FixedTileKernel* {
     note_ = "compile=1: " + why + "; the generic kernel runs";
     kernels_.push_back(k);  // (remembered, so that the attempt is not made again)
@@ -182,7 +231,7 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHos
   arch = arch.substr(0, arch.find(':'));
 
   const auto t0 = std::chrono::steady_clock::now();
-  const std::string text = program_text(P, mode, h);
+  const std::string text = program_text(P, mode, h, threads, lane_ops);
   hiprtcProgram prog = nullptr;
   if (r.create(&prog, text.c_str(), "fbx_tile_fixed.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS) return fail("the program could not be created");
   const std::string o_arch = "--offload-arch=" + arch, i0 = "-I" + p.csrc, i1 = "-I" + p.include, i2 = "-I" + p.rocm_include,
@@ -224,7 +273,7 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHos
     return fail("the compiled code has no kernel");
   }
   int per_cu = 0;
-  if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kTileThreads, P.lds_bytes) != hipSuccess || per_cu < 1) {
+  if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, (int)threads, P.lds_bytes) != hipSuccess || per_cu < 1) {
     (void)hipGetLastError();
     per_cu = 1;
   }
@@ -240,6 +289,7 @@ const FixedTileKernel* TileJit::get(const TileParams& P, int mode, const PlanHos
 hipError_t launch_tile_fixed(const FixedTileKernel& k, const TileParams& P, hipStream_t st) {
   if (P.n_tiles == 0) return hipSuccess;
   std::vector<uint32_t> now = fixed_values(P);
+  now.push_back(k.threads | (k.lane_ops << 16));
   now.push_back(k.key.back());
   if (now != k.key) return hipErrorInvalidValue;  // (a kernel compiled for other numbers)
   uint32_t capacity = tile_cu_count() * k.per_cu;  // as many workgroups as run at the same time
@@ -247,7 +297,7 @@ hipError_t launch_tile_fixed(const FixedTileKernel& k, const TileParams& P, hipS
   TileParams Q = P;
   void* args[] = {&Q};
   const uint32_t grid = std::min(P.n_tiles, capacity);
-  return hipModuleLaunchKernel(reinterpret_cast<hipFunction_t>(k.function), grid, 1, 1, kTileThreads, 1, 1, P.lds_bytes, st, args,
+  return hipModuleLaunchKernel(reinterpret_cast<hipFunction_t>(k.function), grid, 1, 1, k.threads, 1, 1, P.lds_bytes, st, args,
                                nullptr);
 }
 

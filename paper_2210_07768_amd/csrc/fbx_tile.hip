@@ -43,6 +43,14 @@
 
 #include "fbx_device.h"
 
+// How a tile of 64 records runs its single-sign operators (kernels compiled for a plan only): 0 as any
+// other tile, 1 one operator per wavefront with its numbers from the program table, 2 the same as
+// straight-line code generated for the plan (FBX_GEN_L1, FBX_GEN_X11).
+#ifndef FBX_LANE_OPS
+#define FBX_LANE_OPS 0
+#endif
+
+
 namespace fbx {
 namespace {
 
@@ -61,6 +69,13 @@ template <class T>
 __device__ __forceinline__ FBX_GLOBAL T* gptr(T* p) { return reinterpret_cast<FBX_GLOBAL T*>(reinterpret_cast<uintptr_t>(p)); }
 using G64 = FBX_GLOBAL uint64_t*;
 using CG64 = const FBX_GLOBAL uint64_t*;
+// Memory that no kernel of the call writes while this one runs (the per-call operator programs): loads
+// through such a pointer at an address all lanes share go through the scalar unit.
+#define FBX_CONSTANT __attribute__((address_space(4)))
+template <class T>
+__device__ __forceinline__ const FBX_CONSTANT T* cptr(const T* p) {
+  return reinterpret_cast<const FBX_CONSTANT T*>(reinterpret_cast<uintptr_t>(p));
+}
 
 extern __shared__ __align__(16) uint8_t smem[];
 
@@ -1113,6 +1128,88 @@ struct Pass {
     for (uint32_t q = lane; q < ng; q += 64) vals[q] = hash_span(src, s + q, s + q + n, key);
   }
 
+  // A 64-bit literal of generated code, handed over in scalar registers at the place of its use (otherwise
+  // the compiler collects every operator's key in vector registers ahead of the tile loop, and spills them).
+  static __device__ __forceinline__ uint64_t here(uint64_t k) {
+    uint32_t lo = (uint32_t)k, hi = (uint32_t)(k >> 32);
+    asm volatile("" : "+s"(lo), "+s"(hi));
+    return ((uint64_t)hi << 32) | lo;
+  }
+  // ---- one operator on the (up to 64) records of a tile, one record per lane
+  // For tiles of 64 records a wavefront runs one single-sign operator at a time, and what the
+  // operator is (field, key, table rows) is the same in every lane.  In a kernel generated for
+  // the plan these are literals of straight-line code, one piece per operator (the meta-kernel
+  // of Section 4, "Inner-GPU operator launching": each operator a device function, called one
+  // after the other); `op` is the operator's number, under which its array's address lies in the
+  // per-call program table (read through the scalar unit).  Staged records only.
+  // where a single sign of operator `op` goes: to the caller's array (streamed, nothing on the device
+  // reads it again) and, if a later operator reads it, to the on-chip table
+  __device__ __forceinline__ void lane_put(uint32_t lane, uint64_t values, uint32_t stage, uint64_t v) const {
+    __builtin_nontemporal_store(v, gptr<uint64_t>(values) + g_first + lane);
+    if (stage != kNoRow) sh.stage[stage * 64u + lane] = v;
+  }
+  // the address of operator op's array, from the per-call program table through the scalar unit
+  // (generated code: the same address in every lane)
+  __device__ __forceinline__ uint64_t values_of(uint32_t op) const { return cptr(P.prog)[op].values; }
+  __device__ __forceinline__ void lane_hash1(uint32_t field, uint64_t key, uint64_t values, uint32_t stage) const {
+    const uint32_t lane = lane_id();
+    if (lane >= nb) return;
+    uint32_t s, e;
+    src.span(lane, field, s, e);
+    lane_put(lane, values, stage, hash_span(src, s, e, key));
+  }
+  __device__ __forceinline__ void lane_bucket1(uint32_t field, uint64_t key, uint32_t aux_off, uint32_t n_bounds, uint64_t values,
+                                               uint32_t stage) {
+    const uint32_t lane = lane_id();
+    if (lane >= nb) return;
+    uint32_t s, e;
+    src.span(lane, field, s, e);
+    NumState ns;
+    for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
+    bool bad;
+    const int64_t v = ns.finish(bad);
+    malformed += bad ? 1u : 0u;
+    const int64_t* b = reinterpret_cast<const int64_t*>(sh.aux + aux_off);
+    uint32_t lo = 0, hi = n_bounds;  // index = number of boundaries <= v
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (b[mid] <= v) lo = mid + 1; else hi = mid;
+    }
+    lane_put(lane, values, stage, mix64(key + lo));
+  }
+  __device__ __forceinline__ void lane_x11(uint32_t stage_a, uint32_t stage_b, uint64_t key, uint64_t values, uint32_t stage) const {
+    const uint32_t lane = lane_id();
+    if (lane >= nb) return;
+    const uint64_t a = sh.stage[stage_a * 64u + lane], b = sh.stage[stage_b * 64u + lane];
+    lane_put(lane, values, stage, mix64(mix64(a + key) + b));
+  }
+#if FBX_LANE_OPS == 2
+  // generated: one case per single-valued bucket, then one per single-valued hash, in the order of
+  // the work lists; per later layer one case per cross of two single signs
+  __device__ __forceinline__ void lane_l1_unit(uint32_t u) {
+    switch (u) { FBX_GEN_L1 }
+  }
+  __device__ __forceinline__ void lane_x11_unit(uint32_t layer, uint32_t u) {
+    switch (layer) { FBX_GEN_X11 }
+  }
+#else
+  // the same bodies, the operator's numbers read from the program table in LDS (one small piece of code for all)
+  __device__ __forceinline__ void lane_l1_unit(uint32_t u) {
+    const uint32_t ub = sh.lbeg(TL_BUCKET1 + 1) - sh.lbeg(TL_BUCKET1);
+    if (u < ub) {
+      const OpProg& d = sh.prog[sh.lbeg(TL_BUCKET1) + u];
+      lane_bucket1(d.field, d.key, d.aux_off, d.aux_len, d.values, d.stage);
+    } else {
+      const OpProg& d = sh.prog[sh.lbeg(TL_HASH1) + (u - ub)];
+      lane_hash1(d.field, d.key, d.values, d.stage);
+    }
+  }
+  __device__ __forceinline__ void lane_x11_unit(uint32_t layer, uint32_t u) {
+    const OpProg& d = sh.prog[sh.lbeg(TL_LAYER + 2u * (layer - 2u)) + u];
+    lane_x11(d.aux_off, d.aux_len, d.key, d.values, d.stage);
+  }
+#endif
+
   // ---- later layers
   // crosses of two single signs, both on chip
   __device__ __forceinline__ void x11_unit(uint32_t layer, uint32_t u) {
@@ -1313,8 +1410,19 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   ps.live = ps.r < nb;
   ps.g = g_first + ps.r;
   // the single-valued hashes and buckets of layer 1 fill whatever phase has idle wavefronts
-  const uint32_t uh = WRITE ? ps.hash1_units() : 0u, ub = WRITE ? ps.units_of(TL_BUCKET1) : 0u;
+  // tiles of 64 staged records in a kernel compiled for the plan: one single-sign operator a unit, one record a lane
+  constexpr bool kGen = FBX_LANE_OPS != 0 && Src::kTable;
+  const uint32_t ub = WRITE ? ps.units_of(TL_BUCKET1) : 0u;
+  const uint32_t uh = !WRITE ? 0u : (kGen ? sh.lbeg(TL_HASH1 + 1) - sh.lbeg(TL_HASH1) : ps.hash1_units());
+  auto l1_unit = [&](uint32_t u) {
+    if (FBX_SKIP(1u)) return;
+    if constexpr (kGen) { ps.lane_l1_unit(u); return; }
+    if (u < ub) ps.bucket1_unit(u); else ps.hash1_unit(u - ub);  // (the longer units first: a shorter tail)
+  };
+  // (the code generated for a plan's operators is large: it stays in one place, the loop of phase C, and
+  // wavefronts that find no counting unit left then just wait)
   auto fill_one = [&]() -> bool {
+    if constexpr (kGen) return false;
     const uint32_t u = grab_unit(&s_ctr[0]);
     if (u >= uh + ub) return false;
     if (FBX_SKIP(1u)) return true;
@@ -1387,10 +1495,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // index space of the multi-valued hashes (needed after at least one more barrier)
   if (P.n_mh && wave == kWaves - 1) ps.item_offsets();
   if (P.n_gen && wave == kWaves - 2) ps.gen_offsets();  // (likewise: where the list operators' signs start)
-  for_units(&s_ctr[0], uh + ub, [&](uint32_t u) {
-    if (FBX_SKIP(1u)) return;
-    if (u < ub) ps.bucket1_unit(u); else ps.hash1_unit(u - ub);  // (the longer units first: a shorter tail)
-  });
+  for_units(&s_ctr[0], uh + ub, l1_unit);
   FBX_MARK(7);
   // One-launch mode: the words of the tiles before this one (for the wavefront's first ragged
   // operator) are requested now, so that they arrive while the single crosses run.
@@ -1404,7 +1509,9 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
     const uint32_t ux = ps.units_of(TL_LAYER + 2u * (layer - 2u));
     for_units(ctr, ux, [&](uint32_t u) {
-      if (!FBX_SKIP(2u)) ps.x11_unit(layer, u);
+      if (FBX_SKIP(2u)) return;
+      if constexpr (kGen) { ps.lane_x11_unit(layer, u); return; }
+      ps.x11_unit(layer, u);
     });
   }
   FBX_MARK(8);
@@ -1755,7 +1862,7 @@ extern "C" __global__ __launch_bounds__(kTileThreads, FBX_FIXED_WAVES) void FBX_
 }
 #endif
 
-#ifndef __HIPCC_RTC__
+#if !defined(__HIPCC_RTC__) && !defined(FBX_FIXED_MODE)
 // ----------------------------------------------------------- launch wrappers
 uint32_t tile_max_lds() {
   static uint32_t cached = 0;
@@ -1765,7 +1872,7 @@ uint32_t tile_max_lds() {
         hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0)
       cached = (uint32_t)v;
     else
-      cached = 64u * 1024u;
+      cached = 160u * 1024u;  // (no device to ask, as when a plan's kernel source is only written out: gfx950's)
   }
   return cached;
 }

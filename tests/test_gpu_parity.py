@@ -552,6 +552,47 @@ def test_kernels_compiled_for_the_plan_match(case):
     plan.close()
 
 
+@pytest.mark.parametrize("lane_ops,threads", [(1, 512), (2, 512), (1, 1024), (2, 1024)],
+                         ids=["table_512", "generated_512", "table_1024", "generated_1024"])
+def test_one_operator_per_wavefront_on_tiles_of_64_records(lane_ops, threads):
+    """Kernels compiled for the plan, tiles of 64 records: a wavefront runs one single-sign operator at
+    a time, one record per lane, its numbers read from the program table (lane_ops=1) or written
+    into straight-line code generated for the plan, one case per operator (lane_ops=2: the
+    meta-kernel of Section 4 in its own form); workgroups of 512 and of 1024 lanes.  Counting,
+    writing and one-launch kernels, a ragged tail, a second batch, records read in place."""
+    from gpu_harness import expand
+    rng = random.Random(31)
+    long_rec = b"k\t" + bytes(rng.choice(b"abcxyz,0123") for _ in range(70000)) + b"\t1.25,7\tquery text here\n"
+    cases = [(W.get(5, 2500).spec, *W.get(5, 2500).generate()), (W.get(3, 3000).spec, *W.get(3, 3000).generate()),
+             (W.get(1, 700).spec, *W.get(1, 700).generate()), (W.get(4, 500).spec, *W.get(4, 500).generate()),
+             (FRAMING_SPEC, *_cat(FRAMING_RECORDS * 29 + [long_rec]))]
+    for spec, raw, off in cases:
+        raw = np.frombuffer(raw, np.uint8) if isinstance(raw, bytes) else raw
+        n = len(off) - 1
+        want = O.extract(spec, raw, off)
+        plan = B.Plan(spec)
+        for k, v in {"compile": 1, "tile_log2": 6, "lds_budget": 160 * 1024, "tile_threads": threads, "lane_ops": lane_ops}.items():
+            plan.set_option(k, v)
+        d_raw, d_off = to_device(raw, off)
+        res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.2)
+        assert "generic kernel" not in res.note, res.note
+        assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, f"lane_ops={lane_ops} first call")
+        for _ in range(2):
+            ws.fill_(0xB7)
+            plan.set_workspace(ws)
+            res = plan.extract(d_raw, d_off)
+            assert "generic kernel" not in res.note, res.note
+            assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, f"lane_ops={lane_ops} later call")
+        if not res.tile_launches:       # (a plan too wide for tiles of 64 records runs on the walk kernels)
+            plan.close()
+            continue
+        assert plan.compiled()[0] >= 1
+        src = plan.kernel_source(raw.size, n, 1)
+        assert f"#define FBX_LANE_OPS {lane_ops}" in src and f"#define FBX_TILE_THREADS {threads}" in src
+        assert ("lane_hash1(" in src or "lane_bucket1(" in src) == (lane_ops == 2)
+        plan.close()
+
+
 def _random_records(rng, n):
     def field():
         kind = rng.randrange(4)

@@ -118,18 +118,22 @@ def test_tile_kernel_source_compiles_for_a_plan_with_the_run_time_compiler():
             pytest.skip("no run-time compilation library here")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     csrc = os.path.join(root, "paper_2210_07768_amd", "csrc")
-    header = open(os.path.join(csrc, "fbx_device.h")).read()
-    fields = re.findall(r"X\((\w+)\)", header.split("#define FBX_TILE_FIXED_FIELDS(X)")[1].split("\n\n")[0])
-    assert len(fields) >= 30 and "log2T" in fields and "o_prog" in fields
-    # the shape of a two-layer plan on tiles of 32 records (values as the library computes them for
-    # the largest benchmark workload; any consistent set would do for a compile check)
-    shape = dict(n_ops=164, n_layers=2, n_ragged=8, n_rnr=4, n_lists=7, aux_bytes=4096, rnr_words=24, n_mh=4, n_split=4, n_gen=0,
-                 n_fields=100, n_stage=68, log2T=5, raw_cap=32768, row_stride=101, o_off=0, o_rs=528, o_re=656, o_rows=784,
-                 o_raw=7248, o_stage=40064, o_cnt=57472, o_start=58496, o_run=59520, o_base=59552, o_prog=63840,
-                 o_lbeg=74336, o_rnr=74368, o_aux=74464, o_tot=59616, o_ioff=59712, o_ctab=59744, o_cap=59648, o_gfirst=59712,
-                 o_gtot=59712, item_cap=16,
-                 lds_bytes=78560)
-    assert sorted(shape) == sorted(fields), "FBX_TILE_FIXED_FIELDS changed: update the shape used here"
+    # the texts the library itself writes for the largest benchmark workload: the three launch modes
+    # on its usual tiles, and the writing kernel on tiles of 64 records with its single-sign operators
+    # as straight-line code generated for the plan (one case per operator)
+    w = W.get(5)
+    texts = []
+    plan = B.Plan(w.spec)
+    plan.set_option("compile", 1)
+    for mode in (0, 1, 2):
+        texts.append((mode, plan.kernel_source(787 * w.n_records, w.n_records, mode)))
+    assert "P.log2T = 5u;" in texts[0][1] and "#define FBX_LANE_OPS 0" in texts[0][1]
+    for k, v in {"tile_log2": 6, "lds_budget": 160 * 1024, "tile_threads": 1024, "lane_ops": 2}.items():
+        plan.set_option(k, v)
+    texts.append((1, plan.kernel_source(787 * w.n_records, w.n_records, 1)))
+    assert "P.log2T = 6u;" in texts[-1][1] and "#define FBX_TILE_THREADS 1024" in texts[-1][1]
+    assert texts[-1][1].count("lane_hash1(") == 88 and texts[-1][1].count("lane_bucket1(") == 8 and texts[-1][1].count("lane_x11(") == 60
+    plan.close()
     clang_inc = None
     base = os.path.join(os.environ.get("ROCM_PATH", "/opt/rocm"), "lib", "llvm", "lib", "clang")
     for v in sorted(os.listdir(base)) if os.path.isdir(base) else []:
@@ -137,11 +141,8 @@ def test_tile_kernel_source_compiles_for_a_plan_with_the_run_time_compiler():
             clang_inc = os.path.join(base, v, "include")
     if clang_inc is None:
         pytest.skip("the compiler's headers are not installed here")
-    for mode in (0, 1, 2):
-        text = (f"#define FBX_FIXED_MODE {mode}\n#define FBX_FIXED_NAME fbx_tile_fixed_{mode}\n#define FBX_FIXED_ASSIGN "
-                + " ".join(f"P.{k} = {shape[k]}u;" for k in fields)
-                + "\n#define FBX_FIXED_LIST_BEGIN {0u, 88u, 96u, 100u, 100u, 104u, 164u, 164u}"
-                + "\n#define FBX_FIXED_RNR_HEAD {0u, 4u, 0u, 0u}\n#include \"fbx_tile.hip\"\n").encode()
+    for mode, text in texts:
+        text = text.encode()
         prog = ctypes.c_void_p()
         assert rtc.hiprtcCreateProgram(ctypes.byref(prog), text, b"fbx_tile_fixed.hip", 0, None, None) == 0
         opts = [o.encode() for o in ("--offload-arch=gfx950", "-O3", "-std=c++17", "-I" + csrc, "-I" + os.path.join(root, "include"),
