@@ -3,15 +3,23 @@
 
 A step is one fbx_extract call: the whole path (every kernel the call enqueues
 plus its one synchronisation) over one batch of synthetic records that is
-already resident in HBM.  Prints ONE JSON line: records/s, signs/s, the roofline
-of the dominant kernel (HIP-event time on the call's stream, measured live), and
-the CPU oracle timed on a bounded sample of the same workload.
+already resident in HBM.  Two batches of the workload are held in HBM (records
+[0, R) and [R, 2R) of the same generator) and the timed calls alternate between
+them, so that every timed call sizes its ragged arrays from a call on *other*
+records, as a pipeline's calls do.  Prints ONE JSON line: records/s, signs/s,
+the roofline of the dominant kernel (HIP-event time on the call's stream,
+measured live), what the first-call launch sequence costs, how many timed calls
+fell back to it, and the CPU oracle timed on a bounded sample of the same
+workload (all host cores, and one thread).
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -25,32 +33,44 @@ HBM_PEAK_GBPS = 8000.0
 # peak counted in (packed, fused) instructions instead of flops
 VALU_PEAK_PER_S = 256 * 4 * 2.4e9 / 4
 
-# HBM traffic of one launch of the dominant kernel as rocprofv3 counted it (FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a device-to-device copy of known
-# size), for the workloads that were profiled: see profiles/.  Other runs report null.
-MEASURED_TRAFFIC = {
-    # (workload, records, launch sequence, compiled for the plan): bytes per launch; profiles/k_tile_config5_hbm_traffic.md
-    ("config5", 16000000, "one_launch", 1): 42406717805,
-    ("config5", 16000000, "one_launch", 0): 42386037351,
-}
-# Vector instructions (SQ_INSTS_VALU) of one launch of the dominant kernel, same keys;
-# profiles/k_tile_config5_instruction_mix.md
-MEASURED_VALU = {
-    ("config5", 16000000, "one_launch", 1): 7693398336,
-}
-
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_inputs(w, chunk_records=500_000):
-    """Generate the workload chunk by chunk on the host and assemble it in HBM."""
+def source_digest() -> str:
+    """Digest of the kernel and host sources of the library: counter readings in profiles/ name the
+    digest they were taken at and are quoted only while it still matches."""
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2210_07768_amd", "csrc", "*")))
+    for f in files + [os.path.join(ROOT, "include", "fbx.h")]:
+        if os.path.isfile(f):
+            h.update(os.path.basename(f).encode() + b"\0" + open(f, "rb").read() + b"\0")
+    return h.hexdigest()[:16]
+
+
+def measured_counters(workload, records, launch, compile_for_plan):
+    """Counter readings of the dominant kernel for this configuration from the summaries in
+    profiles/ (lines that start with 'bench-key:'), or {} when none was taken at these sources."""
+    want = {"workload": workload, "records": str(records), "launch": launch, "compile": str(compile_for_plan),
+            "sources": source_digest()}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for line in open(path):
+            if not line.startswith("bench-key:"):
+                continue
+            kv = dict(item.split("=", 1) for item in line[len("bench-key:"):].split())
+            if all(kv.get(k) == v for k, v in want.items()):
+                return {k: int(v) for k, v in kv.items() if k not in want}
+    return {}
+
+
+def build_inputs(w, first_record=0, chunk_records=500_000, tag=""):
+    """Generate records [first_record, first_record + n) chunk by chunk on the host and assemble them in HBM."""
     import numpy as np
     import torch
 
     n = w.n_records
-    probe, _ = w.generate(0, min(n, 2048))
+    probe, _ = w.generate(first_record, min(n, 2048))
     est = int(probe.size / min(n, 2048) * n * 1.03) + (1 << 20)
     d_raw = torch.empty(est, dtype=torch.uint8, device="cuda")
     d_off = torch.empty(n + 1, dtype=torch.int64, device="cuda")
@@ -58,7 +78,7 @@ def build_inputs(w, chunk_records=500_000):
     t0 = time.time()
     while r < n:
         m = min(chunk_records, n - r)
-        raw, off = w.generate(r, m)
+        raw, off = w.generate(first_record + r, m)
         if pos + raw.size > d_raw.numel():
             grown = torch.empty(int((pos + raw.size) * 1.1), dtype=torch.uint8, device="cuda")
             grown[:pos].copy_(d_raw[:pos])
@@ -67,29 +87,46 @@ def build_inputs(w, chunk_records=500_000):
         d_off[r:r + m].copy_(torch.from_numpy((off[:-1] + np.uint64(pos)).astype(np.int64)))
         pos += raw.size
         r += m
-        log(f"[bench] generated {r}/{n} records, {pos / 1e9:.2f} GB, {time.time() - t0:.0f}s")
+        if r == n or (r // chunk_records) % 8 == 0:
+            log(f"[bench] batch {tag}: generated {r}/{n} records, {pos / 1e9:.2f} GB, {time.time() - t0:.0f}s")
     d_off[n:].fill_(pos)
     torch.cuda.synchronize()
     return d_raw[:pos], d_off
 
 
-def cpu_baseline(w, budget_s=12.0):
-    """The oracle as it stands, single-threaded, on the first records of the workload."""
+def cpu_baseline(w, budget_s=10.0):
+    """The oracle as it stands on the first records of the workload: over disjoint record ranges on
+    all host cores (the figure reported as `value`), and in one thread."""
+    from concurrent.futures import ThreadPoolExecutor
+
     from oracle import fbx_oracle as O
+    from oracle import ranges
 
     n = min(256, w.n_records)
     raw, off = w.generate(0, n)
     t = time.time()
     O.extract(w.spec, raw, off)
     dt = max(time.time() - t, 1e-4)
-    m = int(min(w.n_records, max(n, n * budget_s / dt)))
-    raw, off = w.generate(0, m)
+    m1 = int(min(w.n_records, max(n, n * budget_s / dt)))
+    raw, off = w.generate(0, m1)
     t = time.time()
     res = O.extract(w.spec, raw, off)
-    dt = time.time() - t
-    return {"value": m / dt, "unit": "records/s", "cores": 1, "kind": "oracle",
-            "signs_per_s": res.n_values_total / dt,
-            "sample": f"first {m} records of {w.name} ({raw.size / 1e6:.1f} MB), {dt:.1f} s, single thread"}
+    dt1 = time.time() - t
+    cores = ranges.host_workers()
+    mc = int(min(w.n_records, m1 * cores))
+    if mc > m1:
+        raw, off = w.generate(0, mc)
+    t = time.time()
+    with ThreadPoolExecutor(cores) as pool:
+        parts = ranges.extract_ranges(w.spec, raw, off, pool, cores * 4)
+    dtc = time.time() - t
+    signs_c = sum(p.n_values_total for _, _, p in parts)
+    return {"value": mc / dtc, "unit": "records/s", "cores": cores, "kind": "oracle",
+            "signs_per_s": signs_c / dtc,
+            "sample": f"first {mc} records of {w.name} ({raw.size / 1e6:.1f} MB), {dtc:.1f} s on {cores} threads "
+                      f"(the single-threaded oracle over disjoint record ranges)",
+            "single_thread": {"value": m1 / dt1, "unit": "records/s", "cores": 1, "signs_per_s": res.n_values_total / dt1,
+                              "sample": f"first {m1} records, {dt1:.1f} s"}}
 
 
 def main():
@@ -106,11 +143,18 @@ def main():
                          "(plan option compile, default); 0: the generic kernel")
     ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
                     help="extra plan option (tuning), e.g. --opt tile_log2=4")
+    ap.add_argument("--one-batch", action="store_true",
+                    help="time every call on the batch the sizes were learned on (what profiles of one kernel use)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a device-to-device copy of this many MiB (3 times) and exit: the known "
                          "traffic against which FETCH_SIZE / WRITE_SIZE readings of rocprofv3 are scaled")
+    ap.add_argument("--print-source-digest", action="store_true",
+                    help="print the digest of the library's sources that counter summaries in profiles/ are keyed on")
     args = ap.parse_args()
+    if args.print_source_digest:
+        print(source_digest())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (records are independent: a batch shards by record range); use --gpus 1")
 
@@ -131,9 +175,11 @@ def main():
         return
     B.lib()  # fails loudly when libfbx.so is missing
     w = W.get(args.config, args.records)
-    log(f"[bench] workload {w.name}: {w.n_records} records x {w.n_fields} fields, {w.n_ops} ops, {w.n_layers} layers")
-    d_raw, d_off = build_inputs(w)
-    raw_len, R = d_raw.numel(), w.n_records
+    R = w.n_records
+    log(f"[bench] workload {w.name}: {R} records x {w.n_fields} fields, {w.n_ops} ops, {w.n_layers} layers")
+    batches = [build_inputs(w, 0, tag="A")]
+    if not args.one_batch:
+        batches.append(build_inputs(w, R, tag="B"))
 
     plan = B.Plan(w.spec)
     plan.set_option("profile", 1)
@@ -144,36 +190,68 @@ def main():
     for kv in args.opt:
         k, v = kv.split("=")
         plan.set_option(k, int(v))
-    res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.03)  # a few percent of headroom, as a serving loop would keep
+    # the first call sizes the workspace (a few percent of headroom, as a serving loop would keep; both batches must fit)
+    res, ws = B.extract_with_retry(plan, *batches[0], slack=1.05)
     log(f"[bench] workspace {ws.numel() / 1e9:.2f} GB, {res.n_values_total} signs, "
         f"{len(res.slot_ids)} slots, malformed {res.n_malformed_numeric}")
 
     notes = [res.note] if res.note else []
-    for _ in range(args.warmup):
-        r = plan.extract(d_raw, d_off)
+    for i in range(max(args.warmup, 1 if len(batches) > 1 else 0)):
+        r = plan.extract(*batches[(i + 1) % len(batches)])
         if r.note:
             notes.append(r.note)
     torch.cuda.synchronize()
     n_compiled, compile_ms = plan.compiled()
     if args.compile:
         log(f"[bench] {n_compiled} tile kernels compiled for the plan in {compile_ms / 1e3:.1f} s (before the timed calls)")
-    kernel_ms = {}
+
+    # what a call costs that cannot use the sizes of the call before it (a plan's first call, or a
+    # batch that outgrows its arrays): counting launch, scan, writing launch, with compiled kernels
+    cold = None
+    if res.tile_launches and args.fused:
+        plan.set_option("one_launch", 0)
+        t0 = time.perf_counter()
+        rc = plan.extract(*batches[0])
+        torch.cuda.synchronize()
+        cold = {"ms": (time.perf_counter() - t0) * 1e3, "tile_launches": rc.tile_launches, "kernel_ms": {}}
+        for which, name in ((1, "count"), (2, "scan"), (3, "alloc"), (101, "tile")):
+            try:
+                cold["kernel_ms"][name] = round(plan.kernel_ms(which), 4)
+            except B.FbxError:
+                pass
+        plan.set_option("one_launch", 1)
+        for kv in args.opt:  # (an explicit one_launch=0 on the command line stays)
+            k, v = kv.split("=")
+            if k == "one_launch":
+                plan.set_option(k, int(v))
+
+    kernel_ms, step_ms, step_bytes, fell_back = {}, [], [], 0
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    first_timed = len(batches) - 1   # (the cold call above ran on batch A: the first timed call takes the other one)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        d_raw, d_off = batches[(first_timed + i) % len(batches)]
+        events[i][0].record()
         res = plan.extract(d_raw, d_off)
+        events[i][1].record()
         for which in [0, 1, 2, 3] + [101 + k for k in range(1 if args.fused else w.n_layers)]:
             try:
                 kernel_ms.setdefault(which, []).append(plan.kernel_ms(which))
             except B.FbxError:
                 pass
+        n_ragged_emitted = sum(1 for s in res.slot_ids if res.slots[s].offsets is not None)
+        step_bytes.append(d_raw.numel() + 8 * (R + 1) + 8 * res.n_values_total + 8 * (R + 1) * n_ragged_emitted)
+        fell_back += 1 if (res.tile_launches == 2 and "fell back" in res.note) else 0
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     # reading the event times sits inside the timed loop: a few microseconds per step
+    step_ms = [a.elapsed_time(b) for a, b in events]
 
     ms_per_step = elapsed / args.steps * 1e3
     n_signs = res.n_values_total
-    n_ragged_emitted = sum(1 for s in res.slot_ids if res.slots[s].offsets is not None)
-    alg_bytes = raw_len + 8 * (R + 1) + 8 * n_signs + 8 * (R + 1) * n_ragged_emitted
+    alg_bytes = float(np.mean(step_bytes))
+    raw_len = batches[(first_timed + args.steps - 1) % len(batches)][0].numel()
 
     # algorithmic bytes per tile-kernel launch: each input read once, each output written once,
     # intermediates and re-reads count zero
@@ -211,31 +289,37 @@ def main():
     if compiled_now and res.tile_launches and "generic kernel" not in " ".join(notes + [res.note]):
         kname = f"fbx_tile_fixed_{kname[-2]} ({kname} compiled for the plan)"
 
+    counters = measured_counters(w.name, R, launch, args.compile)
+    traffic = counters["fetch_bytes"] + counters["write_bytes"] if "fetch_bytes" in counters and "write_bytes" in counters else None
     out = {
         "metric": "records/s", "value": R / (ms_per_step * 1e-3), "unit": "records/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": w.name, "records": R, "fields": w.n_fields, "ops": w.n_ops, "layers": w.n_layers,
-                   "raw_bytes": raw_len, "signs": int(n_signs), "launch": launch, "compile": args.compile},
+                   "raw_bytes": raw_len, "signs": int(n_signs), "launch": launch, "compile": args.compile,
+                   "batches": ("one batch, every call on the records its sizes were learned on" if len(batches) == 1 else
+                               f"two batches of {R} records alternate: every timed call sizes its ragged arrays from a call on other records")},
+        "ms_per_step_median_hip_events": statistics.median(step_ms),
         "signs_per_s": n_signs / (ms_per_step * 1e-3),
         "path_algorithmic_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "path_frac_of_hbm_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernel_ms": kernels,
+        "timed_calls_that_fell_back": fell_back,
+        "first_call_sequence": cold,
         "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get((w.name, R, launch, args.compile)),
+                     "traffic": traffic,
                      "algorithmic_bytes_per_launch": int(launches[dom]), "avg_launch_ms": dom_ms},
     }
-    valu = MEASURED_VALU.get((w.name, R, launch, args.compile))
-    if valu:
+    if "valu" in counters:
         # what actually bounds the kernel: vector instruction issue.  The count per launch is the
-        # profiled one, the duration this run's.
-        rate = valu / (dom_ms * 1e-3)
+        # profiled one (same sources, same configuration), the duration this run's.
+        rate = counters["valu"] / (dom_ms * 1e-3)
         out["roofline_alu"] = {"bound": "alu", "kernel": kname, "achieved": rate, "peak": VALU_PEAK_PER_S,
                                "unit": "wavefront vector instructions/s", "frac": rate / VALU_PEAK_PER_S,
-                               "valu_instructions_per_launch": valu, "per_record": valu / R}
+                               "valu_instructions_per_launch": counters["valu"], "per_record": counters["valu"] / R}
     if args.compile:
         # host time spent compiling, all of it before the timed calls unless compiled_in_timed_calls says otherwise
         out["compile"] = {"kernels": compiled_now, "ms": round(plan.compiled()[1], 1),
