@@ -149,6 +149,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a device-to-device copy of this many MiB (3 times) and exit: the known "
                          "traffic against which FETCH_SIZE / WRITE_SIZE readings of rocprofv3 are scaled")
+    ap.add_argument("--launch-overhead", action="store_true",
+                    help="only measure what Table 1 of the paper measures, on this device, and exit: 1 / 10 / 100 / "
+                         "1,000 / 10,000 back-to-back launches of an empty kernel with five pointer arguments")
     ap.add_argument("--print-source-digest", action="store_true",
                     help="print the digest of the library's sources that counter summaries in profiles/ are keyed on")
     args = ap.parse_args()
@@ -174,6 +177,16 @@ def main():
         print(json.dumps({"copy_bytes_read": src.numel(), "copy_bytes_written": src.numel(), "copies": 3}))
         return
     B.lib()  # fails loudly when libfbx.so is missing
+    if args.launch_overhead:
+        st = torch.cuda.current_stream().cuda_stream
+        B.launch_overhead(100, st)   # (the first launch of a kernel loads its code)
+        table = {}
+        for n in (1, 10, 100, 1000, 10000):
+            runs = sorted(B.launch_overhead(n, st) for _ in range(7))
+            table[str(n)] = {"median_us": round(runs[3], 2), "min_us": round(runs[0], 2), "per_launch_us": round(runs[3] / n, 3)}
+        print(json.dumps({"empty_kernel_launches": table, "arguments": "five pointers", "timed": "host clock, first launch call to end of stream wait",
+                          "paper_table_1_us_on_V100": {"1": 4, "10": 35, "100": 360, "1000": 3619, "10000": 34515}}))
+        return
     w = W.get(args.config, args.records)
     R = w.n_records
     log(f"[bench] workload {w.name}: {R} records x {w.n_fields} fields, {w.n_ops} ops, {w.n_layers} layers")

@@ -183,6 +183,9 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
  * Tuning knobs, all optional.  Keys:
  *   "fused"        1: all layers in one launch (tile kernel, default); 0: one launch per
  *                  layer (walk kernels)
+ *   "tile_engine"  1: with "fused" = 1 the tile kernel runs wherever a plan fits it (default); 0: the
+ *                  walk kernels run all layers in one launch (the same code that "fused" = 0
+ *                  launches once per layer, which makes the two comparable)
  *   "one_launch"   1: later calls skip the counting launch as described at fbx_extract
  *                  (default); 0: always count first
  *   "tile_log2"    -1: records per tile chosen per call (default); 0..6: 2^value records
@@ -262,6 +265,15 @@ fbx_status fbx_plan_kernel_ms(const fbx_plan* plan, uint32_t which, float* ms);
 fbx_status fbx_arena_alloc(uint64_t* d_head, const uint64_t* d_sizes, uint64_t n, uint64_t* d_offsets,
                            uint32_t block_threads, void* hip_stream);
 fbx_status fbx_arena_reset(uint64_t* d_head, uint64_t value, void* hip_stream);
+
+/*
+ * The measurement behind Table 1 of the paper (Section 4, "Inner-GPU operator launching"), on this
+ * device: n_launches launches of an empty kernel with five pointer arguments are enqueued on
+ * hip_stream back to back and waited for; *microseconds (HOST) receives the host time from the
+ * first launch call to the end of the wait.  The stream is drained before the clock starts.
+ * Errors: FBX_E_ARG (0 or more than 10^6 launches, NULL), FBX_E_HIP.
+ */
+fbx_status fbx_launch_overhead(uint32_t n_launches, void* hip_stream, double* microseconds);
 
 #ifdef __cplusplus
 }

@@ -21,6 +21,7 @@ EXPORTS = [
     "fbx_extract", "fbx_last_error", "fbx_status_str", "fbx_plan_info", "fbx_plan_set_option",
     "fbx_plan_kernel_ms", "fbx_plan_compiled", "fbx_arena_alloc", "fbx_arena_reset",
     "fbx_extract_static", "fbx_static_scratch_bytes", "fbx_plan_kernel_source",
+    "fbx_launch_overhead",
 ]
 
 
@@ -76,6 +77,8 @@ def lib():
         L.fbx_plan_kernel_source.restype = ctypes.c_int
         L.fbx_plan_kernel_source.argtypes = [vp, u64, u64, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t,
                                              ctypes.POINTER(ctypes.c_size_t)]
+        L.fbx_launch_overhead.restype = ctypes.c_int
+        L.fbx_launch_overhead.argtypes = [u32, vp, ctypes.POINTER(ctypes.c_double)]
         L.fbx_last_error.restype = ctypes.c_char_p
         L.fbx_last_error.argtypes = [vp]
         L.fbx_status_str.restype = ctypes.c_char_p
@@ -297,3 +300,12 @@ def arena_reset(d_head, value: int, stream: int = 0):
     st = lib().fbx_arena_reset(d_head.data_ptr(), value, stream)
     if st != OK:
         raise FbxError(st, lib().fbx_status_str(st).decode())
+
+
+def launch_overhead(n_launches: int, stream: int = 0) -> float:
+    """Microseconds for n_launches back-to-back launches of an empty kernel with five pointer arguments."""
+    us = ctypes.c_double()
+    st = lib().fbx_launch_overhead(n_launches, stream, ctypes.byref(us))
+    if st != OK:
+        raise FbxError(st, lib().fbx_status_str(st).decode())
+    return us.value

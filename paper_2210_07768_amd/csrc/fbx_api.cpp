@@ -2,6 +2,7 @@
 // one extraction call.  See include/fbx.h for the contract of every entry point.
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -42,6 +43,7 @@ struct fbx_plan {
 
   // options
   int fused = 1;
+  int tile_engine = 1;            // 0: the walk kernels also when all layers share a launch
   uint32_t lds_pad = 0;
   int profile = 0;
   int tile_log2 = -1;             // -1: chosen per call
@@ -202,7 +204,7 @@ bool tile_geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records, Tile
 
 CallGeometry geometry(const fbx_plan& p, uint64_t raw_len, uint64_t n_records) {
   CallGeometry g;
-  g.tile_engine = p.fused && tile_geometry(p, raw_len, n_records, g.tp);
+  g.tile_engine = p.fused && p.tile_engine && tile_geometry(p, raw_len, n_records, g.tp);
   if (g.tile_engine) {
     g.n_tiles = static_cast<uint32_t>((n_records + (1ull << g.tp.log2T) - 1) >> g.tp.log2T);
   } else {
@@ -326,6 +328,9 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   if (k == "fused") {
     if (value != 0 && value != 1) { plan->error = "fused must be 0 or 1"; return FBX_E_ARG; }
     plan->fused = static_cast<int>(value);
+  } else if (k == "tile_engine") {
+    if (value != 0 && value != 1) { plan->error = "tile_engine must be 0 or 1"; return FBX_E_ARG; }
+    plan->tile_engine = static_cast<int>(value);
   } else if (k == "lds_pad") {
     if (value < 0 || value > 65536) { plan->error = "lds_pad must be in 0..65536"; return FBX_E_ARG; }
     plan->lds_pad = static_cast<uint32_t>(value);
@@ -858,6 +863,19 @@ fbx_status fbx_arena_alloc(uint64_t* d_head, const uint64_t* d_sizes, uint64_t n
     return FBX_E_ARG;
   hipError_t e = launch_arena_alloc(d_head, d_sizes, n, d_offsets, block_threads, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? FBX_OK : FBX_E_HIP;
+}
+
+fbx_status fbx_launch_overhead(uint32_t n_launches, void* hip_stream, double* microseconds) {
+  if (!microseconds || n_launches == 0 || n_launches > 1000000u) return FBX_E_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return FBX_E_HIP; }
+  const auto t0 = std::chrono::steady_clock::now();
+  hipError_t e = launch_empty(n_launches, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  const auto t1 = std::chrono::steady_clock::now();
+  if (e != hipSuccess) { (void)hipGetLastError(); return FBX_E_HIP; }
+  *microseconds = std::chrono::duration<double, std::micro>(t1 - t0).count();
+  return FBX_OK;
 }
 
 fbx_status fbx_arena_reset(uint64_t* d_head, uint64_t value, void* hip_stream) {

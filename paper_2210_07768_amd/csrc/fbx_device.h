@@ -150,6 +150,7 @@ hipError_t launch_programs(const WalkParams& P, hipStream_t st);
 hipError_t launch_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets, uint32_t threads,
                               hipStream_t st);
 hipError_t launch_arena_reset(uint64_t* head, uint64_t value, hipStream_t st);
+hipError_t launch_empty(uint32_t n, hipStream_t st);  // n launches of an empty kernel with five pointer arguments
 #endif  // __HIPCC_RTC__
 
 }  // namespace fbx

@@ -282,6 +282,18 @@ __global__ void k_fill64(uint64_t* p, uint64_t n, uint64_t value) {
   for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) p[i] = value;
 }
 
+// An empty kernel with five pointer arguments: what Table 1 of the paper launches to measure the
+// launch overhead that motivates one meta-kernel per layer (Section 4).
+__global__ void k_empty(const void*, const void*, const void*, const void*, void*) {}
+
+hipError_t launch_empty(uint32_t n, hipStream_t st) {
+  for (uint32_t i = 0; i < n; ++i) {
+    hipLaunchKernelGGL(k_empty, dim3(1), dim3(64), 0, st, (const void*)nullptr, (const void*)nullptr, (const void*)nullptr,
+                       (const void*)nullptr, (void*)nullptr);
+  }
+  return hipGetLastError();
+}
+
 // ----------------------------------------------------------- launch wrappers
 hipError_t launch_reset(Ctrl* ctrl, uint64_t arena_base, hipStream_t st) {
   hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctrl, arena_base);
