@@ -250,8 +250,10 @@ fbx_status fbx_plan_kernel_ms(const fbx_plan* plan, uint32_t which, float* ms);
 /*
  * In-kernel dynamic allocation as a primitive (Section 5, Algorithm 1 and
  * "Reset GPU memory pool").  fbx_arena_alloc launches ceil(n / block_threads)
- * workgroups; in each, thread i asks for d_sizes[i] bytes: the workgroup takes a
- * prefix sum of its sizes, ONE thread adds the workgroup total (rounded up to
+ * workgroups that call the library's device-side allocator (the one its own kernels
+ * call, see fbx_extract_unordered); in each, thread i asks for d_sizes[i] bytes: the
+ * workgroup takes a prefix sum of its sizes (inside a wavefront by data-parallel moves,
+ * across wavefronts through LDS), ONE thread adds the workgroup total (rounded up to
  * 128 bytes) to *d_head with an atomic add, and thread i gets
  * old_head + (sum of the sizes of the threads before it).  Workgroups land in
  * arrival order, so offsets are only unique, not ordered, across workgroups.
@@ -265,6 +267,39 @@ fbx_status fbx_plan_kernel_ms(const fbx_plan* plan, uint32_t which, float* ms);
 fbx_status fbx_arena_alloc(uint64_t* d_head, const uint64_t* d_sizes, uint64_t n, uint64_t* d_offsets,
                            uint32_t block_threads, void* hip_stream);
 fbx_status fbx_arena_reset(uint64_t* d_head, uint64_t value, void* hip_stream);
+
+/*
+ * fbx_extract_unordered — one operator of layer 1 whose lists vary in length (a multi-valued
+ * hash or bucket, a filter, an n-gram), run the way Section 5 and Figure 5 describe: one record
+ * per thread; a thread works out how many signs its record yields, the workgroup allocates with
+ * Algorithm 1 (a prefix sum and ONE atomic add on the pool's head per workgroup of 256 threads,
+ * workgroup regions 128-byte aligned), the thread writes its signs into its region and records
+ * where that is.  No counting launch and no scan; in exchange the output is unordered: the
+ * regions of one workgroup lie end to end in record order, workgroups in arrival order.
+ *   slot_id          : an emitted slot of the plan (operator of layer 1 with ragged output)
+ *   d_raw, d_rec_off : as for fbx_extract
+ *   d_pool           : DEVICE, 128-byte aligned, pool_bytes bytes: the pre-allocated pool
+ *   d_state          : DEVICE, four u64 owned by the caller: [0] the pool's idle-memory head
+ *                      (bytes from d_pool), [1..3] used by the call
+ *   reset            : 1: the head is set back to the pool's base first (the constant-time release of
+ *                      Section 5, "Reset GPU memory pool"); 0: allocate behind what earlier calls took
+ *   d_thread_offsets : DEVICE, n_records u64 out: byte offset of record i's signs from d_pool
+ *                      (the "Thread Offsets" of Figure 5)
+ *   d_lengths        : DEVICE, n_records u32 out: signs of record i (token order inside)
+ *   out              : HOST: signs in all, malformed numerics, the head after the call
+ * Needs fbx_plan_set_workspace (the operator's boundaries or prefix are read from the plan's
+ * tables there); touches nothing else in the workspace.  Synchronises the stream once.
+ * Errors: FBX_E_ARG, FBX_E_INPUT, FBX_E_HIP, and FBX_E_NOMEM when the pool is exhausted: nothing
+ * is written beyond it and out->pool_head holds the bytes that would have sufficed.
+ */
+typedef struct {
+  uint64_t n_values, n_malformed_numeric, pool_head;
+} fbx_unordered_result;
+fbx_status fbx_extract_unordered(fbx_plan* plan, uint32_t slot_id, const uint8_t* d_raw, uint64_t raw_len,
+                                 const uint64_t* d_rec_off, uint64_t n_records, void* d_pool,
+                                 uint64_t pool_bytes, uint64_t* d_state, int reset,
+                                 uint64_t* d_thread_offsets, uint32_t* d_lengths, void* hip_stream,
+                                 fbx_unordered_result* out);
 
 /*
  * The measurement behind Table 1 of the paper (Section 4, "Inner-GPU operator launching"), on this

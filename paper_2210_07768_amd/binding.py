@@ -21,7 +21,7 @@ EXPORTS = [
     "fbx_extract", "fbx_last_error", "fbx_status_str", "fbx_plan_info", "fbx_plan_set_option",
     "fbx_plan_kernel_ms", "fbx_plan_compiled", "fbx_arena_alloc", "fbx_arena_reset",
     "fbx_extract_static", "fbx_static_scratch_bytes", "fbx_plan_kernel_source",
-    "fbx_launch_overhead",
+    "fbx_launch_overhead", "fbx_extract_unordered",
 ]
 
 
@@ -43,6 +43,10 @@ class Result(ctypes.Structure):
                 ("n_slots", ctypes.c_uint32), ("n_layers", ctypes.c_uint32),
                 ("slots", ctypes.POINTER(SlotView)),
                 ("tile_launches", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+class UnorderedResult(ctypes.Structure):
+    _fields_ = [("n_values", ctypes.c_uint64), ("n_malformed_numeric", ctypes.c_uint64), ("pool_head", ctypes.c_uint64)]
 
 
 _lib = None
@@ -77,6 +81,9 @@ def lib():
         L.fbx_plan_kernel_source.restype = ctypes.c_int
         L.fbx_plan_kernel_source.argtypes = [vp, u64, u64, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t,
                                              ctypes.POINTER(ctypes.c_size_t)]
+        L.fbx_extract_unordered.restype = ctypes.c_int
+        L.fbx_extract_unordered.argtypes = [vp, u32, vp, u64, vp, u64, vp, u64, vp, ctypes.c_int, vp, vp, vp,
+                                            ctypes.POINTER(UnorderedResult)]
         L.fbx_launch_overhead.restype = ctypes.c_int
         L.fbx_launch_overhead.argtypes = [u32, vp, ctypes.POINTER(ctypes.c_double)]
         L.fbx_last_error.restype = ctypes.c_char_p
@@ -226,6 +233,25 @@ class Plan:
         ms = ctypes.c_float()
         self._check(lib().fbx_plan_kernel_ms(self._h, which, ctypes.byref(ms)))
         return ms.value
+
+    def extract_unordered(self, slot_id: int, d_raw, d_rec_off, pool, state, thread_offsets, lengths, reset: bool = True,
+                          stream: Optional[int] = None) -> UnorderedResult:
+        """fbx_extract_unordered: pool (uint8), state (4 x int64), thread_offsets (int64, one per record) and
+        lengths (int32, one per record) are CUDA tensors owned by the caller."""
+        import torch
+
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        res = UnorderedResult()
+        st = lib().fbx_extract_unordered(self._h, slot_id, d_raw.data_ptr() if d_raw.numel() else 0, d_raw.numel(),
+                                         d_rec_off.data_ptr(), d_rec_off.numel() - 1, pool.data_ptr(), pool.numel(),
+                                         state.data_ptr(), 1 if reset else 0, thread_offsets.data_ptr(), lengths.data_ptr(),
+                                         stream, ctypes.byref(res))
+        if st != OK:
+            err = FbxError(st, lib().fbx_last_error(self._h).decode())
+            err.required_bytes = res.pool_head if st == E_NOMEM else 0
+            raise err
+        return res
 
     def extract_raw(self, raw_ptr: int, raw_len: int, off_ptr: int, n_records: int, stream: int = 0) -> Result:
         res = Result()

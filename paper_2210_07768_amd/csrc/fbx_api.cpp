@@ -865,6 +865,63 @@ fbx_status fbx_arena_alloc(uint64_t* d_head, const uint64_t* d_sizes, uint64_t n
   return e == hipSuccess ? FBX_OK : FBX_E_HIP;
 }
 
+fbx_status fbx_extract_unordered(fbx_plan* plan, uint32_t slot_id, const uint8_t* d_raw, uint64_t raw_len,
+                                 const uint64_t* d_rec_off, uint64_t n_records, void* d_pool, uint64_t pool_bytes,
+                                 uint64_t* d_state, int reset, uint64_t* d_thread_offsets, uint32_t* d_lengths,
+                                 void* hip_stream, fbx_unordered_result* out) {
+  if (!plan || !out || !d_rec_off || (!d_raw && raw_len) || !d_state || (n_records && (!d_thread_offsets || !d_lengths)) ||
+      (!d_pool && pool_bytes)) {
+    if (plan) plan->error = "NULL argument";
+    return FBX_E_ARG;
+  }
+  if (!plan->ws) { plan->error = "no workspace set (the plan's tables are read from it)"; return FBX_E_ARG; }
+  if ((reinterpret_cast<uintptr_t>(d_pool) & 127u) || n_records >= (1ull << 32)) {
+    plan->error = "the pool must be 128-byte aligned and a call takes fewer than 2^32 records";
+    return FBX_E_ARG;
+  }
+  const HostOp* found = nullptr;
+  for (const HostOp& op : plan->host.ops)
+    if ((op.d.flags & F_EMIT) && op.slot == slot_id) found = &op;
+  if (!found || found->d.layer != 1 || found->d.arity != 0) {
+    plan->error = "slot " + std::to_string(slot_id) + " is not an emitted operator of layer 1 with lists of varying length";
+    return FBX_E_ARG;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  UnorderedParams U{};
+  U.raw = d_raw; U.raw_len = raw_len; U.rec_off = d_rec_off; U.n_records = n_records;
+  const OpDesc& d = found->d;
+  U.op.kind = d.kind; U.op.flags = d.flags; U.op.arity = 0; U.op.rag_row = 0;
+  U.op.aux_off = d.aux_off; U.op.aux_len = d.aux_len; U.op.a = U.op.b = 0;
+  U.op.key = d.key; U.op.values = U.op.offsets = 0; U.op.field = d.field; U.op.stage = 0xffffffffu;
+  U.aux = plan->ws + plan->off_aux;
+  U.pool = static_cast<uint8_t*>(d_pool); U.pool_bytes = pool_bytes;
+  U.state = d_state; U.thread_off = d_thread_offsets; U.lengths = d_lengths;
+  hipError_t e;
+  // the counters always start from zero; the head only when asked to (Section 5, "Reset GPU memory pool":
+  // one store releases everything; without it this call allocates behind the calls before it)
+  if (reset) e = launch_fill64(d_state, 4, 0, st);
+  else e = launch_fill64(d_state + 1, 3, 0, st);
+  if (e != hipSuccess) return hip_fail(plan, e, "resetting the pool's state");
+  e = launch_unordered(U, st);
+  if (e != hipSuccess) return hip_fail(plan, e, "kernel with in-kernel allocation");
+  uint64_t state[4] = {0, 0, 0, 0};
+  e = hipMemcpyAsync(state, d_state, sizeof state, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return hip_fail(plan, e, "read-back");
+  out->n_values = state[2];
+  out->n_malformed_numeric = state[3];
+  out->pool_head = state[0];
+  if (state[1] & CE_OFFSETS) { plan->error = "record offsets must be non-decreasing and end within raw_len"; return FBX_E_INPUT; }
+  if (state[1] & CE_TILE) { plan->error = "a record spans 2 GiB or more"; return FBX_E_INPUT; }
+  if (state[1] & CE_OVERFLOW) { plan->error = "an operator produces 2^26 or more signs for one record"; return FBX_E_INPUT; }
+  if (state[1] & CE_NOMEM) {
+    plan->error = "pool too small: " + std::to_string(state[0]) + " bytes would have sufficed";
+    return FBX_E_NOMEM;
+  }
+  plan->error.clear();
+  return FBX_OK;
+}
+
 fbx_status fbx_launch_overhead(uint32_t n_launches, void* hip_stream, double* microseconds) {
   if (!microseconds || n_launches == 0 || n_launches > 1000000u) return FBX_E_ARG;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);

@@ -83,6 +83,21 @@ struct TileParams {
   uint32_t dbg;    // phases to leave out (tuning builds only; results are then wrong)
 };
 
+// One ragged root operator over a batch, allocating in the kernel (k_unordered).
+struct UnorderedParams {
+  const uint8_t* raw;
+  uint64_t raw_len;
+  const uint64_t* rec_off;
+  uint64_t n_records;
+  OpProg op;              // kind, flags, field, key, aux_off, aux_len are read
+  const uint8_t* aux;     // the plan's table of bucket boundaries and prefixes
+  uint8_t* pool;
+  uint64_t pool_bytes;
+  uint64_t* state;        // [4]: idle-memory head (bytes from the pool's base), error bits, signs, malformed numerics
+  uint64_t* thread_off;   // [n_records] byte offset of a record's signs from the pool's base
+  uint32_t* lengths;      // [n_records] signs of a record
+};
+
 // The fields of TileParams that the plan and the tile size fix (all but addresses, sizes of
 // the batch and tuning switches): a kernel compiled for one plan has them as literals.
 #define FBX_TILE_FIXED_FIELDS(X)                                                                                     \
@@ -150,6 +165,7 @@ hipError_t launch_programs(const WalkParams& P, hipStream_t st);
 hipError_t launch_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets, uint32_t threads,
                               hipStream_t st);
 hipError_t launch_arena_reset(uint64_t* head, uint64_t value, hipStream_t st);
+hipError_t launch_unordered(const UnorderedParams& U, hipStream_t st);
 hipError_t launch_empty(uint32_t n, hipStream_t st);  // n launches of an empty kernel with five pointer arguments
 #endif  // __HIPCC_RTC__
 

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 
+#include "fbx_arena.h"
 #include "fbx_device.h"
 
 namespace fbx {
@@ -103,45 +104,14 @@ __global__ __launch_bounds__(kBlock) void k_scan(const uint32_t* tile_cnt, uint6
 }
 
 // ------------------------------------------------------------------- arena
-__device__ __forceinline__ uint64_t round128(uint64_t x) { return (x + 127ull) & ~127ull; }
-
-// Algorithm 1 of the paper (Section 5): every thread of the block brings a
-// size; the block takes a prefix sum, ONE thread adds the block's total to the
-// idle-memory head with an atomic add, and every thread's offset is the old
-// head plus the sizes of the threads before it.  (The listing subtracts the
-// first thread's prefix, which is only right for equal sizes; the prose and
-// the figure call for the exclusive prefix, which is what is computed here.)
-// The block total is rounded up to 128 bytes so that every block starts on a
-// 128-byte line, as the paper asks.  s_scan must hold blockDim.x entries.
-__device__ uint64_t arena_alloc_block(uint64_t* head, uint64_t size, uint64_t* s_scan, uint64_t* s_addr) {
-  const uint32_t tid = threadIdx.x, n = blockDim.x;
-  s_scan[tid] = size;
-  __syncthreads();
-  for (uint32_t d = 1; d < n; d <<= 1) {
-    uint64_t t = tid >= d ? s_scan[tid - d] : 0;
-    __syncthreads();
-    s_scan[tid] += t;
-    __syncthreads();
-  }
-  const uint64_t incl = s_scan[tid];
-  if (tid == 0) {
-    const uint64_t total = round128(s_scan[n - 1]);
-    *s_addr = total ? atomicAdd(reinterpret_cast<unsigned long long*>(head), (unsigned long long)total)
-                    : *reinterpret_cast<volatile uint64_t*>(head);
-  }
-  __syncthreads();
-  const uint64_t out = *s_addr + incl - size;
-  __syncthreads();
-  return out;
-}
+// (Algorithm 1 itself, arena_alloc_wg, lives in fbx_arena.h: any kernel can call it)
+__device__ __forceinline__ uint64_t round128(uint64_t x) { return arena_round128(x); }
 
 __global__ void k_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n, uint64_t* offsets) {
-  extern __shared__ __align__(16) uint8_t dyn_smem[];
-  uint64_t* s_scan = reinterpret_cast<uint64_t*>(dyn_smem);
-  __shared__ uint64_t s_addr;
+  __shared__ uint64_t s_part[1024 / 64 + 2];
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint64_t size = i < n ? sizes[i] : 0;
-  const uint64_t off = arena_alloc_block(head, size, s_scan, &s_addr);
+  const uint64_t off = arena_alloc_wg(head, size, s_part);
   if (i < n) offsets[i] = off;
 }
 
@@ -210,8 +180,7 @@ __global__ __launch_bounds__(kBlock) void k_alloc(WalkParams P, const uint64_t* 
   Ctrl* ctrl = P.ctrl;
   const uint32_t n_ops = P.n_ops, n_layers = P.n_layers;
   const uint64_t n_records = P.n_records;
-  __shared__ uint64_t s_scan[kBlock];
-  __shared__ uint64_t s_addr;
+  __shared__ uint64_t s_part[kBlock / 64 + 2];
   __shared__ unsigned long long s_max;
   if (ctrl->err) return;
   const uint32_t tid = threadIdx.x;
@@ -232,7 +201,7 @@ __global__ __launch_bounds__(kBlock) void k_alloc(WalkParams P, const uint64_t* 
           so = d.arity ? 0 : round128((n_records + 1) * 8ull);
         }
       }
-      const uint64_t off = arena_alloc_block(&ctrl->head, sv + so, s_scan, &s_addr);
+      const uint64_t off = arena_alloc_wg(&ctrl->head, sv + so, s_part);
       if (mine) {
         dyn[i].values_off = off;
         dyn[i].offsets_off = so ? off + sv : 0;
@@ -345,8 +314,7 @@ hipError_t launch_arena_alloc(uint64_t* head, const uint64_t* sizes, uint64_t n,
                               hipStream_t st) {
   if (n == 0) return hipSuccess;
   const uint64_t blocks = (n + threads - 1) / threads;
-  hipLaunchKernelGGL(k_arena_alloc, dim3((uint32_t)blocks), dim3(threads), threads * sizeof(uint64_t), st, head, sizes,
-                     n, offsets);
+  hipLaunchKernelGGL(k_arena_alloc, dim3((uint32_t)blocks), dim3(threads), 0, st, head, sizes, n, offsets);
   return hipGetLastError();
 }
 

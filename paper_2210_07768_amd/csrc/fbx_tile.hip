@@ -41,6 +41,7 @@
 #include <algorithm>
 #include <type_traits>
 
+#include "fbx_arena.h"
 #include "fbx_device.h"
 
 // How a tile of 64 records runs its single-sign operators (kernels compiled for a plan only): 0 as any
@@ -1835,6 +1836,63 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
 }
 
 #ifndef FBX_FIXED_MODE
+// ---- one ragged root operator with in-kernel allocation, results behind per-record pointers
+// Section 5 as the paper uses it (Figure 5): a thread works out how much memory its result needs,
+// the workgroup allocates with Algorithm 1 (one atomic add per workgroup, arena_alloc_wg), the
+// thread writes its result into its region and leaves the region's offset in the table of thread
+// offsets.  One record per thread, read in place; no counting launch, no scan.  Regions of one
+// workgroup lie end to end in record order; workgroups land in the order in which they arrive.
+__global__ __launch_bounds__(kBlock) void k_unordered(UnorderedParams U) {
+  __shared__ uint64_t s_part[kBlock / 64 + 2];
+  const uint64_t r = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  const OpProg& d = U.op;
+  bool ok = r < U.n_records;
+  uint32_t cnt = 0, s = 0, e = 0, err = 0;
+  GlobalSrc src{gptr(U.raw), 0u};
+  if (ok) {
+    const uint64_t a = U.rec_off[r], b = U.rec_off[r + 1];
+    if (a > b || b > U.raw_len) { err = CE_OFFSETS; ok = false; }
+    else if (b - a >= (1ull << 31)) { err = CE_TILE; ok = false; }
+    else {
+      uint32_t len = (uint32_t)(b - a);
+      if (len && U.raw[b - 1] == '\n') --len;
+      src = GlobalSrc{gptr(U.raw) + a, len};
+      src.span(0, d.field, s, e);
+      if (d.kind == OP_NGRAM) cnt = e - s >= d.aux_len ? e - s - d.aux_len + 1u : 0u;
+      else cnt = (d.kind == OP_FILTER && (d.flags & F_NEVER)) ? 0u : ragged_root_count(src, d, U.aux, s, e);
+      if (cnt > kMaxCount) { err = CE_OVERFLOW; ok = false; cnt = 0; }
+    }
+  }
+  const uint64_t off = arena_alloc_wg(&U.state[0], 8ull * cnt, s_part);  // (every thread of the workgroup)
+  uint32_t malformed = 0;
+  if (r < U.n_records) {
+    U.thread_off[r] = ok ? off : 0ull;
+    U.lengths[r] = cnt;
+  }
+  if (ok && cnt) {
+    if (off + 8ull * cnt > U.pool_bytes) {
+      err = CE_NOMEM;  // the pool is exhausted: nothing is written beyond it, the head says what would have sufficed
+    } else {
+      G64 dst = gptr(reinterpret_cast<uint64_t*>(U.pool + off));
+      if (d.kind == OP_NGRAM) {
+        for (uint32_t q = 0; q < cnt; ++q) dst[q] = hash_span(src, s + q, s + q + d.aux_len, d.key);
+      } else {
+        ragged_root_emit(src, d, U.aux, s, e, dst, malformed);
+      }
+    }
+  }
+  if (err) atomicOr(reinterpret_cast<unsigned long long*>(&U.state[1]), (unsigned long long)err);
+  uint64_t total = cnt;
+  for (int sh = 32; sh >= 1; sh >>= 1) {
+    total += __shfl_xor(total, sh, 64);
+    malformed += __shfl_xor(malformed, sh, 64);
+  }
+  if ((threadIdx.x & 63u) == 0) {
+    if (total) atomicAdd(reinterpret_cast<unsigned long long*>(&U.state[2]), (unsigned long long)total);
+    if (malformed) atomicAdd(reinterpret_cast<unsigned long long*>(&U.state[3]), (unsigned long long)malformed);
+  }
+}
+
 // The kernel for any plan: everything it needs to know arrives in P.
 template <int MODE>
 __global__ __launch_bounds__(kTileThreads, 4) void k_tile(TileParams P) {
@@ -1898,6 +1956,13 @@ hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st) {
   if (mode == 0) hipLaunchKernelGGL(k_tile<0>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
   else if (mode == 1) hipLaunchKernelGGL(k_tile<1>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
   else hipLaunchKernelGGL(k_tile<2>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
+  return hipGetLastError();
+}
+
+hipError_t launch_unordered(const UnorderedParams& U, hipStream_t st) {
+  if (U.n_records == 0) return hipSuccess;
+  const uint64_t blocks = (U.n_records + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(k_unordered, dim3((uint32_t)blocks), dim3(kBlock), 0, st, U);
   return hipGetLastError();
 }
 
