@@ -153,3 +153,43 @@ def extract(spec: str, records: List[bytes]) -> Tuple[Dict[int, Tuple[List[int],
                 vals.extend(res)
                 offs.append(len(vals))
     return out, malformed
+
+
+# ---------------------------------------------------------------- the toy "clean views" stage
+def clean(spec: str, records):
+    """Kept records (bytes, each ending in a newline) of the cleaning spec, with Python's own
+    split / partition / startswith (Section 3, "Clean views": fill nulls, take one key out of a flat
+    key:value list, drop instances by a filter)."""
+    lines = [ln.split("#")[0].split() for ln in spec.splitlines()]
+    lines = [ln for ln in lines if ln]
+    assert lines[0] == ["fbxclean", "1"] and lines[1][0] == "fields"
+    n_fields = int(lines[1][1])
+    ops = []
+    for ln in lines[2:]:
+        kv = dict(item.split("=", 1) for item in ln[1:])
+        arg = bytes.fromhex(kv[{"fill": "value", "key": "name", "keep": "prefix"}[ln[0]]])
+        ops.append((ln[0], int(kv["field"]), arg))
+    out = []
+    for rec in records:
+        if rec.endswith(b"\n"):
+            rec = rec[:-1]
+        fields = (rec.split(b"\t") + [b""] * n_fields)[:n_fields]
+        keep = True
+        for kind, k, arg in ops:
+            if kind == "fill":
+                if not fields[k]:
+                    fields[k] = arg
+            elif kind == "key":
+                value = b""
+                for pair in fields[k].split(b";"):
+                    key, sep, val = pair.partition(b":")
+                    if sep and key == arg:
+                        value = val
+                        break
+                fields[k] = value
+            elif not fields[k].startswith(arg):
+                keep = False
+                break
+        if keep:
+            out.append(b"\t".join(fields) + b"\n")
+    return out
