@@ -302,6 +302,47 @@ fbx_status fbx_extract_unordered(fbx_plan* plan, uint32_t slot_id, const uint8_t
                                  fbx_unordered_result* out);
 
 /*
+ * The "clean views" stage in toy form (Section 3, "Clean views": null values are filled, fields are
+ * taken out of a JSON-like column, instances are dropped by a custom filter; Section 4 runs the
+ * stage on the GPU).  The paper defines none of the three; this is the contract built here.
+ * Spec text (line-oriented ASCII, '#' starts a comment):
+ *     fbxclean 1
+ *     fields <F>
+ *     fill field=<k> value=<hex bytes>    an empty field k becomes the value (no tab, no newline, not empty)
+ *     key  field=<k> name=<hex bytes>     field k is a flat list "key:value;key:value;...": it becomes the
+ *                                         value of the first pair whose key is exactly the name, or empty
+ *                                         (a pair's key ends at its first ':'; a pair without ':' never matches)
+ *     keep field=<k> prefix=<hex bytes>   the record is dropped unless field k begins with the prefix
+ * A record (framed as for fbx_extract) is cut into exactly F fields (missing ones are empty, further
+ * ones are dropped); the operators that name a field apply to it in spec order, a filter seeing the
+ * field as the operators before it left it.  A kept record is written as its F fields joined by
+ * '\t' and ended by '\n'; kept records follow each other in input order.
+ *
+ * fbx_clean_create   : HOST only.  Errors: FBX_E_ARG, FBX_E_SPEC (fbx_clean_last_error(NULL) says why).
+ * fbx_clean_scratch_hint : bytes of scratch that fbx_clean_run needs for n_records records.
+ * fbx_clean_run      : d_raw / d_rec_off as for fbx_extract (DEVICE).
+ *     d_out      : DEVICE, out_cap bytes: receives the cleaned text
+ *     d_out_off  : DEVICE, n_records + 1 u64: entries 0 .. n_kept receive the kept records' offsets
+ *                  (entry n_kept = length of the cleaned text), ready to be handed to fbx_extract
+ *     d_scratch  : DEVICE, 256-byte aligned, scratch_bytes bytes, the caller's; contents unspecified afterwards
+ *     out        : HOST: kept records, bytes of cleaned text, scratch bytes needed
+ *   Enqueues on hip_stream and synchronises it once.  Errors: FBX_E_ARG, FBX_E_INPUT (bad offsets),
+ *   FBX_E_HIP, FBX_E_NOMEM: scratch too small (out->required_scratch), or d_out too small: nothing
+ *   is written to it and out->out_len holds the bytes needed.
+ */
+typedef struct fbx_clean fbx_clean;
+typedef struct {
+  uint64_t n_kept, out_len, required_scratch;
+} fbx_clean_result;
+fbx_status fbx_clean_create(const char* spec, size_t spec_len, fbx_clean** out);
+void fbx_clean_destroy(fbx_clean* clean);
+const char* fbx_clean_last_error(const fbx_clean* clean);
+fbx_status fbx_clean_scratch_hint(const fbx_clean* clean, uint64_t n_records, uint64_t* bytes);
+fbx_status fbx_clean_run(fbx_clean* clean, const uint8_t* d_raw, uint64_t raw_len, const uint64_t* d_rec_off,
+                         uint64_t n_records, uint8_t* d_out, uint64_t out_cap, uint64_t* d_out_off,
+                         void* d_scratch, uint64_t scratch_bytes, void* hip_stream, fbx_clean_result* out);
+
+/*
  * The measurement behind Table 1 of the paper (Section 4, "Inner-GPU operator launching"), on this
  * device: n_launches launches of an empty kernel with five pointer arguments are enqueued on
  * hip_stream back to back and waited for; *microseconds (HOST) receives the host time from the

@@ -22,6 +22,7 @@ EXPORTS = [
     "fbx_plan_kernel_ms", "fbx_plan_compiled", "fbx_arena_alloc", "fbx_arena_reset",
     "fbx_extract_static", "fbx_static_scratch_bytes", "fbx_plan_kernel_source",
     "fbx_launch_overhead", "fbx_extract_unordered",
+    "fbx_clean_create", "fbx_clean_destroy", "fbx_clean_last_error", "fbx_clean_scratch_hint", "fbx_clean_run",
 ]
 
 
@@ -43,6 +44,10 @@ class Result(ctypes.Structure):
                 ("n_slots", ctypes.c_uint32), ("n_layers", ctypes.c_uint32),
                 ("slots", ctypes.POINTER(SlotView)),
                 ("tile_launches", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+class CleanResult(ctypes.Structure):
+    _fields_ = [("n_kept", ctypes.c_uint64), ("out_len", ctypes.c_uint64), ("required_scratch", ctypes.c_uint64)]
 
 
 class UnorderedResult(ctypes.Structure):
@@ -84,6 +89,16 @@ def lib():
         L.fbx_extract_unordered.restype = ctypes.c_int
         L.fbx_extract_unordered.argtypes = [vp, u32, vp, u64, vp, u64, vp, u64, vp, ctypes.c_int, vp, vp, vp,
                                             ctypes.POINTER(UnorderedResult)]
+        L.fbx_clean_create.restype = ctypes.c_int
+        L.fbx_clean_create.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(vp)]
+        L.fbx_clean_destroy.restype = None
+        L.fbx_clean_destroy.argtypes = [vp]
+        L.fbx_clean_last_error.restype = ctypes.c_char_p
+        L.fbx_clean_last_error.argtypes = [vp]
+        L.fbx_clean_scratch_hint.restype = ctypes.c_int
+        L.fbx_clean_scratch_hint.argtypes = [vp, u64, ctypes.POINTER(u64)]
+        L.fbx_clean_run.restype = ctypes.c_int
+        L.fbx_clean_run.argtypes = [vp, vp, u64, vp, u64, vp, u64, vp, vp, u64, vp, ctypes.POINTER(CleanResult)]
         L.fbx_launch_overhead.restype = ctypes.c_int
         L.fbx_launch_overhead.argtypes = [u32, vp, ctypes.POINTER(ctypes.c_double)]
         L.fbx_last_error.restype = ctypes.c_char_p
@@ -335,3 +350,45 @@ def launch_overhead(n_launches: int, stream: int = 0) -> float:
     if st != OK:
         raise FbxError(st, lib().fbx_status_str(st).decode())
     return us.value
+
+
+class Clean:
+    """fbx_clean_create / fbx_clean_run / fbx_clean_destroy: the toy "clean views" stage."""
+
+    def __init__(self, spec: str):
+        self._h = ctypes.c_void_p()
+        s = spec.encode() if isinstance(spec, str) else spec
+        st = lib().fbx_clean_create(s, len(s), ctypes.byref(self._h))
+        if st != OK:
+            self._h = ctypes.c_void_p()
+            raise FbxError(st, lib().fbx_clean_last_error(None).decode())
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            lib().fbx_clean_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def scratch_hint(self, n_records: int) -> int:
+        out = ctypes.c_uint64()
+        st = lib().fbx_clean_scratch_hint(self._h, n_records, ctypes.byref(out))
+        if st != OK:
+            raise FbxError(st, "bad argument")
+        return out.value
+
+    def run(self, d_raw, d_rec_off, d_out, d_out_off, scratch, stream: Optional[int] = None) -> CleanResult:
+        """All arguments are CUDA tensors owned by the caller (uint8, int64, uint8, int64, uint8)."""
+        import torch
+
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        res = CleanResult()
+        st = lib().fbx_clean_run(self._h, d_raw.data_ptr() if d_raw.numel() else 0, d_raw.numel(), d_rec_off.data_ptr(),
+                                 d_rec_off.numel() - 1, d_out.data_ptr() if d_out.numel() else 0, d_out.numel(),
+                                 d_out_off.data_ptr(), scratch.data_ptr(), scratch.numel(), stream, ctypes.byref(res))
+        if st != OK:
+            err = FbxError(st, lib().fbx_clean_last_error(self._h).decode())
+            err.required_bytes = res.out_len if st == E_NOMEM else 0
+            raise err
+        return res
