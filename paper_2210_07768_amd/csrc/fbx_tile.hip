@@ -50,6 +50,9 @@
 #ifndef FBX_LANE_OPS
 #define FBX_LANE_OPS 0
 #endif
+#ifndef FBX_EXP
+#define FBX_EXP 0
+#endif
 
 
 namespace fbx {
@@ -582,6 +585,76 @@ struct NumState {
   }
 };
 
+// The same grammar over a staged token [s, e) without a loop over its bytes.  The token's first
+// sixteen bytes are fetched at once; a bit mask of the bytes that are not digits gives the ends of
+// the integer part and of the fraction (count trailing zeros); up to eight integer digits and the
+// first six fraction digits are converted four at a time (digit pairs by one multiply-add, pairs
+// of pairs by another).  Tokens longer than sixteen bytes or integer parts longer than eight
+// digits (rare) take the byte-by-byte state machine.  Value and malformed flag as NumState's.
+__device__ __forceinline__ uint32_t four_digits(uint32_t w) {  // bytes 0..3 hold digit values, byte 0 the most significant
+  const uint32_t t = w * 10u + (w >> 8);                       // byte 0: d0 * 10 + d1, byte 2: d2 * 10 + d3 (no carries: <= 99)
+  return (t & 0xffu) * 100u + ((t >> 16) & 0xffu);
+}
+__device__ __forceinline__ int64_t parse_micro(const LdsSrc& src, uint32_t s, uint32_t e, bool& bad) {
+  const uint32_t n = e - s;
+  uint32_t x0, x1, x2, x3;
+  window8(src, s, x0, x1);
+  window8(src, s + 8u, x2, x3);
+  // bit i: byte i is not a digit (bytes at and beyond n count as such)
+  auto not_digit = [](uint32_t w) -> uint32_t {
+    const uint32_t t = w ^ 0x30303030u;  // '0'..'9' become 0..9
+    return (((t & 0x7f7f7f7fu) + 0x76767676u) | t) & 0x80808080u;
+  };
+  uint32_t lo8 = __builtin_amdgcn_udot4(not_digit(x0), 0x08040201u, 0u, false);
+  lo8 = __builtin_amdgcn_udot4(not_digit(x1), 0x80402010u, lo8, false);
+  uint32_t hi8 = __builtin_amdgcn_udot4(not_digit(x2), 0x08040201u, 0u, false);
+  hi8 = __builtin_amdgcn_udot4(not_digit(x3), 0x80402010u, hi8, false);
+  const uint32_t nd = (((lo8 | (hi8 << 8)) >> 7) | (n >= 16u ? 0x10000u : (~0u << n))) & 0x1ffffu;
+  const uint32_t neg = (x0 & 0xffu) == '-' && n ? 1u : 0u;
+  const uint32_t i1 = neg + (uint32_t)__builtin_ctz(nd >> neg);           // end of the integer part (<= 16)
+  // the byte at i1, if it lies inside the token
+  const uint32_t pick = i1 & 8u ? ((i1 & 4u) ? x3 : x2) : ((i1 & 4u) ? x1 : x0);
+  const bool dot = i1 < n && i1 < 16u && ((pick >> (8u * (i1 & 3u))) & 0xffu) == '.';
+  const uint32_t f0 = i1 + 1u;                                            // first byte of the fraction, if there is one
+  const uint32_t i2 = dot ? f0 + (uint32_t)__builtin_ctz((nd >> f0) | (1u << (16u - min(f0, 16u)))) : i1;  // end of what fits the grammar
+  const uint32_t ni = i1 - neg, nfd = dot ? i2 - f0 : 0u;
+  if (n > 16u || ni > 8u || i2 > 16u) {  // beyond the window: byte by byte
+    NumState ns;
+    for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
+    return ns.finish(bad);
+  }
+  bad = i2 < n || ni + nfd == 0u;
+  // integer part: its ni bytes moved to the top of a 64-bit word, zeros (leading digits of value 0) below
+  const uint64_t all_lo = ((uint64_t)x1 << 32) | x0, all_hi = ((uint64_t)x3 << 32) | x2;
+  const uint64_t from_start = neg ? (all_lo >> 8) | (all_hi << 56) : all_lo;
+  const uint64_t top = ni ? (from_start << (64u - 8u * ni)) & 0x0f0f0f0f0f0f0f0full : 0ull;
+  const uint32_t ip = four_digits((uint32_t)top) * 10000u + four_digits((uint32_t)(top >> 32));
+  // fraction: its first (up to six) bytes at the bottom of a word, zeros (trailing digits of value 0) above
+  const uint32_t nf = min(nfd, 6u);
+  uint64_t fr = f0 >= 8u ? all_hi >> (8u * min(f0 - 8u, 7u)) : (all_lo >> (8u * f0)) | (all_hi << (64u - 8u * f0));  // (f0 >= 1; at f0 = 16 nf is 0)
+  fr &= 0x0f0f0f0f0f0f0f0full & ((1ull << (8u * nf)) - 1ull);
+  const uint32_t h = (uint32_t)(fr >> 32);
+  const uint32_t fp = four_digits((uint32_t)fr) * 100u + (((h * 10u + (h >> 8)) & 0xffu));
+  uint64_t v = (uint64_t)ip * 1000000ull + fp;
+  if (neg) v = 0ull - v;
+  return (int64_t)v;
+}
+__device__ __forceinline__ int64_t parse_micro(const GlobalSrc& src, uint32_t s, uint32_t e, bool& bad) {
+  NumState ns;
+  for (uint32_t p = s; p < e; ++p) ns.step(src.byte(p));
+  return ns.finish(bad);
+}
+// index = number of boundaries <= v; sign = mix64(key + index)
+__device__ __forceinline__ uint64_t bucket_of(int64_t v, uint64_t key, const uint8_t* aux, uint32_t aux_off, uint32_t n_bounds) {
+  const int64_t* b = reinterpret_cast<const int64_t*>(aux + aux_off);
+  uint32_t lo = 0, hi = n_bounds;
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (b[mid] <= v) lo = mid + 1; else hi = mid;
+  }
+  return mix64(key + lo);
+}
+
 __device__ __forceinline__ uint64_t bucket_sign(const OpProg& d, const uint8_t* aux, NumState& ns, uint32_t& malformed) {
   bool bad;
   const int64_t v = ns.finish(bad);
@@ -991,9 +1064,10 @@ struct Pass {
     if (!d || !live) return;
     uint32_t s, e;
     src.span(r, d->field, s, e);
-    NumState ns;
-    for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
-    const uint64_t v = bucket_sign(*d, sh.aux, ns, malformed);
+    bool bad;
+    const int64_t x = parse_micro(src, s, e, bad);
+    malformed += bad ? 1u : 0u;
+    const uint64_t v = bucket_of(x, d->key, sh.aux, d->aux_off, d->aux_len);
     store_single(d->values, g, v);
     if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
   }
@@ -1165,18 +1239,10 @@ struct Pass {
     if (lane >= nb) return;
     uint32_t s, e;
     src.span(lane, field, s, e);
-    NumState ns;
-    for_each_byte(src, s, e, [&](uint32_t b) { ns.step(b); });
     bool bad;
-    const int64_t v = ns.finish(bad);
+    const int64_t v = parse_micro(src, s, e, bad);
     malformed += bad ? 1u : 0u;
-    const int64_t* b = reinterpret_cast<const int64_t*>(sh.aux + aux_off);
-    uint32_t lo = 0, hi = n_bounds;  // index = number of boundaries <= v
-    while (lo < hi) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (b[mid] <= v) lo = mid + 1; else hi = mid;
-    }
-    lane_put(lane, values, stage, mix64(key + lo));
+    lane_put(lane, values, stage, bucket_of(v, key, sh.aux, aux_off, n_bounds));
   }
   __device__ __forceinline__ void lane_x11(uint32_t stage_a, uint32_t stage_b, uint64_t key, uint64_t values, uint32_t stage) const {
     const uint32_t lane = lane_id();

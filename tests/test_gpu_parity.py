@@ -299,6 +299,40 @@ def test_malformed_numerics_are_counted():
     assert res.n_malformed_numeric == want.n_malformed_numeric > 0
 
 
+def test_numeric_tokens_of_every_shape():
+    """Numbers of every length and shape the grammar knows, and text that is not a number, as single
+    values and as lists: short tokens take the kernel's loop-free conversion (a mask of non-digit
+    bytes, four digits at a time), tokens beyond sixteen bytes and integer parts beyond eight digits
+    its byte-by-byte fall-back; whatever follows a token in memory must not matter."""
+    rng = random.Random(2024)
+    digits = lambda k: "".join(rng.choice("0123456789") for _ in range(k))
+
+    def token():
+        kind = rng.random()
+        if kind < 0.55:
+            t = ("-" if rng.random() < 0.3 else "") + digits(rng.choice([0, 1, 1, 2, 3, 5, 8, 9, 12, 19, 23]))
+            if rng.random() < 0.7:
+                t += "." + digits(rng.choice([0, 1, 2, 5, 6, 7, 9, 14]))
+            if rng.random() < 0.1:
+                t += rng.choice(["x", ".", "-", "e5", " "])
+            return t
+        if kind < 0.8:
+            return "".join(rng.choice("0123456789.-x") for _ in range(rng.choice([0, 1, 2, 3, 7, 8, 9, 15, 16, 17, 18, 30])))
+        return rng.choice(["", "-", ".", "-.", "-.5", ".5", "1.", "00001.000001", "99999999", "999999999", "0.0000019",
+                           "12345678.123456", "-12345678.1234567", "9" * 16, "9" * 17, "1" + "0" * 22])
+
+    spec = ("fbx 1\nfields 3\n"
+            "op a bucket slot=0 seed=1 emit=1 field=0 multi=0 bounds=-1000000,0,1,999999,1000000,12345678123456,99999999000000\n"
+            "op b bucket slot=1 seed=2 emit=1 field=1 multi=1 bounds=-5000000,0,5000000\n"
+            "op c bucket slot=2 seed=3 emit=1 field=2 multi=0 bounds=\n"
+            "op x cross slot=3 seed=4 emit=1 a=a b=c\n")
+    recs = [(f"{token()}\t{','.join(token().replace(',', '') for _ in range(rng.randint(1, 4)))}\t{token()}" + ("\n" if i % 2 else "")).encode()
+            for i in range(20000)]
+    for mode in ({}, {"compile": 1}, {"tile_log2": 6, "compile": 1, "lane_ops": 1}, {"fused": 0}):
+        res, want = check(spec, *_cat(recs), mode, label=f"numeric tokens {mode}")
+        assert res.n_malformed_numeric == want.n_malformed_numeric > 1000
+
+
 def test_bad_offsets_are_rejected():
     w = W.get(1, 64)
     raw, off = w.generate()
