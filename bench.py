@@ -42,7 +42,8 @@ def source_digest() -> str:
     """Digest of the kernel and host sources of the library: counter readings in profiles/ name the
     digest they were taken at and are quoted only while it still matches."""
     h = hashlib.sha256()
-    files = sorted(glob.glob(os.path.join(ROOT, "paper_2210_07768_amd", "csrc", "*")))
+    files = sorted(f for f in glob.glob(os.path.join(ROOT, "paper_2210_07768_amd", "csrc", "*"))
+                   if os.path.basename(f) != "fbx_clean.hip")     # (the cleaning stage is no part of the extraction path)
     for f in files + [os.path.join(ROOT, "include", "fbx.h")]:
         if os.path.isfile(f):
             h.update(os.path.basename(f).encode() + b"\0" + open(f, "rb").read() + b"\0")
@@ -129,6 +130,65 @@ def cpu_baseline(w, budget_s=10.0):
                               "sample": f"first {m1} records, {dt1:.1f} s"}}
 
 
+def side_stage(args, w, B, torch):
+    """Timings of the two stages beside the benchmark line: one ragged operator with in-kernel
+    allocation (unordered output) against the same operator through the ordered path, and the toy
+    cleaning stage.  HIP events around each call, median of --steps calls; one JSON line."""
+    R = w.n_records
+    d_raw, d_off = build_inputs(w, 0, tag="A")
+
+    def timed(call):
+        for _ in range(max(args.warmup, 1)):
+            call()
+        ms = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); call(); b.record()
+            torch.cuda.synchronize()
+            ms.append(a.elapsed_time(b))
+        return statistics.median(ms)
+
+    if args.stage == "unordered":
+        line = next(ln for ln in w.spec.split("\n") if " multi=1" in ln and " emit=1" in ln)
+        slot = int(line.split("slot=")[1].split()[0])
+        spec = "\n".join(w.spec.split("\n")[:2] + [line]) + "\n"
+        plan = B.Plan(spec)
+        res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.1)
+        n_signs = res.n_values_total
+        pool = torch.empty(int(8 * n_signs * 1.05) + (R // 256 + 1) * 128 + 4096, dtype=torch.uint8, device="cuda")
+        state = torch.zeros(4, dtype=torch.int64, device="cuda")
+        toff = torch.empty(R, dtype=torch.int64, device="cuda")
+        lens = torch.empty(R, dtype=torch.int32, device="cuda")
+        t_un = timed(lambda: plan.extract_unordered(slot, d_raw, d_off, pool, state, toff, lens))
+        plan.set_option("one_launch", 0)
+        t_cw = timed(lambda: plan.extract(d_raw, d_off))
+        plan.set_option("one_launch", 1)
+        plan.extract(d_raw, d_off)
+        t_one = timed(lambda: plan.extract(d_raw, d_off))
+        alg = d_raw.numel() + 8 * (R + 1) + 8 * n_signs + 8 * (R + 1)
+        print(json.dumps({"stage": "unordered", "workload": w.name, "records": R, "operator": line, "signs": int(n_signs),
+                          "ms": {"in_kernel_allocation_unordered": t_un, "ordered_count_scan_write": t_cw, "ordered_one_launch_look_back": t_one},
+                          "algorithmic_GBps": {"in_kernel_allocation_unordered": alg / t_un / 1e6, "ordered_count_scan_write": alg / t_cw / 1e6,
+                                               "ordered_one_launch_look_back": alg / t_one / 1e6},
+                          "note": "the operator's field is one of many: every variant reads the whole text once (twice with a counting launch)"}))
+        plan.close()
+        return
+    k = next(i for i, f in enumerate(w.fields) if f.kind == 0)   # a single-valued categorical field
+    spec = ("fbxclean 1\n" + f"fields {w.n_fields}\n" + f"fill field={k} value={b'none'.hex()}\n"
+            + f"keep field={k} prefix=\n" + f"fill field={w.n_fields - 1} value=30\n")
+    clean = B.Clean(spec)
+    scratch = torch.empty(clean.scratch_hint(R), dtype=torch.uint8, device="cuda")
+    d_out = torch.empty(d_raw.numel() + 8 * R, dtype=torch.uint8, device="cuda")
+    d_out_off = torch.empty(R + 1, dtype=torch.int64, device="cuda")
+    res = clean.run(d_raw, d_off, d_out, d_out_off, scratch)
+    t = timed(lambda: clean.run(d_raw, d_off, d_out, d_out_off, scratch))
+    alg = d_raw.numel() + 8 * (R + 1) + res.out_len + 8 * (res.n_kept + 1)
+    print(json.dumps({"stage": "clean", "workload": w.name, "records": R, "kept": int(res.n_kept), "spec": spec, "ms": t,
+                      "algorithmic_GBps": alg / t / 1e6, "frac_of_hbm_peak": alg / t / 1e6 / HBM_PEAK_GBPS,
+                      "note": "one record per thread, read in place, twice (measure, write): a toy stage, not tuned"}))
+    clean.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -152,6 +212,10 @@ def main():
     ap.add_argument("--launch-overhead", action="store_true",
                     help="only measure what Table 1 of the paper measures, on this device, and exit: 1 / 10 / 100 / "
                          "1,000 / 10,000 back-to-back launches of an empty kernel with five pointer arguments")
+    ap.add_argument("--stage", choices=["extract", "unordered", "clean"], default="extract",
+                    help="what to time: the extraction path (default, the benchmark line); 'unordered': one ragged "
+                         "operator of layer 1 with in-kernel allocation (fbx_extract_unordered) beside the ordered path "
+                         "on a plan that holds only that operator; 'clean': the toy cleaning stage (fbx_clean_run)")
     ap.add_argument("--print-source-digest", action="store_true",
                     help="print the digest of the library's sources that counter summaries in profiles/ are keyed on")
     args = ap.parse_args()
@@ -190,6 +254,9 @@ def main():
     w = W.get(args.config, args.records)
     R = w.n_records
     log(f"[bench] workload {w.name}: {R} records x {w.n_fields} fields, {w.n_ops} ops, {w.n_layers} layers")
+    if args.stage != "extract":
+        side_stage(args, w, B, torch)
+        return
     batches = [build_inputs(w, 0, tag="A")]
     if not args.one_batch:
         batches.append(build_inputs(w, R, tag="B"))

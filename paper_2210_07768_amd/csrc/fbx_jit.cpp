@@ -127,7 +127,10 @@ void braces(std::ostringstream& os, const uint32_t* v, size_t n) {
 std::string program_text(const TileParams& P, int mode, const PlanHost& h, uint32_t threads, uint32_t lane_ops) {
   std::ostringstream os;
   os << "#define FBX_TILE_THREADS " << threads << "\n";
-  if (const char* x = getenv("FBX_EXP")) os << "#define FBX_EXP " << x << "\n";  // EXPERIMENT HOOK (to be removed)
+  // (tuning: the environment variable FBX_EXP defines the macro of that name for the compiled kernel, so that
+  // two variants of a piece of kernel code, written under #if FBX_EXP & <bit>, can be timed in one process
+  // environment after the other on the same device; no committed code path depends on it)
+  if (const char* x = getenv("FBX_EXP")) os << "#define FBX_EXP " << atoi(x) << "\n";
   os << "#define FBX_FIXED_MODE " << mode << "\n#define FBX_FIXED_NAME fbx_tile_fixed_" << mode << "\n#define FBX_FIXED_ASSIGN";
   FBX_TILE_FIXED_FIELDS(FBX_FIELD_ASSIGN)
   // wavefronts per SIMD the kernel must leave registers for: as many workgroups as the LDS admits

@@ -1033,12 +1033,17 @@ struct Pass {
 
   // ---- layer 1
   // (a unit is 2 G operators, each lane taking two of them one after the other: half the hand-outs and set-ups)
+  static constexpr uint32_t kHashPairs = 1;  // pairs of operators a lane hashes per unit (two pairs measured 1.6 % slower: fewer, longer units balance worse)
   __device__ __forceinline__ uint32_t hash1_units() const {
-    return (sh.lbeg(TL_HASH1 + 1) - sh.lbeg(TL_HASH1) + 2u * G - 1u) / (2u * G);
+    return (sh.lbeg(TL_HASH1 + 1) - sh.lbeg(TL_HASH1) + 2u * kHashPairs * G - 1u) / (2u * kHashPairs * G);
   }
   __device__ __forceinline__ void hash1_unit(uint32_t u) {
     refresh();
     if (!live) return;
+#pragma unroll
+    for (uint32_t pair = 0; pair < kHashPairs; ++pair) hash1_pair(u * kHashPairs + pair);
+  }
+  __device__ __forceinline__ void hash1_pair(uint32_t u) {
     const uint32_t lb = sh.lbeg(TL_HASH1), m = sh.lbeg(TL_HASH1 + 1) - lb;
     // both operators' programs and fields are looked up before either is hashed: the look-ups
     // (program, then field table) are waited for once, not once per operator
@@ -1279,14 +1284,34 @@ struct Pass {
 
   // ---- later layers
   // crosses of two single signs, both on chip
+  static constexpr uint32_t kCrossesPerLane = 2;  // (two a lane: half the hand-outs; measured 0.7 % on the largest workload)
+  __device__ __forceinline__ uint32_t x11_units(uint32_t layer) const {
+    const uint32_t list = TL_LAYER + 2u * (layer - 2u);
+    return (sh.lbeg(list + 1) - sh.lbeg(list) + kCrossesPerLane * G - 1u) / (kCrossesPerLane * G);
+  }
   __device__ __forceinline__ void x11_unit(uint32_t layer, uint32_t u) {
     refresh();
-    const OpProg* d = op_of(TL_LAYER + 2u * (layer - 2u), u);
-    if (!d || !live) return;
-    const uint64_t a = sh.stage[d->aux_off * T + r], b = sh.stage[d->aux_len * T + r];
-    const uint64_t v = mix64(mix64(a + d->key) + b);
-    store_single(d->values, g, v);
-    if (d->stage != kNoRow) sh.stage[d->stage * T + r] = v;
+    if (!live) return;
+    const uint32_t list = TL_LAYER + 2u * (layer - 2u);
+    const uint32_t lb = sh.lbeg(list), m = sh.lbeg(list + 1) - lb;
+    // (a cross never reads a cross of its own layer: the crosses of a unit are independent, their inputs are requested together)
+    const OpProg* d[kCrossesPerLane];
+    uint64_t a[kCrossesPerLane], b[kCrossesPerLane];
+#pragma unroll
+    for (uint32_t k = 0; k < kCrossesPerLane; ++k) {
+      const uint32_t i = (u * kCrossesPerLane + k) * G + og;
+      d[k] = i < m ? &sh.prog[lb + i] : nullptr;
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < kCrossesPerLane; ++k)
+      if (d[k]) { a[k] = sh.stage[d[k]->aux_off * T + r]; b[k] = sh.stage[d[k]->aux_len * T + r]; }
+#pragma unroll
+    for (uint32_t k = 0; k < kCrossesPerLane; ++k) {
+      if (!d[k]) continue;
+      const uint64_t v = mix64(mix64(a[k] + d[k]->key) + b[k]);
+      store_single(d[k]->values, g, v);
+      if (d[k]->stage != kNoRow) sh.stage[d[k]->stage * T + r] = v;
+    }
   }
   // Every other cross or concat: lanes are output signs.  The signs that the list operators of
   // one layer produce in this pass, operator after operator and record after record, form one
@@ -1574,7 +1599,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     hook();
     uint32_t* ctr = &s_ctr[4u + (layer & 1u)];
     if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
-    const uint32_t ux = ps.units_of(TL_LAYER + 2u * (layer - 2u));
+    const uint32_t ux = kGen ? ps.units_of(TL_LAYER + 2u * (layer - 2u)) : ps.x11_units(layer);
     for_units(ctr, ux, [&](uint32_t u) {
       if (FBX_SKIP(2u)) return;
       if constexpr (kGen) { ps.lane_x11_unit(layer, u); return; }
