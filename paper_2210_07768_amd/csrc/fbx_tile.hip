@@ -1762,7 +1762,14 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
   for (;;) {
     if (tile >= P.n_tiles) break;
     uint32_t my_ticket = 0;
-    if (tid == 0) my_ticket = atomicAdd(ticket, 1u);  // the next tile; the answer is picked up a barrier later
+    // One-launch mode on a plan of one layer: a tile has little to do between publishing its counts and
+    // needing its bases, so it matters that the tiles before it are counted by then.  Tiles whose numbers
+    // are taken a whole tile ahead start in an order that has drifted by the time they run (tiles differ
+    // in length); there the next tile's number is taken when this tile is done, at the price of fetching
+    // its offsets and text with nothing to hide behind (the largest one-layer workload: 5 % faster; a
+    // two-layer plan, whose single crosses sit between counts and bases: 7 % slower, so it keeps the early ticket).
+    const bool late_ticket = MODE == 2 && P.n_layers == 1u;
+    if (!late_ticket && tid == 0) my_ticket = atomicAdd(ticket, 1u);  // the next tile; the answer is picked up a barrier later
     uint64_t* off = sh.off + par * (T + 1u);
     uint64_t* off2 = sh.off + (par ^ 1u) * (T + 1u);
     const uint64_t g0 = (uint64_t)tile << P.log2T;
@@ -1796,7 +1803,7 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
     uint64_t off_next = 0, off_next1 = 0, nx_lo = 0, nx_hi = 0;
     auto next_tile_step = [&]() {  // every lane, right after a barrier
       if (pf_stage == 0) {
-        if (tid == 0) s_nxt = my_ticket;
+        if (tid == 0) s_nxt = late_ticket ? atomicAdd(ticket, 1u) : my_ticket;
       } else if (pf_stage == 1) {
         nxt = s_nxt;
         if (nxt < P.n_tiles) {
@@ -1822,6 +1829,9 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
         }
       }
       if (pf_stage < 3) ++pf_stage;
+    };
+    auto next_tile_hook = [&]() {  // (what the phases of a pass call after their barriers)
+      if (!late_ticket) next_tile_step();
     };
 
     uint32_t r0 = nrec_ok ? 0u : nrec;
@@ -1873,7 +1883,7 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
         __syncthreads();
         FBX_MARK(3);
         LdsSrc src{sh.raw, sh.rows, P.row_stride};
-        run_pass<MODE>(P, sh, src, nb, g0 + r0, tile, malformed, overflow, next_tile_step);
+        run_pass<MODE>(P, sh, src, nb, g0 + r0, tile, malformed, overflow, next_tile_hook);
         r0 = r1;
       } else {
         // record r0 alone exceeds the section: it is read in place
@@ -1885,7 +1895,7 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
         }
         __syncthreads();
         GlobalSrc src{gptr(P.raw) + o0, s_len};
-        run_pass<MODE>(P, sh, src, 1u, g0 + r0, tile, malformed, overflow, next_tile_step);
+        run_pass<MODE>(P, sh, src, 1u, g0 + r0, tile, malformed, overflow, next_tile_hook);
         r0 += 1u;
       }
       __syncthreads();  // the sections are reused by the next pass
