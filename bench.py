@@ -185,7 +185,7 @@ def side_stage(args, w, B, torch):
     alg = d_raw.numel() + 8 * (R + 1) + res.out_len + 8 * (res.n_kept + 1)
     print(json.dumps({"stage": "clean", "workload": w.name, "records": R, "kept": int(res.n_kept), "spec": spec, "ms": t,
                       "algorithmic_GBps": alg / t / 1e6, "frac_of_hbm_peak": alg / t / 1e6 / HBM_PEAK_GBPS,
-                      "note": "one record per thread, read in place, twice (measure, write): a toy stage, not tuned"}))
+                      "note": "two launches over tiles of records staged in LDS (measure, write) and a scan between them"}))
     clean.close()
 
 

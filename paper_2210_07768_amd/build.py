@@ -10,7 +10,7 @@ _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfbx.so")
 SOURCES = ["fbx_plan.cpp", "fbx_api.cpp", "fbx_jit.cpp", "fbx_support.hip", "fbx_walk.hip", "fbx_tile.hip", "fbx_clean.hip"]
-HEADERS = ["fbx_internal.h", "fbx_device.h", "fbx_arena.h", os.path.join(_ROOT, "include", "fbx.h")]
+HEADERS = ["fbx_internal.h", "fbx_device.h", "fbx_arena.h", "fbx_split.h", os.path.join(_ROOT, "include", "fbx.h")]
 
 
 def hipcc() -> str:

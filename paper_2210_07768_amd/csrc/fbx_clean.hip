@@ -7,7 +7,16 @@
 //
 // Three steps on the caller's stream: every record is measured (kept or dropped, bytes of its
 // cleaned form), an exclusive scan over records places the kept ones (the scan kernels of the
-// extraction path), every kept record is written.  One record per thread, read in place.
+// extraction path), every kept record is written.
+//
+// Measuring and writing work on tiles of T consecutive records, the way the extraction kernel does:
+// a workgroup copies the tile's text into LDS with 16-byte loads that all its lanes share, groups of
+// lanes split each record at its tabs into a table of field ends (split_bytes, the extraction path's
+// splitter), and lanes then are (record, field) pairs: a lane applies its field's operators, leaves
+// the cleaned field's length and source in LDS, a prefix sum per record turns lengths into positions,
+// and in the writing launch the lane copies its field to where it goes; neighbouring lanes write
+// neighbouring fields.  A tile whose text does not fit the LDS section, and a specification with
+// too many fields for the tables, take one record per thread, read in place (slow, same results).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -19,6 +28,7 @@
 #include <vector>
 
 #include "fbx_device.h"
+#include "fbx_split.h"
 
 using namespace fbx;
 
@@ -46,7 +56,15 @@ struct CleanParams {
   uint64_t out_cap;
   uint64_t* out_off;
   Ctrl* ctrl;
+  // shape of the tile kernels (set by the host; log2T == kNoTiles: one record per thread)
+  uint32_t log2T;       // records per tile
+  uint32_t raw_cap;     // bytes of the text section in LDS (a multiple of 16)
+  uint32_t row_stride;  // 16-bit entries per record in the table of field ends
+  uint32_t o_rows, o_len, o_src;  // where the tables start in LDS
 };
+
+constexpr uint32_t kCleanThreads = 256, kCleanRawPad = 16, kCleanMaxT = 64;
+constexpr uint32_t kSrcConst = 0x80000000u;  // the field's bytes come from the operators' arguments, not from the record
 
 struct Bytes {
   const uint8_t* p;
@@ -110,9 +128,8 @@ __device__ bool clean_frame(const CleanParams& C, uint64_t r, const uint8_t*& re
   return true;
 }
 
-__global__ __launch_bounds__(kBlock) void k_clean_measure(CleanParams C) {
-  const uint64_t r = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (r >= C.n_records) return;
+// ---- one record per thread, read in place
+__device__ void measure_in_place(const CleanParams& C, uint64_t r) {
   const uint8_t* rec = nullptr;
   uint32_t rn = 0;
   uint64_t bytes = 0;
@@ -123,15 +140,8 @@ __global__ __launch_bounds__(kBlock) void k_clean_measure(CleanParams C) {
   C.lens[C.n_records + r] = keep ? 1u : 0u;
 }
 
-__global__ __launch_bounds__(kBlock) void k_clean_write(CleanParams C) {
-  const uint64_t r = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (C.ctrl->err) return;
-  if (r == 0) {
-    C.out_off[C.total[1]] = C.total[0];
-    C.ctrl->required = C.total[0];
-    if (C.total[0] > C.out_cap) atomicOr(&C.ctrl->err, (uint32_t)CE_NOMEM);
-  }
-  if (r >= C.n_records || !C.lens[C.n_records + r] || C.total[0] > C.out_cap) return;
+__device__ void write_in_place(const CleanParams& C, uint64_t r) {
+  if (!C.lens[C.n_records + r]) return;
   const uint8_t* rec = nullptr;
   uint32_t rn = 0;
   if (!clean_frame(C, r, rec, rn)) return;
@@ -144,6 +154,217 @@ __global__ __launch_bounds__(kBlock) void k_clean_write(CleanParams C) {
     dst += v.n;
     *dst++ = ++k < C.n_fields ? '\t' : '\n';
   });
+}
+
+// What the writing launch does once: the end of the offsets array, the size the caller needs, the
+// capacity check.  Returns false (in every thread of every workgroup) when nothing may be written.
+__device__ bool write_may_go_ahead(const CleanParams& C, bool first_thread) {
+  if (C.ctrl->err) return false;
+  if (first_thread) {
+    C.out_off[C.total[1]] = C.total[0];
+    C.ctrl->required = C.total[0];
+    if (C.total[0] > C.out_cap) atomicOr(&C.ctrl->err, (uint32_t)CE_NOMEM);
+  }
+  return C.total[0] <= C.out_cap;
+}
+
+__global__ __launch_bounds__(kBlock) void k_clean_measure(CleanParams C) {
+  const uint64_t r = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (r < C.n_records) measure_in_place(C, r);
+}
+
+__global__ __launch_bounds__(kBlock) void k_clean_write(CleanParams C) {
+  const uint64_t r = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (!write_may_go_ahead(C, r == 0)) return;
+  if (r < C.n_records) write_in_place(C, r);
+}
+
+// ---- tiles of records staged in LDS
+extern __shared__ __align__(16) uint8_t clean_smem[];
+
+// A cleaned field while its operators are applied: `n` bytes at position `at` of the staged text,
+// or of the operators' arguments (fixed == true).
+struct Field {
+  uint32_t at, n;
+  bool fixed;
+};
+
+// One workgroup, one tile of up to 1 << C.log2T records.  WRITE == false: the measuring launch.
+template <bool WRITE>
+__global__ __launch_bounds__(kCleanThreads) void k_clean_tile(CleanParams C) {
+  __shared__ uint64_t s_off[kCleanMaxT + 1];
+  __shared__ uint64_t s_base[kCleanMaxT];
+  __shared__ uint32_t s_rs[kCleanMaxT], s_re[kCleanMaxT], s_len[kCleanMaxT], s_drop[kCleanMaxT];
+  __shared__ uint32_t s_bad;
+  __shared__ uint32_t s_go;
+  const uint32_t tid = threadIdx.x;
+  if (WRITE) {  // (one thread decides for the workgroup: the error word may change while the launch runs)
+    if (tid == 0) s_go = write_may_go_ahead(C, blockIdx.x == 0) ? 1u : 0u;
+    __syncthreads();
+    if (!s_go) return;
+  }
+  const uint32_t T = 1u << C.log2T, F = C.n_fields;
+  const uint64_t g0 = (uint64_t)blockIdx.x << C.log2T;
+  if (g0 >= C.n_records) return;  // (an empty batch still launches one workgroup, for the lines above)
+  const uint32_t nb = (uint32_t)min((uint64_t)T, C.n_records - g0);
+  uint8_t* raw = clean_smem;
+  uint16_t* rows = reinterpret_cast<uint16_t*>(clean_smem + C.o_rows);
+  uint32_t* flen = reinterpret_cast<uint32_t*>(clean_smem + C.o_len);  // bytes of the cleaned field and its separator, then where it starts in the cleaned record
+  uint32_t* fsrc = reinterpret_cast<uint32_t*>(clean_smem + C.o_src);  // where its bytes come from
+  if (tid == 0) s_bad = 0;
+  if (tid <= nb) s_off[tid] = C.rec_off[g0 + tid];
+  if (tid < kCleanMaxT) s_drop[tid] = 0;
+  __syncthreads();
+  if (tid < nb) {
+    const uint64_t a = s_off[tid], b = s_off[tid + 1];
+    if (a > b || b > C.raw_len) atomicOr(&s_bad, (uint32_t)CE_OFFSETS);
+    else if (b - a >= (1ull << 31)) atomicOr(&s_bad, (uint32_t)CE_TILE);
+  }
+  __syncthreads();
+  if (s_bad) {  // the call fails; the arrays the scan reads still get defined values
+    if (tid == 0) atomicOr(&C.ctrl->err, s_bad);
+    if (!WRITE && tid < nb) C.lens[g0 + tid] = C.lens[C.n_records + g0 + tid] = 0u;
+    return;
+  }
+  const uint64_t o0 = s_off[0];
+  const uintptr_t ok_lo = reinterpret_cast<uintptr_t>(C.raw), ok_hi = ok_lo + C.raw_len;
+  const uint32_t delta = (uint32_t)((ok_lo + o0) & 15u);
+  if (s_off[nb] - o0 + delta > (uint64_t)C.raw_cap) {  // the text does not fit the section
+    if (tid < nb) {
+      if (WRITE) write_in_place(C, g0 + tid); else measure_in_place(C, g0 + tid);
+    }
+    return;
+  }
+  {  // the tile's text, in whole 16-byte chunks
+    const uint32_t nchunks = (delta + (uint32_t)(s_off[nb] - o0) + 15u) >> 4;
+    const uintptr_t a0 = ok_lo + o0 - delta;
+    for (uint32_t c = tid; c < nchunks; c += kCleanThreads) {
+      const uintptr_t ca = a0 + 16u * c;
+      u32x4 v;
+      if (ca >= ok_lo && ca + 16u <= ok_hi) {
+        v = *reinterpret_cast<const u32x4*>(ca);
+      } else {  // a chunk across an end of the caller's buffer: what lies outside reads as zero
+        uint32_t w[4] = {0, 0, 0, 0};
+        for (uint32_t i = 0; i < 16; ++i) {
+          const uintptr_t bi = ca + i;
+          if (bi >= ok_lo && bi < ok_hi) w[i >> 2] |= (uint32_t)*reinterpret_cast<const uint8_t*>(bi) << (8u * (i & 3u));
+        }
+        v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
+      }
+      *reinterpret_cast<u32x4*>(raw + kCleanRawPad + 16u * c) = v;
+    }
+    if (tid < nb) {
+      s_rs[tid] = kCleanRawPad + delta + (uint32_t)(s_off[tid] - o0);
+      s_re[tid] = kCleanRawPad + delta + (uint32_t)(s_off[tid + 1] - o0);
+    }
+  }
+  __syncthreads();
+  // field ends: 256 / T lanes (at most 64) share a record; entries from the record's tab count on hold its end
+  const uint32_t lg = 8u - C.log2T < 6u ? 8u - C.log2T : 6u;
+  const uint32_t gsz = 1u << lg, j = tid & (gsz - 1u), rr = tid >> lg;
+  const bool act = rr < nb;
+  uint32_t rs = 0, re = 0;
+  if (act) {
+    rs = s_rs[rr]; re = s_re[rr];
+    if (re > rs && raw[re - 1u] == '\n') --re;  // one trailing newline is not part of the record
+  }
+  uint16_t* row = rows + rr * C.row_stride;
+  {
+    const uint32_t tabs = split_bytes(raw, rs, re, act, kTabs, lg, j, F, [&](uint32_t k, uint32_t pos) { row[1u + k] = (uint16_t)pos; });
+    if (act) {
+      if (j == 0) row[0] = (uint16_t)(rs - 1u);
+      for (uint32_t kk = tabs + j; kk < F; kk += gsz) row[1u + kk] = (uint16_t)re;
+    }
+  }
+  __syncthreads();
+  // lanes as (record, field) pairs: a wavefront takes a record, its lanes the fields
+  auto byte_of = [&](const Field& f, uint32_t i) -> uint32_t { return f.fixed ? C.args[f.at + i] : raw[f.at + i]; };
+  for (uint32_t r = tid >> 6; r < nb; r += kCleanThreads / 64u) {
+    const uint16_t* rw = rows + r * C.row_stride;
+    for (uint32_t k = tid & 63u; k < F; k += 64u) {
+      const uint32_t s = (uint32_t)rw[k] + 1u, e = rw[k + 1u];
+      Field f{s, e > s ? e - s : 0u, false};  // (a missing field is empty)
+      bool keep = true;
+      for (uint32_t o = C.first_op[k]; o < C.first_op[k + 1] && keep; ++o) {
+        const CleanOp op = C.ops[o];
+        if (op.kind == CK_FILL) {
+          if (f.n == 0) f = Field{op.arg_off, op.arg_len, true};
+        } else if (op.kind == CK_KEY) {
+          // value of the first pair "key:value" (pairs separated by ';') whose key is exactly the name
+          uint32_t p = 0;
+          for (;;) {
+            uint32_t q = p;
+            while (q < f.n && byte_of(f, q) != ';') ++q;
+            uint32_t c = p;
+            while (c < q && byte_of(f, c) != ':') ++c;
+            if (c < q && c - p == op.arg_len) {
+              bool same = true;
+              for (uint32_t i = 0; i < op.arg_len && same; ++i) same = byte_of(f, p + i) == C.args[op.arg_off + i];
+              if (same) { f.at += c + 1u; f.n = q - c - 1u; break; }
+            }
+            if (q >= f.n) { f.n = 0; break; }
+            p = q + 1u;
+          }
+        } else {
+          keep = f.n >= op.arg_len;
+          for (uint32_t i = 0; i < op.arg_len && keep; ++i) keep = byte_of(f, i) == C.args[op.arg_off + i];
+        }
+      }
+      if (!keep) s_drop[r] = 1u;
+      flen[r * F + k] = f.n + 1u;  // a tab or the newline after every field
+      fsrc[r * F + k] = f.at | (f.fixed ? kSrcConst : 0u);
+    }
+  }
+  __syncthreads();
+  {  // lengths become positions inside the cleaned record: the lanes that shared the record's tabs share its fields
+    const uint32_t c = (F + gsz - 1u) >> lg;
+    const uint32_t k0 = min(j * c, F), k1 = min(k0 + c, F);
+    uint32_t sum = 0;
+    if (act) for (uint32_t k = k0; k < k1; ++k) sum += flen[rr * F + k];
+    const uint32_t incl = group_prefix(sum, lg, j);
+    const uint32_t total = __shfl(incl, (int)(lane_id() | (gsz - 1u)), 64);
+    if (act) {
+      uint32_t at = incl - sum;
+      for (uint32_t k = k0; k < k1; ++k) {
+        const uint32_t n = flen[rr * F + k];
+        flen[rr * F + k] = at;
+        at += n;
+      }
+      if (j == 0) s_len[rr] = total;
+    }
+  }
+  __syncthreads();
+  if (!WRITE) {
+    if (tid < nb) {
+      const bool kept = !s_drop[tid];
+      C.lens[g0 + tid] = kept ? s_len[tid] : 0u;
+      C.lens[C.n_records + g0 + tid] = kept ? 1u : 0u;
+    }
+    return;
+  }
+  if (tid < nb && !s_drop[tid]) {
+    const uint64_t at = C.base[g0 + tid];
+    s_base[tid] = at;
+    C.out_off[C.base[C.n_records + g0 + tid]] = at;
+  }
+  __syncthreads();
+  for (uint32_t r = tid >> 6; r < nb; r += kCleanThreads / 64u) {
+    if (s_drop[r]) continue;
+    for (uint32_t k = tid & 63u; k < F; k += 64u) {
+      const uint32_t at = flen[r * F + k];
+      const uint32_t n = (k + 1u < F ? flen[r * F + k + 1u] : s_len[r]) - at - 1u;
+      const uint32_t src = fsrc[r * F + k];
+      uint8_t* dst = C.out + s_base[r] + at;
+      if (src & kSrcConst) {
+        const uint8_t* from = C.args + (src & ~kSrcConst);
+        for (uint32_t i = 0; i < n; ++i) dst[i] = from[i];
+      } else {
+        const uint8_t* from = raw + src;
+        for (uint32_t i = 0; i < n; ++i) dst[i] = from[i];
+      }
+      dst[n] = k + 1u < F ? '\t' : '\n';
+    }
+  }
 }
 
 uint64_t up256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
@@ -340,16 +561,40 @@ fbx_status fbx_clean_run(fbx_clean* clean, const uint8_t* d_raw, uint64_t raw_le
   C.base = reinterpret_cast<const uint64_t*>(sc + L.base);
   C.total = total;
   C.out = d_out; C.out_cap = out_cap; C.out_off = d_out_off; C.ctrl = ctrl;
-  const uint32_t blocks = static_cast<uint32_t>((n_records + kBlock - 1) / kBlock);
+  // Tiles: as many records as usually fit the text section with room to spare, their tables within the
+  // budget; the three sections stay under the 64 KiB a workgroup gets without asking for more.
+  constexpr uint32_t kTextMax = 24576, kTableMax = 32768;
+  const uint64_t mean = n_records ? raw_len / n_records + 1 : 1;
+  const uint64_t F = clean->n_fields;
+  const uint64_t row_stride = (F + 2 + 7) & ~uint64_t(7);
+  auto tables = [&](uint64_t T) { return T * (row_stride * 2 + F * 8); };
+  uint32_t log2T = 6;
+  while (log2T && ((mean << log2T) * 5 / 4 > kTextMax || tables(1ull << log2T) > kTableMax)) --log2T;
+  const bool tiles = tables(1ull << log2T) <= kTableMax;
+  uint32_t lds = 0;
+  if (tiles) {
+    const uint64_t T = 1ull << log2T;
+    C.log2T = log2T;
+    C.raw_cap = static_cast<uint32_t>(std::min<uint64_t>(kTextMax, std::max<uint64_t>(4096, (T * mean * 3 / 2 + 64 + 15) & ~uint64_t(15))));
+    C.row_stride = static_cast<uint32_t>(row_stride);
+    C.o_rows = kCleanRawPad + C.raw_cap + 16;  // (the splitter reads whole 16-byte chunks: one more behind the text)
+    C.o_len = static_cast<uint32_t>(C.o_rows + T * row_stride * 2);
+    C.o_src = static_cast<uint32_t>(C.o_len + T * F * 4);
+    lds = static_cast<uint32_t>(C.o_src + T * F * 4);
+  }
+  const uint32_t blocks = tiles ? static_cast<uint32_t>((n_records + (1ull << log2T) - 1) >> log2T)
+                                : static_cast<uint32_t>((n_records + kBlock - 1) / kBlock);
   if (n_records) {
-    hipLaunchKernelGGL(k_clean_measure, dim3(blocks), dim3(kBlock), 0, st, C);
+    if (tiles) hipLaunchKernelGGL(k_clean_tile<false>, dim3(blocks), dim3(kCleanThreads), lds, st, C);
+    else hipLaunchKernelGGL(k_clean_measure, dim3(blocks), dim3(kBlock), 0, st, C);
     e = hipGetLastError();
     if (e == hipSuccess)
       e = launch_scan(C.lens, reinterpret_cast<uint64_t*>(sc + L.base), total, reinterpret_cast<uint64_t*>(sc + L.part), 2,
                       static_cast<uint32_t>(n_records), ctrl, st);
     if (e != hipSuccess) return hip_failed(e, "measuring and placing records");
   }
-  hipLaunchKernelGGL(k_clean_write, dim3(std::max(blocks, 1u)), dim3(kBlock), 0, st, C);
+  if (tiles) hipLaunchKernelGGL(k_clean_tile<true>, dim3(std::max(blocks, 1u)), dim3(kCleanThreads), lds, st, C);
+  else hipLaunchKernelGGL(k_clean_write, dim3(std::max(blocks, 1u)), dim3(kBlock), 0, st, C);
   e = hipGetLastError();
   if (e != hipSuccess) return hip_failed(e, "writing records");
   struct { Ctrl c; uint8_t pad[256 - sizeof(Ctrl)]; uint64_t total[2]; } back;

@@ -57,6 +57,45 @@ def test_clean_matches_the_oracle(seed):
     assert bool((d_out[res.out_len:] == 0x21).all()), "written beyond the cleaned text"
 
 
+def _wide_case(rng, F, n, long_every=0, n_ops=12, width=10, keep_all=False):
+    """n records of about F fields (some fewer, some more) of 0..width bytes, operators on random fields;
+    every long_every-th record holds one field of 30 to 70 KB."""
+    lines = ["fbxclean 1", f"fields {F}"]
+    for o in range(n_ops):
+        kind = "keep" if o == n_ops // 2 else rng.choice(["fill", "fill", "key"])  # (one filter: more would drop nearly every record)
+        arg = "".join(rng.choice("abk") for _ in range(rng.randint(0 if kind != "fill" else 1, {"fill": 9, "key": 2, "keep": 0 if keep_all else 1}[kind]))).encode().hex()
+        lines.append(f"{kind} field={rng.randrange(F)} {dict(fill='value', key='name', keep='prefix')[kind]}={arg}")
+    field = lambda: "".join(rng.choice("abc:;k") for _ in range(rng.randint(0, width)))
+    recs = []
+    for i in range(n):
+        fields = [field() for _ in range(F + rng.choice([0, 0, 0, 0, -1, 1, -F // 2]))]
+        if long_every and i % long_every == long_every - 1 and fields:
+            fields[rng.randrange(len(fields))] = "".join(rng.choice("ab;:k") for _ in range(64)) * rng.randint(470, 1100)
+        recs.append(("\t".join(fields) + ("\n" if rng.random() < 0.8 else "")).encode())
+    return "\n".join(lines) + "\n", recs
+
+
+@pytest.mark.parametrize("F,n,long_every,n_ops,width", [
+    (130, 3000, 0, 40, 10),      # tiles of 16 records, two turns of a wavefront per record
+    (130, 3001, 0, 40, 10),      # the same with a filter that keeps every record
+    (100, 2500, 97, 30, 8),      # now and then a tile whose text does not fit the section: read in place
+    (1, 9000, 0, 2, 6),          # tiles of 64 short records
+    (7, 700, 5, 6, 300),         # long fields: few records per tile, many tiles read in place
+    (5000, 24, 0, 50, 3),        # more fields than the tables in LDS hold: one record per thread
+])
+def test_clean_tiles_of_every_shape(F, n, long_every, n_ops, width):
+    rng = random.Random(F * 1000 + n)
+    spec, recs = _wide_case(rng, F, n, long_every, n_ops, width, keep_all=n % 2 == 1)
+    raw, off = _cat(recs)
+    want_raw, want_off = C.clean(spec, raw, off)
+    assert 0 < len(want_off) - 1, "the case keeps no record"
+    res, d_out, d_out_off = _gpu_clean(spec, raw, off, out_cap=want_raw.size + 1000, misalign=n % 5)
+    assert res.n_kept == len(want_off) - 1 and res.out_len == want_raw.size
+    assert np.array_equal(d_out_off[:res.n_kept + 1].cpu().numpy().view(np.uint64), want_off)
+    assert np.array_equal(d_out[:res.out_len].cpu().numpy(), want_raw)
+    assert bool((d_out[res.out_len:] == 0x21).all()), "written beyond the cleaned text"
+
+
 def test_clean_edge_cases_and_errors():
     import torch
     recs = [b"ann\tage:3;city:rome;x:1\tok1\t5\n", b"\tcity:;age:4\tokay\t\n", b"bob\tage:3\tok\t1", b"cy\tcity:oslo\tnot ok\t2\n",
