@@ -296,6 +296,7 @@ fbx_status fbx_plan_kernel_source(const fbx_plan* plan, uint64_t raw_len, uint64
   Q.n_ops = static_cast<uint32_t>(h.ops.size()); Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged;
   Q.n_rnr = h.n_derive;
   Q.rnr_words = static_cast<uint32_t>(h.derive_tab.size());
+  Q.alias_at = h.alias_at; Q.n_alias = h.n_alias;
   Q.n_lists = static_cast<uint32_t>(h.tile_list_begin.size()) - 1u;
   Q.aux_bytes = static_cast<uint32_t>(h.aux.size());
   Q.n_fields = h.n_fields; Q.n_stage = h.n_stage;
@@ -509,6 +510,7 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
       Q.n_ops = n_ops; Q.n_layers = h.n_layers; Q.n_ragged = h.n_ragged;
       Q.n_rnr = h.n_derive;
       Q.rnr_words = static_cast<uint32_t>(h.derive_tab.size());
+      Q.alias_at = h.alias_at; Q.n_alias = h.n_alias;
       Q.n_lists = static_cast<uint32_t>(h.tile_list_begin.size()) - 1u;
       Q.aux_bytes = static_cast<uint32_t>(h.aux.size());
 
@@ -620,11 +622,12 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
   // Ragged arrays can be sized from what the last call produced (plus a margin): then the
   // counting launch is skipped.  A batch that does not fit its arrays, or a tile that needs
   // several passes, sends the call back to the exact sequence.
-  // (every tile reads 512 bytes of placement words per ragged operator: only worth it when that is
+  // (every tile reads 512 bytes of placement words per ragged operator that is placed by look-back,
+  // which those whose counts follow from another operator's are not: only worth it when that is
   // little next to the tile's own text)
   bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records &&
              ws_bytes > plan->margin_failed_ws &&
-             uint64_t(h.n_ragged) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T;
+             uint64_t(h.n_ragged - h.n_alias) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T;
   if (one) {
     plan->cap_host.resize(h.n_ragged);
     for (uint32_t r = 0; r < h.n_ragged; ++r) {

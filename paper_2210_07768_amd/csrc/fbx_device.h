@@ -64,6 +64,8 @@ struct TileParams {
   uint64_t* row_actual;        // [n_ragged] signs actually produced (mode 2)
   uint32_t n_ops, n_layers, n_ragged, n_rnr, n_lists, aux_bytes;  // (n_rnr: operators in rnr)
   uint32_t rnr_words;   // 32-bit words of the rnr table
+  uint32_t alias_at;    // word of the rnr table at which the rows' (parent, scale, add) triples start
+  uint32_t n_alias;     // ragged rows whose sign counts follow from another row's (PlanHost::n_alias)
   uint32_t n_mh;        // multi-valued hashes: the first n_mh entries of the ragged root list
   uint32_t n_split;     // multi-valued root operators of any kind: the first n_split entries of that list
   uint32_t n_gen;       // list operators of layers >= 2 (crosses and concats that are not computed along with their input)
@@ -101,7 +103,7 @@ struct UnorderedParams {
 // The fields of TileParams that the plan and the tile size fix (all but addresses, sizes of
 // the batch and tuning switches): a kernel compiled for one plan has them as literals.
 #define FBX_TILE_FIXED_FIELDS(X)                                                                                     \
-  X(n_ops) X(n_layers) X(n_ragged) X(n_rnr) X(n_lists) X(aux_bytes) X(rnr_words) X(n_mh) X(n_split) X(n_gen) X(n_fields) \
+  X(n_ops) X(n_layers) X(n_ragged) X(n_rnr) X(n_lists) X(aux_bytes) X(rnr_words) X(alias_at) X(n_alias) X(n_mh) X(n_split) X(n_gen) X(n_fields) \
   X(n_stage) X(log2T) X(raw_cap) X(row_stride) X(o_off) X(o_rs) X(o_re) X(o_rows) X(o_raw) X(o_stage) X(o_cnt)     \
   X(o_start) X(o_run) X(o_base) X(o_prog) X(o_lbeg) X(o_rnr) X(o_aux) X(o_tot) X(o_ioff) X(o_ctab) X(o_cap)         \
   X(o_gfirst) X(o_gtot) X(item_cap) X(lds_bytes)

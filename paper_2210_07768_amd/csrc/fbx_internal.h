@@ -145,12 +145,14 @@ struct PlanHost {
   // OpDesc::fuse): its position in tile_lists, grouped by hash.
   std::vector<uint32_t> derive_tab;
   uint32_t n_derive = 0;                  // operators in derive_tab
+  uint32_t alias_at = 0, n_alias = 0;     // derive_tab[alias_at + 3 * row ..]: (parent row or kNoAlias, scale, add); rows that have a parent
 };
 
 // Work lists of the tile kernel.  Layer 1 has four lists; TL_FUSED holds the crosses that
 // the lanes of a multi-valued hash compute along with its items; every later layer l
 // has two, TL_LAYER + 2 * (l - 2) (crosses of two single signs) and the next
 // one (every other cross or concat).
+constexpr uint32_t kNoAlias = 0xffffffffu;  // a ragged row whose sign counts follow from no other row's (PlanHost::alias_at)
 enum TileList : uint32_t { TL_HASH1 = 0, TL_BUCKET1 = 1, TL_RAGROOT = 2, TL_NGRAM = 3, TL_FUSED = 4, TL_LAYER = 5 };
 
 // Returns FBX_OK or FBX_E_SPEC (message in err).

@@ -437,6 +437,39 @@ fbx_status parse_plan(const char* spec, size_t len, PlanHost& plan, std::string&
       }
       dh.fuse = first | ((n_fused - first) << 16);
     }
+    // Ragged operators of later layers whose count per record is scale * (count of an earlier ragged
+    // operator) + add, whatever the record: a cross with a fixed-arity input, a concat with one, a concat
+    // of two such operators over the same one.  Their signs before any tile follow from that operator's,
+    // so the one-launch placement need not look back for them.  Three words per ragged row
+    // (parent row or kNoAlias, scale, add) behind the rest of the table.
+    plan.alias_at = static_cast<uint32_t>(plan.derive_tab.size());
+    std::vector<uint32_t> alias(3u * plan.n_ragged, 0u);
+    for (uint32_t row = 0; row < plan.n_ragged; ++row) alias[3u * row] = kNoAlias;
+    for (uint32_t e = 0; e < plan.n_derive; ++e) {
+      const uint32_t* d = &plan.derive_tab[hw + 4u * e];
+      struct Lin { bool ok; uint32_t parent; uint64_t scale, add; };  // count = scale * count(parent) + add; parent kNoAlias: a constant
+      auto lin = [&](uint32_t src) -> Lin {
+        if (src >> 31) return {true, kNoAlias, 0, src & 0x7fffffffu};
+        if (alias[3u * src] != kNoAlias) return {true, alias[3u * src], alias[3u * src + 1], alias[3u * src + 2]};
+        return {true, src, 1, 0};
+      };
+      const Lin a = lin(d[1]), b = lin(d[2]);
+      Lin r{false, kNoAlias, 0, 0};
+      if (d[3] == 0u) {  // cross: the counts multiply
+        if (a.parent == kNoAlias) r = {true, b.parent, b.scale * a.add, b.add * a.add};
+        else if (b.parent == kNoAlias) r = {true, a.parent, a.scale * b.add, a.add * b.add};
+      } else {           // concat: the counts add
+        if (a.parent == kNoAlias || b.parent == kNoAlias || a.parent == b.parent)
+          r = {true, a.parent == kNoAlias ? b.parent : a.parent, a.scale + b.scale, a.add + b.add};
+      }
+      if (r.ok && r.parent != kNoAlias && r.scale <= 0xffffffffull && r.add <= 0xffffffffull) {
+        alias[3u * d[0]] = r.parent;
+        alias[3u * d[0] + 1] = static_cast<uint32_t>(r.scale);
+        alias[3u * d[0] + 2] = static_cast<uint32_t>(r.add);
+        ++plan.n_alias;
+      }
+    }
+    plan.derive_tab.insert(plan.derive_tab.end(), alias.begin(), alias.end());
   }
   return FBX_OK;
 }

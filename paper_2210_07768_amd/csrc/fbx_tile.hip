@@ -192,6 +192,13 @@ __device__ __forceinline__ Sh views(const TileParams& P) {
 
 // ------------------------------------------------------------ byte sources
 // Where a lane reads record bytes from.  Positions are 32-bit.
+// One-launch mode: true for a ragged row whose signs before a tile follow from another row's
+// (the plan's table of such rows: PlanHost::alias_at); such a row publishes nothing and is placed
+// along with the row it follows.
+__device__ __forceinline__ bool row_follows(const TileParams& P, const Sh& sh, uint32_t row) {
+  return P.n_alias != 0u && sh.rnr[P.alias_at + 3u * row] != kNoAlias;
+}
+
 struct LdsSrc {
   static constexpr bool kTable = true;  // positions fit the 16-bit comma table
   const uint8_t* raw8;
@@ -846,7 +853,7 @@ struct Pass {
       if (r == T - 1u) {
         sh.run[row] = before + incl;
         sh.tot[row] = incl;
-        if (lb_tile != kNoRow)  // one-launch mode: later tiles may need it at once
+        if (lb_tile != kNoRow && !row_follows(P, sh, row))  // one-launch mode: later tiles may need it at once
           lb_store(P.lb_state + (uint64_t)row * P.n_tiles + lb_tile, kLbAggregate | incl);
       }
     }
@@ -1298,7 +1305,24 @@ __device__ __forceinline__ bool lb_place_row(const TileParams& P, const Sh& sh, 
     upper -= 64u;  // all counts: look further back (upper >= 64 here, else lane `upper` had stopped the window)
     spins = 0;
   }
-  if (!abort && excl + agg > sh.cap[row]) {  // the array was sized too small: nothing may be written
+  bool small = !abort && excl + agg > sh.cap[row];  // an array was sized too small: nothing may be written
+  if (P.n_alias && !abort) {
+    // the rows that follow this one: scale * (its signs before the tile) + add * (records before the tile)
+    for (uint32_t c0 = 0; c0 < P.n_ragged; c0 += 64u) {
+      const uint32_t c = c0 + lane;
+      if (c >= P.n_ragged) continue;
+      const uint32_t* a = sh.rnr + P.alias_at + 3u * c;
+      if (a[0] != row) continue;
+      const uint64_t before = (uint64_t)a[1] * excl + (uint64_t)a[2] * ((uint64_t)tile << P.log2T);
+      if (__umul64hi((uint64_t)a[1], excl) != 0ull || before + sh.tot[c] > sh.cap[c]) {
+        small = true;
+      } else {
+        sh.base[c] = before;
+        if (tile + 1u == P.n_tiles) gptr(P.row_actual)[c] = before + sh.tot[c];
+      }
+    }
+  }
+  if (__ballot(small)) {
     if (lane == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
     abort = true;
   }
@@ -1413,7 +1437,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // One-launch mode: the words of the tiles before this one (for the wavefront's first ragged
   // operator) are requested now, so that they arrive while the single crosses run.
   uint64_t early = kLbPrefix;
-  if (MODE == 2 && wave < P.n_ragged) early = lb_window(P, wave, tile);
+  if (MODE == 2 && wave < P.n_ragged && !row_follows(P, sh, wave)) early = lb_window(P, wave, tile);
   // ---- the single crosses of every later layer: they only read signs kept on chip
   for (uint32_t layer = 2; layer <= P.n_layers; ++layer) {
     __syncthreads();  // the layer barrier: every sign this layer reads is in place
@@ -1433,19 +1457,19 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // ---- one-launch mode: the tile's bases come from the tiles before it.  The count went out
   // long ago, so the tiles before this one have had time to count.
   if (MODE == 2) {
-    if (wave < P.n_ragged && !lb_place_row(P, sh, tile, wave, early) && lane == 0) s_good = 0u;
+    if (wave < P.n_ragged && !row_follows(P, sh, wave) && !lb_place_row(P, sh, tile, wave, early) && lane == 0) s_good = 0u;
     constexpr uint32_t kRows = 4;  // further operators: a wavefront looks back for several at the same time
     for (uint32_t row0 = wave + kWaves; row0 < P.n_ragged; row0 += kRows * kWaves) {
       uint64_t v[kRows];
 #pragma unroll
       for (uint32_t k = 0; k < kRows; ++k) {
         const uint32_t row = row0 + k * kWaves;
-        v[k] = row < P.n_ragged ? lb_window(P, row, tile) : kLbPrefix;
+        v[k] = row < P.n_ragged && !row_follows(P, sh, row) ? lb_window(P, row, tile) : kLbPrefix;
       }
 #pragma unroll
       for (uint32_t k = 0; k < kRows; ++k) {
         const uint32_t row = row0 + k * kWaves;
-        if (row < P.n_ragged && !lb_place_row(P, sh, tile, row, v[k]) && lane == 0) s_good = 0u;
+        if (row < P.n_ragged && !row_follows(P, sh, row) && !lb_place_row(P, sh, tile, row, v[k]) && lane == 0) s_good = 0u;
       }
     }
     __syncthreads();

@@ -82,3 +82,23 @@ def random_dag(rng, n_roots, n_rest):
         ids.append(f"n{i}")
         deps[f"n{i}"] = (a, b)
     return "\n".join(lines) + "\n", ids, deps
+
+
+# Ragged operators of later layers whose count per record follows from one earlier ragged operator's
+# (eight of them) and two that do not (a product of two lists, a concat over two different lists).
+FOLLOW_SPEC = ("fbx 1\nfields 4\n"
+        "op s0 hash slot=0 seed=1 emit=1 field=0 multi=0\n"
+        "op s1 hash slot=1 seed=2 emit=1 field=1 multi=0\n"
+        "op m hash slot=2 seed=3 emit=1 field=2 multi=1\n"
+        "op k hash slot=3 seed=4 emit=1 field=3 multi=1\n"
+        "op two concat slot=4 emit=1 a=s0 b=s1\n"            # fixed arity 2
+        "op x1 cross slot=5 seed=5 emit=1 a=s0 b=m\n"        # 1 * count(m)
+        "op c1 concat slot=6 emit=1 a=m b=s1\n"              # count(m) + 1
+        "op mk cross slot=7 seed=6 emit=1 a=m b=k\n"         # a product: placed by its own look-back
+        "op x2 cross slot=8 seed=7 emit=1 a=two b=m\n"       # 2 * count(m)
+        "op c2 concat slot=9 emit=1 a=two b=k\n"             # count(k) + 2
+        "op c3 concat slot=10 emit=1 a=x2 b=c1\n"            # 3 * count(m) + 1
+        "op x3 cross slot=11 seed=8 emit=1 a=c1 b=two\n"     # 2 * count(m) + 2
+        "op c4 concat slot=12 emit=1 a=c3 b=c2\n"            # over two different operators: its own look-back
+        "op x4 cross slot=13 seed=9 emit=0 a=s1 b=c3\n"      # 3 * count(m) + 1, not emitted, read by c5
+        "op c5 concat slot=14 emit=1 a=x4 b=x3\n")           # 5 * count(m) + 3

@@ -8,7 +8,7 @@ import pytest
 from oracle import fbx_oracle as O
 from paper_2210_07768_amd import binding as B
 from paper_2210_07768_amd import workloads as W
-from helpers import FRAMING_RECORDS, FRAMING_SPEC, random_dag
+from helpers import FOLLOW_SPEC, FRAMING_RECORDS, FRAMING_SPEC, random_dag
 from gpu_harness import assert_same, check, check_window, device_workload, run_gpu, to_device
 from oracle_ranges import check_every_sign, extract_parallel
 
@@ -231,6 +231,40 @@ def test_one_launch_mode_with_more_tiles_than_workgroups(cfg, n, compile_for_pla
             assert np.array_equal(go, oo), f"{w.name} call {call} slot {s}: offsets differ"
             assert np.array_equal(gv, ov), f"{w.name} call {call} slot {s}: signs differ"
     assert (plan.compiled()[0] >= 2) == bool(compile_for_plan)
+    plan.close()
+
+
+@pytest.mark.parametrize("tile_log2,compile_for_plan,grid_limit", [(5, 0, 0), (6, 0, 8), (5, 1, 0)])
+def test_one_launch_mode_with_rows_that_follow_other_rows(tile_log2, compile_for_plan, grid_limit):
+    """Ragged operators whose count per record is a multiple of another ragged operator's plus a
+    constant (a cross or a concat with a fixed-arity input, a concat of two such operators over the
+    same one, operators over those) are placed from that operator's look-back result in the
+    one-launch sequence; a cross of two lists is not.  A first call, then two that place by
+    look-back, over many tiles, every sign against the oracle."""
+    from gpu_harness import expand
+    rng = random.Random(4242 + tile_log2)
+    n = 20_000  # (hundreds of tiles: the look-back moves past its first window)
+    word = lambda: "".join(rng.choice("abcdefg") for _ in range(rng.randint(0, 40)))
+    recs = [("\t".join([word(), word(), ",".join(word() for _ in range(rng.randint(1, 6))),
+                         ",".join(word() for _ in range(rng.randint(1, 3)))]) + "\n").encode() for _ in range(n)]
+    spec = FOLLOW_SPEC
+    raw, off = _cat(recs)
+    raw = np.frombuffer(raw, np.uint8)
+    want = O.extract(spec, raw, off)
+    plan = B.Plan(spec)
+    plan.set_option("tile_log2", tile_log2)
+    plan.set_option("compile", compile_for_plan)
+    if grid_limit:
+        plan.set_option("grid_limit", grid_limit)
+    d_raw, d_off = to_device(raw, off)
+    res, ws = B.extract_with_retry(plan, d_raw, d_off, slack=1.05)
+    for call in range(3):
+        if call:
+            ws.fill_(0x5A)
+            plan.set_workspace(ws)
+            res = plan.extract(d_raw, d_off)
+            assert res.tile_launches == 1, res.note
+        assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, f"call {call}")
     plan.close()
 
 

@@ -176,3 +176,18 @@ def test_fixed_arity_beyond_the_sign_limit_is_a_spec_error():
     with pytest.raises(B.FbxError) as e:
         B.Plan(spec(26))
     assert e.value.status == B.E_SPEC and "2^26" in str(e.value)
+
+
+def test_rows_that_follow_other_rows_are_found():
+    """The planner marks ragged operators whose count per record is scale * (an earlier ragged operator's) + add:
+    the kernel text compiled for the plan carries their number."""
+    import re
+    from helpers import FOLLOW_SPEC
+    plan = B.Plan(FOLLOW_SPEC)
+    text = plan.kernel_source(100_000, 1000, 2)
+    assert re.search(r"P\.n_ragged = 12u;", text) and re.search(r"P\.n_alias = 8u;", text)
+    plan.close()
+    w = W.get(5, 1000)
+    plan = B.Plan(w.spec)
+    assert re.search(r"P\.n_alias = 4u;", plan.kernel_source(787_000, 1000, 2))  # the four crosses of a single sign with a list
+    plan.close()
