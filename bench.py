@@ -55,14 +55,15 @@ def measured_counters(workload, records, launch, compile_for_plan):
     profiles/ (lines that start with 'bench-key:'), or {} when none was taken at these sources."""
     want = {"workload": workload, "records": str(records), "launch": launch, "compile": str(compile_for_plan),
             "sources": source_digest()}
+    found = {}
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
         for line in open(path):
             if not line.startswith("bench-key:"):
                 continue
             kv = dict(item.split("=", 1) for item in line[len("bench-key:"):].split())
             if all(kv.get(k) == v for k, v in want.items()):
-                return {k: int(v) for k, v in kv.items() if k not in want}
-    return {}
+                found.update({k: int(v) for k, v in kv.items() if k not in want})
+    return found
 
 
 def build_inputs(w, first_record=0, chunk_records=500_000, tag=""):
