@@ -166,11 +166,14 @@ def side_stage(args, w, B, torch):
         plan.set_option("one_launch", 1)
         plan.extract(d_raw, d_off)
         t_one = timed(lambda: plan.extract(d_raw, d_off))
+        plan.set_option("placement", 1)
+        t_arr = timed(lambda: plan.extract(d_raw, d_off))
         alg = d_raw.numel() + 8 * (R + 1) + 8 * n_signs + 8 * (R + 1)
         print(json.dumps({"stage": "unordered", "workload": w.name, "records": R, "operator": line, "signs": int(n_signs),
-                          "ms": {"in_kernel_allocation_unordered": t_un, "ordered_count_scan_write": t_cw, "ordered_one_launch_look_back": t_one},
+                          "ms": {"in_kernel_allocation_unordered": t_un, "ordered_count_scan_write": t_cw, "ordered_one_launch_look_back": t_one,
+                                 "tile_kernel_arrival_order": t_arr},
                           "algorithmic_GBps": {"in_kernel_allocation_unordered": alg / t_un / 1e6, "ordered_count_scan_write": alg / t_cw / 1e6,
-                                               "ordered_one_launch_look_back": alg / t_one / 1e6},
+                                               "ordered_one_launch_look_back": alg / t_one / 1e6, "tile_kernel_arrival_order": alg / t_arr / 1e6},
                           "note": "the operator's field is one of many: every variant reads the whole text once (twice with a counting launch)"}))
         plan.close()
         return
@@ -207,6 +210,7 @@ def main():
     ap.add_argument("--one-batch", action="store_true",
                     help="time every call on the batch the sizes were learned on (what profiles of one kernel use)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-arrival", action="store_true", help="skip the calls with ragged slots placed in arrival order")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a device-to-device copy of this many MiB (3 times) and exit: the known "
                          "traffic against which FETCH_SIZE / WRITE_SIZE readings of rocprofv3 are scaled")
@@ -409,6 +413,32 @@ def main():
         notes.append(res.note)
     if notes:
         out["note"] = "; ".join(dict.fromkeys(notes))
+    # Beside the line: the same calls with the tiles of a ragged slot placed in the order in which they
+    # arrive (plan option placement=1: one atomic add per slot and tile instead of the look-back; each
+    # record's lists are the same, the arrays are no longer in record order).  Not the benchmark's
+    # value: the path's result is the record-ordered CSR.
+    has_ragged = any(s_.offsets is not None for s_ in res.slots.values())
+    if args.fused and res.tile_launches and has_ragged and not args.no_arrival and not any(kv.startswith("placement=") for kv in args.opt):
+        plan.set_option("placement", 1)
+        for i in range(2):  # (compiles the kernel of that mode)
+            plan.extract(*batches[(first_timed + i) % len(batches)])
+        a_ms, a_kernel, a_res = [], [], None
+        for i in range(args.steps):
+            d_raw, d_off = batches[(first_timed + i) % len(batches)]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            a_res = plan.extract(d_raw, d_off)
+            e1.record()
+            torch.cuda.synchronize()
+            a_ms.append(e0.elapsed_time(e1))
+            a_kernel.append(plan.kernel_ms(101))
+        k_ms = float(np.mean(a_kernel))
+        out["arrival_order"] = {"ms_per_step_median_hip_events": statistics.median(a_ms), "tile_kernel_ms": round(k_ms, 4),
+                                "records_per_s": R / (statistics.median(a_ms) * 1e-3),
+                                "tile_kernel_frac_of_hbm_peak": alg_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                "tile_launches": a_res.tile_launches, "arrival_tile_records": a_res.arrival_tile_records,
+                                "note": "plan option placement=1; ragged arrays hold the tiles' shares in arrival order"}
+        plan.set_option("placement", 0)
     if not args.no_cpu:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(w)

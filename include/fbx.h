@@ -48,6 +48,8 @@ typedef struct {
   const uint64_t* values;  /* DEVICE, n_values entries, record order, token order inside     */
   const uint64_t* offsets; /* DEVICE, n_records + 1 entries, offsets[0] = 0,
                               offsets[n_records] = n_values; NULL for fixed-arity slots      */
+  const uint64_t* tile_ends; /* DEVICE; NULL unless fbx_result.arrival_tile_records != 0 and the
+                              slot is ragged: see there                                      */
 } fbx_slot_view;
 
 typedef struct {
@@ -62,7 +64,16 @@ typedef struct {
   uint32_t tile_launches;       /* launches of the tile kernel this call took: 2 = counting +
                                    writing, 1 = one launch (no ragged slots, or ragged arrays
                                    sized from the previous call), 0 = the walk kernels ran    */
-  uint32_t reserved;
+  uint32_t arrival_tile_records; /* 0: ragged slots are in record order (offsets as above).
+                                   k > 0 (plan option "placement" = 1, and the call took the one-launch
+                                   sequence): records were placed in tiles of k, tiles in the order in
+                                   which they arrived.  Record r of a ragged slot then owns
+                                   values[offsets[r], end) with end = offsets[r + 1], except for the last
+                                   record of a tile (r % k == k - 1), whose end = tile_ends[r / k], and
+                                   the batch's last record, whose end = offsets[n_records].  The tiles'
+                                   shares [tile_ends[t] - signs of tile t, tile_ends[t]) are disjoint
+                                   and cover [0, n_values); offsets are not monotone over tiles.
+                                   Fixed-arity slots are in record order always.                     */
 } fbx_result;
 
 /*
@@ -188,6 +199,12 @@ fbx_status fbx_plan_info(const fbx_plan* plan, uint32_t* n_ops, uint32_t* n_laye
  *                  launches once per layer, which makes the two comparable)
  *   "one_launch"   1: later calls skip the counting launch as described at fbx_extract
  *                  (default); 0: always count first
+ *   "placement"    0: ragged slots in record order (default).  1: in a call that skips the counting
+ *                  launch every tile of records takes its share of a ragged slot with one atomic
+ *                  add on the slot's running total (Section 5, Algorithm 1, a tile's share as the
+ *                  block) instead of waiting for the tiles before it: tiles land in the order in
+ *                  which they arrive (fbx_result.arrival_tile_records says so and how to read it),
+ *                  and plans with many ragged operators skip the counting launch too
  *   "tile_log2"    -1: records per tile chosen per call (default); 0..6: 2^value records
  *   "raw_cap"      0: bytes of text a workgroup stages at a time chosen per call (default);
  *                  64..65000: that many

@@ -35,7 +35,8 @@ class FbxError(RuntimeError):
 
 class SlotView(ctypes.Structure):
     _fields_ = [("slot_id", ctypes.c_uint32), ("fixed_arity", ctypes.c_uint32),
-                ("n_values", ctypes.c_uint64), ("values", ctypes.c_void_p), ("offsets", ctypes.c_void_p)]
+                ("n_values", ctypes.c_uint64), ("values", ctypes.c_void_p), ("offsets", ctypes.c_void_p),
+                ("tile_ends", ctypes.c_void_p)]
 
 
 class Result(ctypes.Structure):
@@ -43,7 +44,7 @@ class Result(ctypes.Structure):
                 ("n_malformed_numeric", ctypes.c_uint64), ("arena_high_water", ctypes.c_uint64),
                 ("n_slots", ctypes.c_uint32), ("n_layers", ctypes.c_uint32),
                 ("slots", ctypes.POINTER(SlotView)),
-                ("tile_launches", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("tile_launches", ctypes.c_uint32), ("arrival_tile_records", ctypes.c_uint32)]
 
 
 class CleanResult(ctypes.Structure):
@@ -125,10 +126,18 @@ class Slot:
     """One emitted slot of a result; ``values`` / ``offsets`` are torch views of the workspace
     (made when first asked for: a result with hundreds of slots costs nothing to hand over)."""
 
-    def __init__(self, slot_id, fixed_arity, n_values, ws64, values_at, offsets_at, n_offsets):
+    def __init__(self, slot_id, fixed_arity, n_values, ws64, values_at, offsets_at, n_offsets, tile_ends_at=None, n_tiles=0):
         self.slot_id, self.fixed_arity, self.n_values = slot_id, fixed_arity, n_values
         self._ws64, self._values_at, self._offsets_at, self._n_offsets = ws64, values_at, offsets_at, n_offsets
+        self._tile_ends_at, self._n_tiles = tile_ends_at, n_tiles
         self._values = self._offsets = None
+
+    @property
+    def tile_ends(self):
+        """Arrival order only (ExtractResult.arrival_tile_records != 0, ragged slot): where each tile's share ends."""
+        if self._tile_ends_at is None:
+            return None
+        return self._ws64[self._tile_ends_at:self._tile_ends_at + self._n_tiles]
 
     @property
     def values(self):
@@ -157,6 +166,7 @@ class ExtractResult:
         self.arena_high_water = 0
         self.n_layers = 0
         self.tile_launches = 0
+        self.arrival_tile_records = 0   # 0: ragged slots in record order; k: tiles of k records in arrival order (fbx.h)
         self.note = ""
         self._table = None   # (bytes of the library's slot table, workspace as int64, its base address, offsets per slot)
         self._slots = None
@@ -164,12 +174,17 @@ class ExtractResult:
 
     def _build(self):
         table, ws64, base, n_offsets = self._table
+        k = self.arrival_tile_records
+        n_tiles = -(-(n_offsets - 1) // k) if k else 0
         n = len(table) // ctypes.sizeof(SlotView)
         self._slots, self._slot_ids = {}, []
         for sv in ((SlotView * n).from_buffer_copy(table) if n else ()):
             v0 = ((sv.values or base) - base) // 8
             o0 = (sv.offsets - base) // 8 if sv.offsets else None
-            self._slots[sv.slot_id] = Slot(sv.slot_id, sv.fixed_arity, sv.n_values, ws64, v0, o0, n_offsets)
+            # (the table of tile ends lies in the workspace; with the entry point that allocates nothing it does not, and no view is made)
+            inside = sv.tile_ends and base <= sv.tile_ends < base + ws64.numel() * 8
+            t0 = (sv.tile_ends - base) // 8 if inside else None
+            self._slots[sv.slot_id] = Slot(sv.slot_id, sv.fixed_arity, sv.n_values, ws64, v0, o0, n_offsets, t0, n_tiles)
             self._slot_ids.append(sv.slot_id)
 
     @property
@@ -304,6 +319,7 @@ class Plan:
         out.n_malformed_numeric, out.arena_high_water = res.n_malformed_numeric, res.arena_high_water
         out.n_layers = res.n_layers
         out.tile_launches = res.tile_launches
+        out.arrival_tile_records = res.arrival_tile_records
         out.note = lib().fbx_last_error(self._h).decode()
         # the library's slot table is overwritten by the next call: copy the plain numbers out now
         ws64 = home[: home.numel() // 8 * 8].view(torch.int64)

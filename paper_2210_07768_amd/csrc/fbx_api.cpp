@@ -53,6 +53,7 @@ struct fbx_plan {
   uint32_t grid_limit = 0;
   uint32_t spin_limit = 1u << 22;   // polls a tile of the one-launch sequence waits for an earlier tile's count
   int one_launch = 1;             // size ragged arrays from the last call and skip the counting launch
+  int placement = 0;              // one-launch sequence: 0 tiles placed in record order (look-back), 1 in the order they arrive (one atomic add each)
   int compile = 0;                // compile the tile kernel for this plan at run time (Section 4's meta-kernel)
   uint32_t tile_threads = 512;    // lanes of a workgroup of the kernels compiled for the plan
   uint32_t lane_ops = 0;          // tiles of 64 records in compiled kernels: how single-sign operators run (see fbx_tile.hip)
@@ -288,7 +289,7 @@ fbx_status fbx_plan_compiled(const fbx_plan* plan, uint32_t* n_kernels, double* 
 
 fbx_status fbx_plan_kernel_source(const fbx_plan* plan, uint64_t raw_len, uint64_t n_records, int mode, char* buf,
                                   size_t buf_len, size_t* needed) {
-  if (!plan || mode < 0 || mode > 2 || (!buf && buf_len)) return FBX_E_ARG;
+  if (!plan || mode < 0 || mode > 3 || (!buf && buf_len)) return FBX_E_ARG;
   const CallGeometry g = geometry(*plan, raw_len, n_records);
   if (!g.tile_engine) return FBX_E_ARG;  // (plans too wide for the tile kernel have no such kernel)
   TileParams Q = g.tp;
@@ -353,6 +354,9 @@ fbx_status fbx_plan_set_option(fbx_plan* plan, const char* key, int64_t value) {
   } else if (k == "tile_threads") {
     if (value != 512 && value != 1024) { plan->error = "tile_threads must be 512 or 1024"; return FBX_E_ARG; }
     plan->tile_threads = static_cast<uint32_t>(value);
+  } else if (k == "placement") {
+    if (value != 0 && value != 1) { plan->error = "placement must be 0 (record order) or 1 (arrival order)"; return FBX_E_ARG; }
+    plan->placement = static_cast<int>(value);
   } else if (k == "one_launch") {
     if (value != 0 && value != 1) { plan->error = "one_launch must be 0 or 1"; return FBX_E_ARG; }
     plan->one_launch = static_cast<int>(value);
@@ -534,9 +538,10 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
         tick(3, 0);
         FBX_LAUNCH(launch_alloc(P, Q.row_cap, ws_bytes, 0, st), "allocation kernel");
         tick(3, 1);
-        FBX_LAUNCH(launch_fill64(Q.lb_state, uint64_t(h.n_ragged) * g.n_tiles, 0, st), "look-back state");
+        if (plan->placement) FBX_LAUNCH(launch_fill64(Q.row_actual, h.n_ragged, 0, st), "running totals");
+        else FBX_LAUNCH(launch_fill64(Q.lb_state, uint64_t(h.n_ragged) * g.n_tiles, 0, st), "look-back state");
         tick(4, 0);
-        FBX_LAUNCH(tile_launch(Q, 2), "tile kernel (one launch)");
+        FBX_LAUNCH(tile_launch(Q, plan->placement ? 3 : 2), "tile kernel (one launch)");
         tick(4, 1);
         plan->tile_launch_layer.push_back(1);
       } else {
@@ -627,7 +632,7 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
   // little next to the tile's own text)
   bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records &&
              ws_bytes > plan->margin_failed_ws &&
-             uint64_t(h.n_ragged - h.n_alias) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T;
+             (plan->placement || uint64_t(h.n_ragged - h.n_alias) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T);
   if (one) {
     plan->cap_host.resize(h.n_ragged);
     for (uint32_t r = 0; r < h.n_ragged; ++r) {
@@ -695,6 +700,7 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
     plan->learned_records = n_records;
     plan->learned = true;
   }
+  const bool arrival = one && plan->placement && h.n_ragged;
   uint64_t total = 0;
   for (size_t s = 0; s < plan->emitted.size(); ++s) {
     const uint32_t i = plan->emitted[s];
@@ -705,6 +711,7 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
     v.n_values = (one && !d.arity) ? actual[d.rag_row] : y[i].n_values;
     v.values = reinterpret_cast<const uint64_t*>(reg.origin + y[i].values_off);
     v.offsets = d.arity ? nullptr : reinterpret_cast<const uint64_t*>(reg.origin + y[i].offsets_off);
+    v.tile_ends = (arrival && !d.arity) ? P.tile_base + uint64_t(d.rag_row) * g.n_tiles : nullptr;
     total += v.n_values;
   }
   out->n_records = n_records;
@@ -725,6 +732,7 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
     if (!note.empty()) plan->error += (plan->error.empty() ? "" : "; ") + note;
   }
   out->tile_launches = g.tile_engine ? (one ? 1u : (h.n_ragged ? 2u : 1u)) : 0u;
+  out->arrival_tile_records = arrival ? 1u << g.tp.log2T : 0u;
   return FBX_OK;
 }
 

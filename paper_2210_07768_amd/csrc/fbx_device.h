@@ -110,7 +110,8 @@ struct UnorderedParams {
 
 #ifndef __HIPCC_RTC__  // (the launch wrappers are host code: not for the run-time compiler)
 // mode 0: counting launch; 1: writing launch (bases from the scan over tiles);
-// 2: counting and writing in one launch (bases by look-back, arrays sized by row_cap)
+// 2: counting and writing in one launch (bases by look-back, arrays sized by row_cap);
+// 3: the same with bases by one atomic add per (ragged operator, tile) on row_actual: tiles in arrival order
 hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st);
 hipError_t launch_fill64(uint64_t* p, uint64_t n, uint64_t value, hipStream_t st);
 uint32_t tile_max_lds();  // dynamic LDS a workgroup of the tile kernel may ask for on this device

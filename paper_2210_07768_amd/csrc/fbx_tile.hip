@@ -1416,14 +1416,14 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   if (P.n_ragged) {
     const uint32_t us = ps.scan_units();
     for (uint32_t u = wave; u < us; u += kWaves) ps.scan_unit(u);
-    if (MODE == 2 && overflow) s_absurd = 1u;  // (rare: a plain flag is cheaper than a vote in every tile)
+    if (MODE >= 2 && overflow) s_absurd = 1u;  // (rare: a plain flag is cheaper than a vote in every tile)
     __syncthreads();
-    if (MODE == 2) absurd = s_absurd != 0u;
+    if (MODE >= 2) absurd = s_absurd != 0u;
     FBX_MARK(6);
     hook();
   }
-  if (MODE == 2 && absurd) {  // absurd counts: nothing of this tile may be placed (whatever it published is overwritten)
-    lb_abort_tile(P, tile);
+  if (MODE >= 2 && absurd) {  // absurd counts: nothing of this tile may be placed (whatever it published is overwritten)
+    if (MODE == 2) lb_abort_tile(P, tile);
     return;
   }
   if (!WRITE) return;
@@ -1475,6 +1475,31 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     __syncthreads();
     FBX_MARK(9);
     if (!s_good) return;  // the call fails or falls back: leave the arrays alone
+  } else if (MODE == 3) {
+    // ---- arrival order (Section 5, Algorithm 1 with the tile's share of a ragged operator as the block):
+    // one atomic add per (operator, tile) on the operator's running total; tiles land in the order
+    // in which they get here.  Where the tile's share ends goes into the table that the look-back
+    // words occupy in mode 2: a record's list ends where the next record's starts, except for a
+    // tile's last record.
+    if (wave == 0) {
+      bool small = false;
+      for (uint32_t row = lane; row < P.n_ragged; row += 64u) {
+        const uint64_t n = sh.tot[row];
+        const uint64_t at = atomicAdd(reinterpret_cast<unsigned long long*>(P.row_actual) + row, (unsigned long long)n);
+        if (at + n > sh.cap[row]) {
+          small = true;  // the array was sized too small: nothing may be written
+        } else {
+          sh.base[row] = at;
+          gptr(P.lb_state)[(uint64_t)row * P.n_tiles + tile] = at + n;
+        }
+      }
+      if (__ballot(small) && lane == 0) {
+        atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
+        s_good = 0u;
+      }
+    }
+    __syncthreads();
+    if (!s_good) return;
   } else if (P.n_mh) {
     __syncthreads();  // the item index space laid out in phase C is read by every wavefront
   }
@@ -1575,7 +1600,7 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
   copy_table(smem + P.o_lbeg, P.list_begin, (P.n_lists + 1u) * 4u);
   copy_table(smem + P.o_rnr, P.rnr, P.rnr_words * 4u);
   copy_table(smem + P.o_aux, P.aux, P.aux_bytes);
-  if (MODE == 2) copy_table(smem + P.o_cap, P.row_cap, P.n_ragged * 8u);
+  if (MODE >= 2) copy_table(smem + P.o_cap, P.row_cap, P.n_ragged * 8u);
 #ifdef FBX_TILE_PROF
   if (tid < 16) s_prof[tid] = 0;
   if (tid == 0) s_prof_last = clock64();
@@ -1680,13 +1705,13 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
     };
 
     uint32_t r0 = nrec_ok ? 0u : nrec;
-    if (MODE == 2 && nrec_ok) {
+    if (MODE >= 2 && nrec_ok) {
       // placement needs the whole tile's counts at once: a tile that takes several passes
       // (or holds a record that is read in place) sends the call back to the counting launch
       const uint32_t d0 = (uint32_t)((ok_lo + off[0]) & 15u);
       if (off[nrec] - off[0] + d0 > (uint64_t)P.raw_cap) {
         if (tid == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
-        lb_abort_tile(P, tile);
+        if (MODE == 2) lb_abort_tile(P, tile);
         r0 = nrec;
       }
     }
@@ -1774,7 +1799,7 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
   if (!WRITE) {
     if (overflow) atomicOr(&P.ctrl->err, (uint32_t)CE_OVERFLOW);
   } else {
-    if (MODE == 2 && overflow) atomicOr(&P.ctrl->err, (uint32_t)CE_OVERFLOW);
+    if (MODE >= 2 && overflow) atomicOr(&P.ctrl->err, (uint32_t)CE_OVERFLOW);
     for (int d = 32; d >= 1; d >>= 1) malformed += __shfl_xor(malformed, d, 64);
     if (lane_id() == 0 && malformed)
       atomicAdd(reinterpret_cast<unsigned long long*>(&P.ctrl->n_malformed), (unsigned long long)malformed);
@@ -1883,8 +1908,10 @@ uint32_t tile_max_lds() {
 
 hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st) {
   if (P.n_tiles == 0) return hipSuccess;
-  const void* fn = mode == 0 ? reinterpret_cast<const void*>(&k_tile<0>)
-                             : (mode == 1 ? reinterpret_cast<const void*>(&k_tile<1>) : reinterpret_cast<const void*>(&k_tile<2>));
+  const void* fn = mode == 0   ? reinterpret_cast<const void*>(&k_tile<0>)
+                   : mode == 1 ? reinterpret_cast<const void*>(&k_tile<1>)
+                   : mode == 2 ? reinterpret_cast<const void*>(&k_tile<2>)
+                               : reinterpret_cast<const void*>(&k_tile<3>);
   if (P.lds_bytes > 48u * 1024u) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds_bytes);
     if (e != hipSuccess) return e;
@@ -1901,7 +1928,8 @@ hipError_t launch_tile(const TileParams& P, int mode, hipStream_t st) {
   const uint32_t grid = std::min(P.n_tiles, capacity);
   if (mode == 0) hipLaunchKernelGGL(k_tile<0>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
   else if (mode == 1) hipLaunchKernelGGL(k_tile<1>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
-  else hipLaunchKernelGGL(k_tile<2>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
+  else if (mode == 2) hipLaunchKernelGGL(k_tile<2>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
+  else hipLaunchKernelGGL(k_tile<3>, dim3(grid), dim3(kTileThreads), P.lds_bytes, st, Q);
   return hipGetLastError();
 }
 
