@@ -27,7 +27,9 @@
 //     turned into positions by a prefix sum over the tile's records on top of
 //     the tile's base.  The base comes from a counting launch of this same
 //     kernel and a scan over tiles, or, in the one-launch mode, from the words
-//     that the tiles before this one have published (see lb_place_row).
+//     that the tiles before this one have published (see lb_place_row), or,
+//     where the caller does not need record order, from one atomic add on the
+//     operator's running total (place_by_arrival).
 //  6. Workgroups are persistent and software-pipelined: while a tile is worked
 //     on, the ticket and the record offsets of the next tile are fetched and one
 //     byte of every line of its text is touched, so that the text is on its way
@@ -1432,6 +1434,42 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
   // index space of the multi-valued hashes (needed after at least one more barrier)
   if (P.n_mh && wave == kWaves - 1) ps.item_offsets();
   if (P.n_gen && wave == kWaves - 2) ps.gen_offsets();  // (likewise: where the list operators' signs start)
+  // Arrival order (Section 5, Algorithm 1 with the tile's share of a ragged operator as the block): one
+  // atomic add per (operator, tile) on the operator's running total; tiles land in the order in which
+  // they get here.  Where the tile's share ends goes into the table that the look-back words occupy in
+  // mode 2: a record's list ends where the next record's starts, except for a tile's last record.
+  auto place_by_arrival = [&]() {  // one wavefront
+    bool small = false;
+    for (uint32_t row = lane; row < P.n_ragged; row += 64u) {
+      const uint64_t n = sh.tot[row];
+      const uint64_t at = atomicAdd(reinterpret_cast<unsigned long long*>(P.row_actual) + row, (unsigned long long)n);
+      if (at + n > sh.cap[row]) {
+        small = true;  // the array was sized too small: nothing may be written
+      } else {
+        sh.base[row] = at;
+        gptr(P.lb_state)[(uint64_t)row * P.n_tiles + tile] = at + n;
+      }
+    }
+    if (__ballot(small) && lane == 0) {
+      atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
+      s_good = 0u;
+    }
+  };
+  // Launches that know a tile's bases early (from the scan over tiles, or by arrival): the ragged root
+  // operators share a hand-out with the first layer of single crosses, long units first.
+  constexpr bool kEarlyBases = MODE == 1 || MODE == 3;
+  if (kEarlyBases && MODE == 3 && P.n_ragged && wave == 0) place_by_arrival();
+  auto ragged_root_units = [&]() -> uint32_t {
+    return (P.n_mh ? ps.item_units() : 0u) + ps.other_units() + ps.ngram_units();
+  };
+  auto ragged_root_unit = [&](uint32_t u) {
+    if (FBX_SKIP(4u)) return;
+    const uint32_t um = P.n_mh ? ps.item_units() : 0u, uo = ps.other_units();
+    if (u < uo) ps.other_unit(u);
+    else if (u < uo + um) ps.item_unit(u - uo);
+    else ps.ngram_unit(u - uo - um);
+  };
+  bool ragged_roots_done = false;
   for_units(&s_ctr[0], uh + ub, l1_unit);
   FBX_MARK(7);
   // One-launch mode: the words of the tiles before this one (for the wavefront's first ragged
@@ -1445,10 +1483,17 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     uint32_t* ctr = &s_ctr[4u + (layer & 1u)];
     if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
     const uint32_t ux = kGen ? ps.units_of(TL_LAYER + 2u * (layer - 2u)) : ps.x11_units(layer);
-    for_units(ctr, ux, [&](uint32_t u) {
+    uint32_t ur = 0;
+    if (kEarlyBases && layer == 2u && P.n_ragged) {
+      if (MODE == 3 && !s_good) return;  // the call falls back: leave the arrays alone
+      ur = ragged_root_units();
+      ragged_roots_done = true;
+    }
+    for_units(ur ? &s_ctr[3] : ctr, ur + ux, [&](uint32_t u) {
+      if (u < ur) { ragged_root_unit(u); return; }
       if (FBX_SKIP(2u)) return;
-      if constexpr (kGen) { ps.lane_x11_unit(layer, u); return; }
-      ps.x11_unit(layer, u);
+      if constexpr (kGen) { ps.lane_x11_unit(layer, u - ur); return; }
+      ps.x11_unit(layer, u - ur);
     });
   }
   FBX_MARK(8);
@@ -1475,45 +1520,14 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     __syncthreads();
     FBX_MARK(9);
     if (!s_good) return;  // the call fails or falls back: leave the arrays alone
-  } else if (MODE == 3) {
-    // ---- arrival order (Section 5, Algorithm 1 with the tile's share of a ragged operator as the block):
-    // one atomic add per (operator, tile) on the operator's running total; tiles land in the order
-    // in which they get here.  Where the tile's share ends goes into the table that the look-back
-    // words occupy in mode 2: a record's list ends where the next record's starts, except for a
-    // tile's last record.
-    if (wave == 0) {
-      bool small = false;
-      for (uint32_t row = lane; row < P.n_ragged; row += 64u) {
-        const uint64_t n = sh.tot[row];
-        const uint64_t at = atomicAdd(reinterpret_cast<unsigned long long*>(P.row_actual) + row, (unsigned long long)n);
-        if (at + n > sh.cap[row]) {
-          small = true;  // the array was sized too small: nothing may be written
-        } else {
-          sh.base[row] = at;
-          gptr(P.lb_state)[(uint64_t)row * P.n_tiles + tile] = at + n;
-        }
-      }
-      if (__ballot(small) && lane == 0) {
-        atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
-        s_good = 0u;
-      }
-    }
+  } else if (MODE == 3 && !ragged_roots_done) {  // (a plan of one layer: the bases taken before phase C are read from here on)
     __syncthreads();
     if (!s_good) return;
-  } else if (P.n_mh) {
+  } else if (P.n_mh && !ragged_roots_done) {
     __syncthreads();  // the item index space laid out in phase C is read by every wavefront
   }
   // ---- ragged root operators
-  {
-    const uint32_t um = P.n_mh ? ps.item_units() : 0u;
-    const uint32_t uo = ps.other_units(), un = ps.ngram_units();
-    for_units(&s_ctr[3], um + uo + un, [&](uint32_t u) {
-      if (FBX_SKIP(4u)) return;
-      if (u < uo) ps.other_unit(u);
-      else if (u < uo + um) ps.item_unit(u - uo);
-      else ps.ngram_unit(u - uo - um);
-    });
-  }
+  if (!ragged_roots_done) for_units(&s_ctr[3], ragged_root_units(), ragged_root_unit);
   FBX_MARK(10);
   // ---- the list crosses / concats, layer by layer
   for (uint32_t layer = 2, turn = 0; layer <= P.n_layers; ++layer) {
