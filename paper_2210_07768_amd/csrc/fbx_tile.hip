@@ -1456,7 +1456,9 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     }
   };
   // Launches that know a tile's bases early (from the scan over tiles, or by arrival): the ragged root
-  // operators share a hand-out with the first layer of single crosses, long units first.
+  // operators share a hand-out with the last layer of single crosses, long units first.  (The last
+  // layer: a cross computed along with a multi-valued hash's items reads a single sign of any earlier
+  // layer, which must be in place; nothing on the chip reads the last layer's single signs.)
   constexpr bool kEarlyBases = MODE == 1 || MODE == 3;
   if (kEarlyBases && MODE == 3 && P.n_ragged && wave == 0) place_by_arrival();
   auto ragged_root_units = [&]() -> uint32_t {
@@ -1484,7 +1486,7 @@ __device__ __forceinline__ void run_pass(const TileParams& P, const Sh& sh, cons
     if (tid == 0) s_ctr[4u + ((layer + 1u) & 1u)] = 0;  // the next layer's counter (idle since the barrier before this one)
     const uint32_t ux = kGen ? ps.units_of(TL_LAYER + 2u * (layer - 2u)) : ps.x11_units(layer);
     uint32_t ur = 0;
-    if (kEarlyBases && layer == 2u && P.n_ragged) {
+    if (kEarlyBases && layer == P.n_layers && P.n_ragged) {
       if (MODE == 3 && !s_good) return;  // the call falls back: leave the arrays alone
       ur = ragged_root_units();
       ragged_roots_done = true;
