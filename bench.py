@@ -422,7 +422,7 @@ def main():
         plan.set_option("placement", 1)
         for i in range(2):  # (compiles the kernel of that mode)
             plan.extract(*batches[(first_timed + i) % len(batches)])
-        a_ms, a_kernel, a_res = [], [], None
+        a_ms, a_kernel, a_res, a_fell = [], [], None, 0
         for i in range(args.steps):
             d_raw, d_off = batches[(first_timed + i) % len(batches)]
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -432,11 +432,13 @@ def main():
             torch.cuda.synchronize()
             a_ms.append(e0.elapsed_time(e1))
             a_kernel.append(plan.kernel_ms(101))
+            a_fell += 1 if "fell back" in a_res.note else 0
         k_ms = float(np.mean(a_kernel))
         out["arrival_order"] = {"ms_per_step_median_hip_events": statistics.median(a_ms), "tile_kernel_ms": round(k_ms, 4),
                                 "records_per_s": R / (statistics.median(a_ms) * 1e-3),
                                 "tile_kernel_frac_of_hbm_peak": alg_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                 "tile_launches": a_res.tile_launches, "arrival_tile_records": a_res.arrival_tile_records,
+                                "timed_calls_that_fell_back": a_fell,
                                 "note": "plan option placement=1; ragged arrays hold the tiles' shares in arrival order"}
         plan.set_option("placement", 0)
     if not args.no_cpu:

@@ -1,6 +1,7 @@
 // C ABI of libfbx: plan lifetime, workspace layout, and the launch sequence of
 // one extraction call.  See include/fbx.h for the contract of every entry point.
 #include <algorithm>
+#include <cmath>
 #include <atomic>
 #include <chrono>
 #include <cstdio>
@@ -638,7 +639,9 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
     for (uint32_t r = 0; r < h.n_ragged; ++r) {
       const unsigned __int128 scaled =
           (unsigned __int128)plan->learned_total[r] * n_records / plan->learned_records;
-      const unsigned __int128 cap = scaled + scaled / 64 + 256;
+      // (a sixty-fourth, and sixteen standard deviations of a count that size: operators that yield signs for
+      // few records, many at a time, vary far more between batches than their size suggests)
+      const unsigned __int128 cap = scaled + scaled / 64 + (unsigned __int128)(16.0 * std::sqrt((double)scaled)) + 256;
       plan->cap_host[r] = cap > (unsigned __int128)(1ull << 60) ? (1ull << 60) : (uint64_t)cap;
     }
   }
