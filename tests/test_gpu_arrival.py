@@ -92,7 +92,10 @@ def _arrival_calls(spec, raw, off, options, label, want_one_launch=True):
     (2, 900, {}),            # many ragged operators on tiles of four records: one launch in this order only
     (2, 900, {"compile": 1}),
     (4, 1500, {}), (3, 5000, {"compile": 1}),
-], ids=["config5", "config5_compiled", "config5_compiled_8_workgroups", "config2", "config2_compiled", "config4", "config3_compiled"])
+    (5, 6000, {"compile": 1, "tile_log2": 6, "lds_budget": 160 * 1024, "lane_ops": 2}),   # generated straight-line operators
+    (4, 1500, {"compile": 1}),
+], ids=["config5", "config5_compiled", "config5_compiled_8_workgroups", "config2", "config2_compiled", "config4", "config3_compiled",
+        "config5_generated_operators", "config4_compiled"])
 def test_workloads_in_arrival_order(cfg, n, options):
     w = W.get(cfg, n)
     raw, off = w.generate()
