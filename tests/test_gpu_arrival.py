@@ -13,6 +13,7 @@ from paper_2210_07768_amd import binding as B
 from paper_2210_07768_amd import workloads as W
 from helpers import FOLLOW_SPEC
 from gpu_harness import assert_same, expand, to_device
+from oracle_ranges import extract_parallel
 
 pytestmark = pytest.mark.gpu
 
@@ -62,9 +63,16 @@ def assert_same_in_arrival_order(res, want, n, label=""):
     assert res.n_malformed_numeric == want.n_malformed_numeric, label
 
 
+class _Want:
+    """The oracle's result over disjoint record ranges on all host cores, in the shape O.extract gives."""
+
+    def __init__(self, spec, raw, off):
+        self.slots, self.slot_ids, self.n_values_total, self.n_malformed_numeric = extract_parallel(spec, raw, off)
+
+
 def _arrival_calls(spec, raw, off, options, label, want_one_launch=True):
     n = len(off) - 1
-    want = O.extract(spec, raw, off)
+    want = O.extract(spec, raw, off) if n < 50_000 else _Want(spec, raw, off)
     plan = B.Plan(spec)
     plan.set_option("placement", 1)
     for key, v in options.items():
@@ -94,8 +102,11 @@ def _arrival_calls(spec, raw, off, options, label, want_one_launch=True):
     (4, 1500, {}), (3, 5000, {"compile": 1}),
     (5, 6000, {"compile": 1, "tile_log2": 6, "lds_budget": 160 * 1024, "lane_ops": 2}),   # generated straight-line operators
     (4, 1500, {"compile": 1}),
+    (5, 1_000_000, {"compile": 1}),   # far more tiles than workgroups that run at the same time
+    (2, 120_000, {"compile": 1}),
 ], ids=["config5", "config5_compiled", "config5_compiled_8_workgroups", "config2", "config2_compiled", "config4", "config3_compiled",
-        "config5_generated_operators", "config4_compiled"])
+        "config5_generated_operators", "config4_compiled",
+        "config5_a_million_records", "config2_30000_tiles"])
 def test_workloads_in_arrival_order(cfg, n, options):
     w = W.get(cfg, n)
     raw, off = w.generate()
