@@ -264,6 +264,14 @@ class Plan:
         self._check(lib().fbx_plan_kernel_ms(self._h, which, ctypes.byref(ms)))
         return ms.value
 
+    def kernel_ms_all(self, which_ids) -> Dict[int, float]:
+        """fbx_plan_kernel_ms for every timer of the list that the last call used (no exception for the others)."""
+        out, ms, fn = {}, ctypes.c_float(), lib().fbx_plan_kernel_ms
+        for which in which_ids:
+            if fn(self._h, which, ctypes.byref(ms)) == 0:
+                out[which] = ms.value
+        return out
+
     def extract_unordered(self, slot_id: int, d_raw, d_rec_off, pool, state, thread_offsets, lengths, reset: bool = True,
                           stream: Optional[int] = None) -> UnorderedResult:
         """fbx_extract_unordered: pool (uint8), state (4 x int64), thread_offsets (int64, one per record) and
