@@ -144,6 +144,8 @@ fbx_status fbx_plan_set_workspace(fbx_plan* plan, void* d_workspace, uint64_t by
  * plan counts in a launch of its own; later calls size the arrays from the call
  * before (plus a margin), count and write in one launch, and repeat themselves
  * with the counting launch if a batch does not fit (out->tile_launches tells).
+ * After a batch in which some tile of records was too long for on-chip staging
+ * the next 1, 2, 4 ... 64 calls count first without trying (fbx_last_error says so).
  * On an error the contents of the workspace are unspecified.
  * Errors: FBX_E_ARG, FBX_E_NOMEM, FBX_E_INPUT, FBX_E_HIP.
  */

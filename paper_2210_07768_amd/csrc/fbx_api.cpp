@@ -54,6 +54,7 @@ struct fbx_plan {
   uint32_t grid_limit = 0;
   uint32_t spin_limit = 1u << 22;   // polls a tile of the one-launch sequence waits for an earlier tile's count
   int one_launch = 1;             // size ragged arrays from the last call and skip the counting launch
+  uint32_t passes_skip = 0, passes_backoff = 0;  // calls that do not try the one-launch sequence after a tile did not fit its LDS section; how many next time
   int placement = 0;              // one-launch sequence: 0 tiles placed in record order (look-back), 1 in the order they arrive (one atomic add each)
   int compile = 0;                // compile the tile kernel for this plan at run time (Section 4's meta-kernel)
   uint32_t tile_threads = 512;    // lanes of a workgroup of the kernels compiled for the plan
@@ -631,7 +632,11 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
   // (every tile reads 512 bytes of placement words per ragged operator that is placed by look-back,
   // which those whose counts follow from another operator's are not: only worth it when that is
   // little next to the tile's own text)
-  bool one = g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records &&
+  // (a batch with a tile that did not fit the LDS section is likely to be followed by more of its kind: the
+  // sequence is then left untried for 1, 2, 4 ... up to 64 calls, so that such batches do not pay for two attempts each)
+  const bool resting = plan->passes_skip > 0;
+  if (resting) --plan->passes_skip;
+  bool one = !resting && g.tile_engine && plan->one_launch && plan->learned && h.n_ragged && n_records && plan->learned_records &&
              ws_bytes > plan->margin_failed_ws &&
              (plan->placement || uint64_t(h.n_ragged - h.n_alias) * 512u * 2u <= (raw_len / n_records) << g.tp.log2T);
   if (one) {
@@ -657,8 +662,13 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
     if (one && (c->err & (CE_SPEC | CE_NOMEM | CE_STALL))) {
       // Every kernel has exited normally and the tiles that could not be placed wrote nothing: the
       // exact sequence (counting launch, scan, writing launch) can still answer the call.
+      if (c->err & CE_PASSES) {
+        plan->passes_backoff = plan->passes_backoff ? std::min(64u, plan->passes_backoff * 2u) : 1u;
+        plan->passes_skip = plan->passes_backoff;
+      }
       fell_back = (c->err & CE_STALL) ? "one-launch attempt fell back to the counting launch: a bounded wait for an earlier tile ran out"
-                  : (c->err & CE_SPEC) ? "one-launch attempt fell back to the counting launch: a tile larger than the LDS section, or more signs than the arrays were sized for"
+                  : (c->err & CE_PASSES) ? "one-launch attempt fell back to the counting launch: a tile larger than the LDS section"
+                  : (c->err & CE_SPEC) ? "one-launch attempt fell back to the counting launch: more signs than the arrays were sized for"
                                        : "one-launch attempt fell back to the counting launch: the margin on the arrays did not fit the workspace";
       if (!(c->err & (CE_SPEC | CE_STALL))) plan->margin_failed_ws = ws_bytes;
       one = false;  // fall back to counting first
@@ -667,6 +677,8 @@ fbx_status extract_impl(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len, 
     break;
   }
   plan->last_mode = one ? 2 : 1;
+  if (one) plan->passes_backoff = 0;  // (the sequence went through: the next tile that does not fit starts over at one call)
+  if (resting && !fell_back) fell_back = "one-launch sequence not tried: a recent batch had a tile larger than the LDS section";
 #undef FBX_LAUNCH
 
   const OpDyn* y = reinterpret_cast<const OpDyn*>(plan->readback.data() + plan->off_dyn);

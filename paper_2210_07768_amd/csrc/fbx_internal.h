@@ -105,7 +105,8 @@ static_assert(sizeof(Ctrl) == 64, "Ctrl must stay 64 bytes");
 enum CtrlErr : uint32_t {
   CE_OFFSETS = 1u, CE_NOMEM = 2u, CE_OVERFLOW = 4u, CE_TILE = 8u,
   CE_SPEC = 16u,   // one-launch mode cannot place this batch (capacity or tile size): run the counting launch
-  CE_STALL = 32u   // a bounded wait in the one-launch mode ran out
+  CE_STALL = 32u,  // a bounded wait in the one-launch mode ran out
+  CE_PASSES = 64u  // (with CE_SPEC) the reason was a tile whose text does not fit the LDS section
 };
 
 struct HostOp {

@@ -1736,7 +1736,7 @@ __device__ __forceinline__ void tile_body(const TileParams& P) {
       // (or holds a record that is read in place) sends the call back to the counting launch
       const uint32_t d0 = (uint32_t)((ok_lo + off[0]) & 15u);
       if (off[nrec] - off[0] + d0 > (uint64_t)P.raw_cap) {
-        if (tid == 0) atomicOr(&P.ctrl->err, (uint32_t)CE_SPEC);
+        if (tid == 0) atomicOr(&P.ctrl->err, (uint32_t)(CE_SPEC | CE_PASSES));
         if (MODE == 2) lb_abort_tile(P, tile);
         r0 = nrec;
       }

@@ -90,7 +90,7 @@ def _arrival_calls(spec, raw, off, options, label, want_one_launch=True, may_fal
             # (no ragged operator in the plan: one launch, nothing to place, record order)
             assert res.tile_launches == 1 and res.arrival_tile_records == 0, res.note
             assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, f"{label} call {call}")
-        elif may_fall_back and res.tile_launches == 2 and "fell back" in res.note:
+        elif may_fall_back and res.tile_launches == 2 and ("fell back" in res.note or "not tried" in res.note):
             # (records of very different lengths: a tile's text did not fit the LDS section, the counting sequence answered)
             assert res.arrival_tile_records == 0
             assert_same({s: expand(res.slots[s], n) for s in res.slot_ids}, res, want, f"{label} call {call}")

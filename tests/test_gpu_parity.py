@@ -767,3 +767,42 @@ def test_algorithm1_arena_primitive():
         B.arena_alloc(d_head, d_sizes[:threads], d_off[:threads], threads)
         torch.cuda.synchronize()
         assert int(d_off[0].cpu()) == 4096
+
+
+def test_batches_with_a_tile_that_does_not_fit_stop_trying_the_one_launch_sequence():
+    """One long record among short ones: its tile's text does not fit the LDS section, the one-launch attempt falls
+    back, and the next call does not try again (then one more attempt, then two calls of rest, ...).  A batch
+    without such a record takes one launch again once the rest is over.  Every call's result is the oracle's."""
+    from gpu_harness import expand
+    spec = ("fbx 1\nfields 2\n"
+            "op a hash slot=0 seed=1 emit=1 field=0 multi=1\n"
+            "op b hash slot=1 seed=2 emit=1 field=1 multi=0\n"
+            "op c cross slot=2 seed=3 emit=1 a=b b=a\n")
+    short = [b"xxxxxxxx,yyyyyyyy,zzzzzzzz\tqqqqqqqqqqqq\n"] * 3000   # (long enough for the one-launch sequence to be worth trying)
+    with_long = list(short)
+    with_long[1234] = b",".join([b"item"] * 30000) + b"\tq\n"   # 150 KB: more than any LDS section
+    cat = lambda recs: (np.frombuffer(b"".join(recs), np.uint8), np.cumsum([0] + [len(r) for r in recs]).astype(np.uint64))
+    want_long, want_short = O.extract(spec, *cat(with_long)), O.extract(spec, *cat(short))
+    plan = B.Plan(spec)
+    d_long, d_short = to_device(*cat(with_long)), to_device(*cat(short))
+    res, ws = B.extract_with_retry(plan, *d_long, slack=1.2)
+    seen = []
+    for call in range(6):
+        res = plan.extract(*d_long)
+        assert res.tile_launches == 2
+        seen.append("fell back" if "fell back" in res.note else ("rest" if "not tried" in res.note else res.note))
+        assert_same({s: expand(res.slots[s], 3000) for s in res.slot_ids}, res, want_long, f"call {call}")
+    assert seen == ["fell back", "rest", "fell back", "rest", "rest", "fell back"], seen
+    for call in range(4):     # (four calls of rest are due)
+        res = plan.extract(*d_short)
+        assert res.tile_launches == 2 and "not tried" in res.note
+    res = plan.extract(*d_short)
+    assert res.tile_launches == 1, res.note
+    assert_same({s: expand(res.slots[s], 3000) for s in res.slot_ids}, res, want_short, "short batch, one launch")
+    res = plan.extract(*d_long)
+    assert "fell back" in res.note   # (after a call that went through, the rests start over at one call)
+    res = plan.extract(*d_long)
+    assert "not tried" in res.note
+    res = plan.extract(*d_long)
+    assert "fell back" in res.note
+    plan.close()
