@@ -162,7 +162,9 @@ fbx_status fbx_extract(fbx_plan* plan, const uint8_t* d_raw, uint64_t raw_len,
  *     fbx_static_scratch_bytes() = 64 MiB that is part of the library's device code: every GPU
  *     the library runs on holds one copy until the process ends;
  *   - the operators' arrays (the results) go to the caller's buffer:
- *       d_out     : DEVICE, 256-byte aligned, out_bytes bytes; out->slots point into it.
+ *       d_out     : DEVICE, 256-byte aligned, out_bytes bytes; out->slots point into it
+ *                   (all but tile_ends of a result in arrival order, which points into the
+ *                   library's array and holds until the next call on this GPU).
  * No fbx_plan_set_workspace is needed.  The call allocates and frees no device memory and
  * compiles nothing: plan options "compile" and "profile" are ignored here.
  * Limit: a batch whose tables exceed the array (they grow with tiles x ragged operators; the
